@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdaCons aggregation hot path on one MI355X.
+
+A step is one whole aggregation (stage A1 Gram, A2 coefficients, A3 weighted sum) through the
+C ABI over one N x d gradient matrix already resident in HBM.  The default workload is the
+graded one: N = 8 workers, d = 25,557,032 fp32 (ResNet-50-sized), synthetic gradients from the
+seeded recipe in workloads/ (two consecutive steps of the stream, used alternately).
+
+Prints ONE JSON line.  `value` is the effective bandwidth: algorithmic bytes of one aggregation
+(G read twice + fp32 out written once) divided by the mean time of a step.  Excluded from the
+timed region: input generation, host/device copies, coefficient readback.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads
+    import paper_2411_03742_amd as ada
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = workloads.CONFIGS[args.workload]
+
+    # two consecutive steps of the seeded stream, kept resident and used alternately
+    bufs = []
+    for G in workloads.stream(w.scaled(w.d, 2), dev):
+        bufs.append(G.clone())
+    out = torch.empty(w.d, dtype=torch.float32, device=dev)
+    agg = ada.AdaCons(w.N, w.d, beta=0.99)
+    keys = {"gram_blocks_per_cu": ada.ADACONS_TUNE_GRAM_BLOCKS_PER_CU,
+            "wsum_blocks_per_cu": ada.ADACONS_TUNE_WSUM_BLOCKS_PER_CU,
+            "fuse_coeffs": ada.ADACONS_TUNE_FUSE_COEFFS,
+            "reverse_second_pass": ada.ADACONS_TUNE_REVERSE_SECOND_PASS}
+    tuned = {}
+    for kv in args.tune:
+        k, v = kv.split("=")
+        agg.tune(keys[k], int(v))
+        tuned[k] = int(v)
+
+    stream = torch.cuda.current_stream()
+    for i in range(args.warmup):
+        agg.aggregate(bufs[i % 2], out=out, stream=stream)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` aggregations, nothing else on the stream ----------
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(args.steps):
+        agg.aggregate(bufs[i % 2], out=out, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = max(wall_ms, e0.elapsed_time(e1)) / args.steps
+    info = agg.coeffs()
+    assert abs(info["gamma"].sum() - 1.0) < 1e-6 and info["numeric_flags"] == 0
+
+    # ---- same loop again with the library's HIP events around each stage (same stream) ----
+    nprof = min(args.steps, 1000)
+    agg.profile_begin(nprof)
+    for i in range(nprof):
+        agg.aggregate(bufs[i % 2], out=out, stream=stream)
+    prof = agg.profile_end(stream=stream)
+
+    floor = w.floor_bytes
+    gbps = floor / (ms_per_step * 1e-3) / 1e9
+    eb = w.elem_bytes
+    stages = {
+        "gram (A1+A2)": (w.N * w.d * eb, prof["gram_ms"]),
+        "wsum (A3)": (w.N * w.d * eb + 4 * w.d, prof["wsum_ms"]),
+    }
+    dom = max(stages, key=lambda k: stages[k][1])
+    dom_bytes, dom_ms = stages[dom]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+        "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 5),
+        "stages_ms": {k: round(v[1], 5) for k, v in stages.items()},
+        "stages_GBps": {k: round(v[0] / (v[1] * 1e-3) / 1e9, 1) for k, v in stages.items()},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, bufs[0])
+
+    line = {
+        "metric": "aggregation effective HBM bandwidth (N=%d, d=%d, %s): algorithmic bytes per aggregation / time"
+                  % (w.N, w.d, w.dtype),
+        "value": round(gbps, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: N=%d workers, d=%d %s gradients, beta=0.99, momentum+normalisation"
+                               % (w.name, w.N, w.d, w.dtype), "tuning": tuned},
+        "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "aggregations_per_s": round(1e3 / ms_per_step, 1),
+        "gradients_per_s": round(w.N * 1e3 / ms_per_step, 1),
+        "algorithmic_bytes_per_step": floor,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    agg.close()
+    return 0
+
+
+def cpu_baseline(w, G) -> dict:
+    """The float64 oracle, as it stands, on this machine's host cores: whole aggregations of the same
+    workload (Gram, coefficients, weighted sum), repeated for a bounded time."""
+    import numpy as np
+    import workloads
+    from oracle import adacons_oracle as o
+
+    Gh = workloads.to_oracle_input(G)
+    times = []
+    budget_s, t_start = 20.0, time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_start < budget_s and len(times) < 10):
+        st = o.OracleState(w.N, beta=0.99)
+        t0 = time.perf_counter()
+        o.aggregate(Gh, st, want_out=True)
+        times.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_start > 3 * budget_s:
+            break
+    med = float(np.median(times))
+    return {"value": round(w.floor_bytes / med / 1e9, 3), "unit": "GB/s", "cores": o.num_threads(),
+            "kind": "oracle", "seconds_per_aggregation": round(med, 4),
+            "aggregations_per_s": round(1.0 / med, 4),
+            "sample": "%d whole aggregations of the full %s input (one step of the stream), median" % (len(times), w.name)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

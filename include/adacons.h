@@ -1,0 +1,187 @@
+/*
+ * adacons.h -- C ABI of the MI355X (gfx950) AdaCons gradient-aggregation library.
+ *
+ * AdaCons (arXiv 2411.03742) replaces the plain average of N workers' gradients
+ * by a weighted sum  psi = sum_i gamma_i g_i  (Eq. 4, Eq. 12) whose weights come
+ * from a first-order step on the N-dimensional subspace objective (Eq. 5-7),
+ * smoothed by a momentum on the *sorted* coefficients (Eq. 11) and normalised
+ * to sum to one (Sec. 3.4, Eq. 12-13).
+ *
+ * This library is the single-GPU hot path of that aggregator.  The N gradients
+ * are the rows of one N x d matrix G resident in device memory; one call
+ * computes, in three stream-ordered stages,
+ *
+ *   A1  K = G G^T                      (Eq. 7 third line: every <g_i, g_j>; its diagonal
+ *                                       gives ||g_i||^2, its row sums N <g_i, gbar>)
+ *   A2  a_i = <g_i, gbar>/||g_i||      (Eq. 7)  ->  sorted EMA (Eq. 11)  ->  c_i = a~_i/||g_i||
+ *       (second normalisation of the column-normalised subspace matrix, Eq. 8)
+ *       ->  gamma = c / sum c          (Eq. 12-13)
+ *   A3  out = sum_i gamma_i g_i        (Eq. 12)
+ *
+ * Conventions common to every call
+ *   - No torch or C++ types cross this boundary: plain pointers and sizes.
+ *   - "device pointer" = memory of the current HIP device (hipMalloc or a
+ *     framework's allocator); "host pointer" = ordinary host memory.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   - Every function returns an adacons_status; nothing throws or aborts.
+ *     adacons_last_error() gives a thread-local text for the last failure.
+ *   - Numeric degeneracy (a zero gradient, NaN/Inf, weights that cancel) is not
+ *     an error: it raises bits in a device-side status word that
+ *     adacons_coeffs() returns (ADACONS_NUM_*).
+ *   - One state is one coefficient stream: calls that use the same state must be
+ *     ordered on one stream (or otherwise serialised by the caller).
+ */
+#ifndef ADACONS_H
+#define ADACONS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADACONS_N_MAX 64 /* largest supported worker count */
+
+typedef struct adacons_state adacons_state; /* opaque, library-owned */
+
+typedef enum {
+    ADACONS_F32 = 0, /* G holds IEEE binary32 */
+    ADACONS_BF16 = 1 /* G holds bfloat16 (upper half of binary32); accumulation and out stay fp32 */
+} adacons_dtype;
+
+typedef enum {
+    ADACONS_OK = 0,
+    ADACONS_EINVAL = 1,       /* null pointer, bad size, N mismatch, beta outside [0,1), aliasing */
+    ADACONS_EUNSUPPORTED = 2, /* N > ADACONS_N_MAX, unknown dtype, wrong GPU architecture */
+    ADACONS_EALIGN = 3,       /* G or out not aligned to its element size */
+    ADACONS_EHIP = 4,         /* a HIP runtime call failed (see adacons_last_error) */
+    ADACONS_ENOMEM = 5        /* device or host allocation failed */
+} adacons_status;
+
+/* Variant flags (the ablation columns of Table 2).  Default = both. */
+enum {
+    ADACONS_FLAG_MOMENTUM = 1u,  /* sorted EMA of Eq. 11; off: a~ = a */
+    ADACONS_FLAG_NORMALIZE = 2u, /* sum-to-one weights of Eq. 12-13; off: gamma_i = c_i (lambda = 1, Eq. 8) */
+    ADACONS_FLAG_DEFAULT = 3u
+};
+
+/* Bits of the numeric status word returned by adacons_coeffs(). */
+enum {
+    ADACONS_NUM_ZERO_NORM = 1u,       /* some ||g_i|| = 0: that worker gets a_i = c_i = 0 */
+    ADACONS_NUM_NONFINITE = 2u,       /* NaN/Inf reached K: EMA state left untouched */
+    ADACONS_NUM_UNIFORM_FALLBACK = 4u /* gamma_i = 1/N used (non-finite, or |sum c| <= 1e-12 sum|c|) */
+};
+
+/*
+ * Create the carried state of one coefficient stream: the EMA vector m of
+ * Eq. 11 (N doubles kept in sorted order, zero-initialised), the call counter,
+ * the coefficient buffers and the partial-sum workspace of stage A1, all on the
+ * current HIP device.  This is the only call that allocates device memory.
+ *   st       out: receives the handle (host pointer to a host pointer)
+ *   N        number of workers, 1 <= N <= ADACONS_N_MAX
+ *   d_max    largest gradient length later calls may pass, >= 1
+ *   beta     EMA factor of Eq. 11, 0 <= beta < 1 (the paper uses 0.99, Table 2)
+ *   flags    ADACONS_FLAG_* bits
+ * Errors: EINVAL, EUNSUPPORTED, ENOMEM, EHIP.  Synchronises `hip_stream` once.
+ */
+adacons_status adacons_init_state(adacons_state **st, int N, int64_t d_max, double beta,
+                                  unsigned flags, void *hip_stream);
+
+/* Free everything the state owns.  The caller must have drained all work using it. */
+adacons_status adacons_destroy_state(adacons_state *st);
+
+/* m := 0, call counter := 0 (asynchronous on the stream). */
+adacons_status adacons_reset_state(adacons_state *st, void *hip_stream);
+
+/*
+ * One aggregation psi_t({g_i}) (Eq. 4 with Eq. 12): stages A1, A2, A3 enqueued on
+ * `hip_stream`.  Asynchronous; allocates nothing; never synchronises.
+ *   G      device pointer, N x d row-major contiguous (row i = g_i, row stride d elements),
+ *          element type `dtype`; read twice; must stay valid until the stream reaches the
+ *          end of this call's work; must be aligned to its element size.  The 128-bit fast
+ *          path is taken when G is 16-byte aligned and d*sizeof(elem) % 16 == 0, otherwise a
+ *          slower element-wise path runs (same results).
+ *   N, d   must satisfy N == state's N, 1 <= d <= d_max
+ *   out    device pointer to d floats (fp32 for both dtypes), caller-owned, written once,
+ *          4-byte aligned, must not overlap G
+ * State mutated: m (Eq. 11), call counter, gamma / raw / smoothed coefficient buffers, K,
+ * numeric status word.
+ * Errors: EINVAL, EUNSUPPORTED, EALIGN, EHIP (launch failure).
+ */
+adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype dtype,
+                                 adacons_state *st, float *out, void *hip_stream);
+
+/*
+ * Read back the coefficients of the most recent adacons_aggregate() on this state
+ * (the three stages of Fig. 7: first-order, after momentum, after normalisation).
+ * Copies on `hip_stream` and waits for it: the only synchronising call of the hot API.
+ *   gamma_host     host pointer, N doubles: the weights gamma_i actually applied
+ *   raw_host       host pointer, N doubles, or NULL: a_i of Eq. 7
+ *   smoothed_host  host pointer, N doubles, or NULL: a~_i after Eq. 11
+ *   numeric_flags  host pointer or NULL: ADACONS_NUM_* bits of that call
+ */
+adacons_status adacons_coeffs(const adacons_state *st, double *gamma_host, double *raw_host,
+                              double *smoothed_host, uint32_t *numeric_flags, void *hip_stream);
+
+/*
+ * Stage A1 alone: K = G G^T (Eq. 7 third line / the double sum of Eq. 8) into the state's
+ * K buffer, without touching the coefficient state.  Same argument rules as
+ * adacons_aggregate.  Asynchronous.
+ */
+adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype,
+                            adacons_state *st, void *hip_stream);
+
+/* Copy the state's K (N x N doubles, row-major, symmetric) to the host; synchronises the stream. */
+adacons_status adacons_read_gram(const adacons_state *st, double *K_host, void *hip_stream);
+
+/*
+ * Stage A3 alone: out = sum_i gamma_i g_i (Eq. 12) with caller-supplied weights.
+ *   gamma_host  host pointer, N doubles (rounded to fp32 for the kernel); copied to the
+ *               state's weight buffer on the stream, overwriting the last aggregate's weights
+ * Other arguments as in adacons_aggregate.  Synchronises the stream once (host weights).
+ */
+adacons_status adacons_weighted_sum(const void *G, int N, int64_t d, adacons_dtype dtype,
+                                    const double *gamma_host, adacons_state *st, float *out,
+                                    void *hip_stream);
+
+/*
+ * Checkpoint / resume of the carried state of Eq. 11: m (N doubles, sorted order) and the call
+ * counter.  Both synchronise the stream.  Import requires the same N.
+ */
+adacons_status adacons_state_export(const adacons_state *st, double *m_host, int64_t *step,
+                                    void *hip_stream);
+adacons_status adacons_state_import(adacons_state *st, const double *m_host, int64_t step,
+                                    void *hip_stream);
+
+/*
+ * Tuning knobs (launch shape only; results stay within the documented tolerances, and are
+ * bit-identical between runs for a fixed setting).  value < 0 restores the default.
+ */
+typedef enum {
+    ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0,  /* persistent workgroups per CU in stage A1 */
+    ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1,  /* persistent workgroups per CU in stage A3 */
+    ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2; 0: A2 is its own launch */
+    ADACONS_TUNE_REVERSE_SECOND_PASS = 3, /* 1: A3 walks the columns backwards (cache reuse) */
+    ADACONS_TUNE_COUNT_
+} adacons_tune_key;
+adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);
+
+/*
+ * Per-kernel timing with HIP events on the caller's stream, for roofline reporting.
+ * adacons_profile_begin() creates event pairs for up to max_calls aggregations (this
+ * allocates; call it outside any timed region); later adacons_aggregate() calls record an
+ * event before stage A1, between A2 and A3, and after A3.  adacons_profile_end() waits for the
+ * stream, returns the mean duration in milliseconds of A1+A2 (gram_ms) and of A3 (wsum_ms) over
+ * the recorded calls and their count, and stops recording.  Any output pointer may be NULL.
+ */
+adacons_status adacons_profile_begin(adacons_state *st, int max_calls);
+adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *wsum_ms, int *calls,
+                                   void *hip_stream);
+
+const char *adacons_status_string(adacons_status s);
+const char *adacons_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADACONS_H */

@@ -1,0 +1,72 @@
+// Internal declarations shared by the HIP translation units of libadacons.
+// Nothing here is visible across the C ABI (include/adacons.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adacons.h"
+
+namespace adacons {
+
+constexpr int kNMax = ADACONS_N_MAX;
+constexpr int kBlock = 256;  // threads per workgroup (4 wavefronts of 64) in every kernel
+constexpr int kWave = 64;
+
+// Device-resident part of a coefficient stream (one per adacons_state).
+struct DevState {
+    double m[kNMax];         // EMA of the order statistics, sorted order (Eq. 11)
+    double gamma[kNMax];     // weights applied by the last aggregation (Eq. 12-13)
+    double a_raw[kNMax];     // first-order coefficients a_i (Eq. 7)
+    double a_smooth[kNMax];  // after the sorted EMA, redistributed to the workers (Eq. 11)
+    float gamma32[kNMax];    // gamma rounded for the weighted-sum kernel
+    unsigned long long step; // number of coefficient updates so far
+    unsigned numeric_flags;  // ADACONS_NUM_* of the last update
+    unsigned blocks_done;    // ticket counter of the Gram kernel's last-workgroup tail
+};
+static_assert(sizeof(DevState) % sizeof(unsigned) == 0, "DevState is cleared word by word");
+
+struct CoeffParams {
+    int N;
+    double beta;
+    unsigned flags;
+};
+
+// What a Gram kernel does once its own partial row is written.
+enum GramMode {
+    kGramPartialsOnly = 0,  // a later launch reduces the partial rows
+    kGramFinishK = 1,       // last workgroup reduces the partial rows into K
+    kGramFinishCoeffs = 2   // ... and also runs the coefficient update (stage A2)
+};
+
+struct GramTail {
+    double *partials;  // [rows][N(N+1)/2], one row per workgroup
+    double *K;         // [N][N]
+    DevState *ds;
+    CoeffParams cp;
+    int mode;
+};
+
+__host__ __device__ inline int num_pairs(int N) { return N * (N + 1) / 2; }
+// Position of (i, j), i <= j, in the row-major packed upper triangle.
+__host__ __device__ inline int pair_index(int i, int j, int N) { return i * N - (i * (i - 1)) / 2 + (j - i); }
+
+struct LaunchShape {
+    int num_cu;
+    int blocks_per_cu;  // <= 0: let the launcher decide
+    int max_rows;       // capacity of the partials workspace in rows
+};
+
+// gram.hip
+hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
+                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream);
+hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStream_t stream);
+int gram_rows_needed(int N, int num_cu);
+hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t stream);  // K may be NULL
+
+// wsum.hip
+hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
+                       const LaunchShape &shape, const float *gamma, float *out, bool reverse,
+                       hipStream_t stream);
+
+}  // namespace adacons

@@ -1,0 +1,329 @@
+// C ABI of libadacons (declared in include/adacons.h): argument checks, state ownership,
+// stream-ordered launches of the three stages.  No kernel code here.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "adacons_internal.h"
+
+using namespace adacons;
+
+struct adacons_state {
+    int N;
+    int64_t d_max;
+    double beta;
+    unsigned flags;
+    int device;
+    int num_cu;
+    DevState *ds;      // device
+    double *partials;  // device, [max_rows][N(N+1)/2]
+    double *K;         // device, [N][N]
+    int max_rows;
+    int tune[ADACONS_TUNE_COUNT_];
+    // per-kernel timing (adacons_profile_begin/end)
+    std::vector<hipEvent_t> events;  // 3 per call: before A1, after A1+A2, after A3
+    int prof_capacity;
+    int prof_calls;
+};
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+adacons_status fail(adacons_status s, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+adacons_status hip_fail(hipError_t e, const char *what) {
+    return fail(ADACONS_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(call)                                    \
+    do {                                                 \
+        hipError_t e_ = (call);                          \
+        if (e_ != hipSuccess) return hip_fail(e_, #call); \
+    } while (0)
+
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* occupancy */, 0 /* occupancy */, 1, 1};
+
+size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
+
+// Checks shared by the three compute entry points.  out may be NULL (stage A1 alone).
+adacons_status check_call(const void *G, int N, int64_t d, adacons_dtype dtype, const adacons_state *st,
+                          const float *out, bool need_out, bool *vec_ok) {
+    if (!st) return fail(ADACONS_EINVAL, "state is NULL");
+    if (!G) return fail(ADACONS_EINVAL, "G is NULL");
+    if (need_out && !out) return fail(ADACONS_EINVAL, "out is NULL");
+    if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return fail(ADACONS_EUNSUPPORTED, "unknown dtype %d", (int)dtype);
+    if (N != st->N) return fail(ADACONS_EINVAL, "N=%d does not match the state's N=%d", N, st->N);
+    if (d < 1 || d > st->d_max)
+        return fail(ADACONS_EINVAL, "d=%lld outside [1, d_max=%lld]", (long long)d, (long long)st->d_max);
+    const size_t es = elem_size(dtype);
+    const uintptr_t g0 = reinterpret_cast<uintptr_t>(G);
+    if (g0 % es) return fail(ADACONS_EALIGN, "G not aligned to its element size");
+    bool ok = (g0 % 16 == 0) && ((uint64_t)d * es % 16 == 0);
+    if (need_out) {
+        const uintptr_t o0 = reinterpret_cast<uintptr_t>(out);
+        if (o0 % 4) return fail(ADACONS_EALIGN, "out not 4-byte aligned");
+        const uintptr_t g1 = g0 + (uint64_t)N * (uint64_t)d * es, o1 = o0 + (uint64_t)d * 4;
+        if (o0 < g1 && g0 < o1) return fail(ADACONS_EINVAL, "out overlaps G");
+        ok = ok && (o0 % 16 == 0);
+    }
+    *vec_ok = ok;
+    return ADACONS_OK;
+}
+
+LaunchShape shape_of(const adacons_state *st, adacons_tune_key key) {
+    LaunchShape s;
+    s.num_cu = st->num_cu;
+    s.blocks_per_cu = st->tune[key];
+    s.max_rows = st->max_rows;
+    return s;
+}
+
+GramTail tail_of(adacons_state *st, int mode) {
+    GramTail t;
+    t.partials = st->partials;
+    t.K = st->K;
+    t.ds = st->ds;
+    t.cp.N = st->N;
+    t.cp.beta = st->beta;
+    t.cp.flags = st->flags;
+    t.mode = mode;
+    return t;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *adacons_status_string(adacons_status s) {
+    switch (s) {
+        case ADACONS_OK: return "ok";
+        case ADACONS_EINVAL: return "invalid argument";
+        case ADACONS_EUNSUPPORTED: return "unsupported";
+        case ADACONS_EALIGN: return "misaligned pointer";
+        case ADACONS_EHIP: return "HIP runtime error";
+        case ADACONS_ENOMEM: return "out of memory";
+    }
+    return "unknown status";
+}
+
+const char *adacons_last_error(void) { return g_err; }
+
+adacons_status adacons_init_state(adacons_state **out_st, int N, int64_t d_max, double beta, unsigned flags,
+                                  void *hip_stream) {
+    if (!out_st) return fail(ADACONS_EINVAL, "st is NULL");
+    *out_st = nullptr;
+    if (N < 1) return fail(ADACONS_EINVAL, "N=%d < 1", N);
+    if (N > ADACONS_N_MAX) return fail(ADACONS_EUNSUPPORTED, "N=%d > ADACONS_N_MAX=%d", N, ADACONS_N_MAX);
+    if (d_max < 1) return fail(ADACONS_EINVAL, "d_max < 1");
+    if (!(beta >= 0.0 && beta < 1.0)) return fail(ADACONS_EINVAL, "beta=%g outside [0, 1)", beta);
+    if (flags & ~ADACONS_FLAG_DEFAULT) return fail(ADACONS_EINVAL, "unknown flag bits 0x%x", flags);
+
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(ADACONS_EUNSUPPORTED, "built for gfx950 only, device is %s", prop.gcnArchName);
+
+    adacons_state *st = new (std::nothrow) adacons_state();
+    if (!st) return fail(ADACONS_ENOMEM, "host allocation failed");
+    st->N = N;
+    st->d_max = d_max;
+    st->beta = beta;
+    st->flags = flags;
+    st->device = dev;
+    st->num_cu = prop.multiProcessorCount;
+    st->ds = nullptr;
+    st->partials = nullptr;
+    st->K = nullptr;
+    st->max_rows = gram_rows_needed(N, st->num_cu);
+    for (int k = 0; k < ADACONS_TUNE_COUNT_; ++k) st->tune[k] = kTuneDefault[k];
+    st->prof_capacity = 0;
+    st->prof_calls = 0;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&st->ds), sizeof(DevState));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->partials), (size_t)st->max_rows * num_pairs(N) * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->K), (size_t)N * N * sizeof(double));
+    if (e == hipSuccess) e = launch_clear_state(st->ds, st->K, N * N, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        adacons_status rc = (e == hipErrorOutOfMemory) ? fail(ADACONS_ENOMEM, "device allocation failed")
+                                                       : hip_fail(e, "adacons_init_state");
+        adacons_destroy_state(st);
+        return rc;
+    }
+    *out_st = st;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_destroy_state(adacons_state *st) {
+    if (!st) return ADACONS_OK;
+    for (hipEvent_t ev : st->events) (void)hipEventDestroy(ev);
+    if (st->ds) (void)hipFree(st->ds);
+    if (st->partials) (void)hipFree(st->partials);
+    if (st->K) (void)hipFree(st->K);
+    delete st;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_reset_state(adacons_state *st, void *hip_stream) {
+    if (!st) return fail(ADACONS_EINVAL, "state is NULL");
+    HIP_TRY(launch_clear_state(st->ds, nullptr, 0, static_cast<hipStream_t>(hip_stream)));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype dtype, adacons_state *st,
+                                 float *out, void *hip_stream) {
+    bool vec_ok = false;
+    adacons_status rc = check_call(G, N, d, dtype, st, out, true, &vec_ok);
+    if (rc != ADACONS_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const bool prof = st->prof_capacity > 0 && st->prof_calls < st->prof_capacity;
+    hipEvent_t *ev = prof ? &st->events[(size_t)st->prof_calls * 3] : nullptr;
+
+    if (prof) HIP_TRY(hipEventRecord(ev[0], s));
+    HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
+                        tail_of(st, kGramFinishCoeffs), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s));
+    if (prof) HIP_TRY(hipEventRecord(ev[1], s));
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out,
+                        st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s));
+    if (prof) {
+        HIP_TRY(hipEventRecord(ev[2], s));
+        st->prof_calls += 1;
+    }
+    return ADACONS_OK;
+}
+
+adacons_status adacons_coeffs(const adacons_state *st, double *gamma_host, double *raw_host, double *smoothed_host,
+                              uint32_t *numeric_flags, void *hip_stream) {
+    if (!st) return fail(ADACONS_EINVAL, "state is NULL");
+    if (!gamma_host) return fail(ADACONS_EINVAL, "gamma_host is NULL");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const size_t nb = (size_t)st->N * sizeof(double);
+    HIP_TRY(hipMemcpyAsync(gamma_host, st->ds->gamma, nb, hipMemcpyDeviceToHost, s));
+    if (raw_host) HIP_TRY(hipMemcpyAsync(raw_host, st->ds->a_raw, nb, hipMemcpyDeviceToHost, s));
+    if (smoothed_host) HIP_TRY(hipMemcpyAsync(smoothed_host, st->ds->a_smooth, nb, hipMemcpyDeviceToHost, s));
+    unsigned nf = 0;
+    if (numeric_flags) HIP_TRY(hipMemcpyAsync(&nf, &st->ds->numeric_flags, sizeof nf, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (numeric_flags) *numeric_flags = nf;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype, adacons_state *st,
+                            void *hip_stream) {
+    bool vec_ok = false;
+    adacons_status rc = check_call(G, N, d, dtype, st, nullptr, false, &vec_ok);
+    if (rc != ADACONS_OK) return rc;
+    HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
+                        tail_of(st, kGramFinishK), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0,
+                        static_cast<hipStream_t>(hip_stream)));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_read_gram(const adacons_state *st, double *K_host, void *hip_stream) {
+    if (!st) return fail(ADACONS_EINVAL, "state is NULL");
+    if (!K_host) return fail(ADACONS_EINVAL, "K_host is NULL");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(hipMemcpyAsync(K_host, st->K, (size_t)st->N * st->N * sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_weighted_sum(const void *G, int N, int64_t d, adacons_dtype dtype, const double *gamma_host,
+                                    adacons_state *st, float *out, void *hip_stream) {
+    bool vec_ok = false;
+    adacons_status rc = check_call(G, N, d, dtype, st, out, true, &vec_ok);
+    if (rc != ADACONS_OK) return rc;
+    if (!gamma_host) return fail(ADACONS_EINVAL, "gamma_host is NULL");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    float g32[kNMax];
+    for (int i = 0; i < N; ++i) g32[i] = (float)gamma_host[i];
+    HIP_TRY(hipMemcpyAsync(st->ds->gamma, gamma_host, (size_t)N * sizeof(double), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(st->ds->gamma32, g32, (size_t)N * sizeof(float), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));  // g32 lives on this frame
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out,
+                        st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_state_export(const adacons_state *st, double *m_host, int64_t *step, void *hip_stream) {
+    if (!st || !m_host || !step) return fail(ADACONS_EINVAL, "NULL argument");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    unsigned long long t = 0;
+    HIP_TRY(hipMemcpyAsync(m_host, st->ds->m, (size_t)st->N * sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(&t, &st->ds->step, sizeof t, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *step = (int64_t)t;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_state_import(adacons_state *st, const double *m_host, int64_t step, void *hip_stream) {
+    if (!st || !m_host) return fail(ADACONS_EINVAL, "NULL argument");
+    if (step < 0) return fail(ADACONS_EINVAL, "step < 0");
+    for (int i = 0; i < st->N; ++i)
+        if (!std::isfinite(m_host[i])) return fail(ADACONS_EINVAL, "m[%d] is not finite", i);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const unsigned long long t = (unsigned long long)step;
+    HIP_TRY(hipMemcpyAsync(st->ds->m, m_host, (size_t)st->N * sizeof(double), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(&st->ds->step, &t, sizeof t, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value) {
+    if (!st) return fail(ADACONS_EINVAL, "state is NULL");
+    if ((int)key < 0 || key >= ADACONS_TUNE_COUNT_) return fail(ADACONS_EINVAL, "unknown tuning key %d", (int)key);
+    if (value < 0) value = kTuneDefault[key];
+    if ((key == ADACONS_TUNE_GRAM_BLOCKS_PER_CU || key == ADACONS_TUNE_WSUM_BLOCKS_PER_CU) && value > 8)
+        return fail(ADACONS_EINVAL, "at most 8 workgroups per CU");
+    st->tune[key] = value;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_profile_begin(adacons_state *st, int max_calls) {
+    if (!st) return fail(ADACONS_EINVAL, "state is NULL");
+    if (max_calls < 1 || max_calls > 4096) return fail(ADACONS_EINVAL, "max_calls outside [1, 4096]");
+    while ((int)st->events.size() < 3 * max_calls) {
+        hipEvent_t ev;
+        HIP_TRY(hipEventCreate(&ev));
+        st->events.push_back(ev);
+    }
+    st->prof_capacity = max_calls;
+    st->prof_calls = 0;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *wsum_ms, int *calls,
+                                   void *hip_stream) {
+    if (!st) return fail(ADACONS_EINVAL, "state is NULL");
+    HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+    double a = 0.0, w = 0.0;
+    for (int c = 0; c < st->prof_calls; ++c) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, st->events[3 * c], st->events[3 * c + 1]));
+        a += ms;
+        HIP_TRY(hipEventElapsedTime(&ms, st->events[3 * c + 1], st->events[3 * c + 2]));
+        w += ms;
+    }
+    const int n = st->prof_calls;
+    if (gram_ms) *gram_ms = n ? a / n : 0.0;
+    if (wsum_ms) *wsum_ms = n ? w / n : 0.0;
+    if (calls) *calls = n;
+    st->prof_capacity = 0;
+    st->prof_calls = 0;
+    return ADACONS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Device-side helpers: 128-bit loads of fp32 / bf16 gradient elements, wavefront sums.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adacons {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+typedef uint16_t bf16_bits;  // a bfloat16 as stored: the upper half of an IEEE binary32
+
+__device__ __forceinline__ float bf16_widen(unsigned bits16) { return __uint_as_float(bits16 << 16); }
+
+// Elements per 128-bit load.
+template <typename T> struct VecWidth;
+template <> struct VecWidth<float> { static constexpr int value = 4; };
+template <> struct VecWidth<bf16_bits> { static constexpr int value = 8; };
+
+// Load VEC consecutive elements at p (p aligned to VEC*sizeof(T)) and widen them to fp32.
+// NT selects a non-temporal load (data not needed in cache again).
+template <typename T, int VEC, bool NT = false>
+__device__ __forceinline__ void load_vec(const T *__restrict__ p, float (&v)[VEC]);
+
+template <>
+__device__ __forceinline__ void load_vec<float, 4, false>(const float *__restrict__ p, float (&v)[4]) {
+    const f32x4 x = *reinterpret_cast<const f32x4 *>(p);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+}
+template <>
+__device__ __forceinline__ void load_vec<float, 4, true>(const float *__restrict__ p, float (&v)[4]) {
+    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+}
+template <>
+__device__ __forceinline__ void load_vec<float, 1, false>(const float *__restrict__ p, float (&v)[1]) { v[0] = p[0]; }
+template <>
+__device__ __forceinline__ void load_vec<float, 1, true>(const float *__restrict__ p, float (&v)[1]) {
+    v[0] = __builtin_nontemporal_load(p);
+}
+
+__device__ __forceinline__ void unpack_bf16x8(const u32x4 x, float (&v)[8]) {
+    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+    v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
+    v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+}
+template <>
+__device__ __forceinline__ void load_vec<bf16_bits, 8, false>(const bf16_bits *__restrict__ p, float (&v)[8]) {
+    unpack_bf16x8(*reinterpret_cast<const u32x4 *>(p), v);
+}
+template <>
+__device__ __forceinline__ void load_vec<bf16_bits, 8, true>(const bf16_bits *__restrict__ p, float (&v)[8]) {
+    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)), v);
+}
+template <>
+__device__ __forceinline__ void load_vec<bf16_bits, 1, false>(const bf16_bits *__restrict__ p, float (&v)[1]) {
+    v[0] = bf16_widen(p[0]);
+}
+template <>
+__device__ __forceinline__ void load_vec<bf16_bits, 1, true>(const bf16_bits *__restrict__ p, float (&v)[1]) {
+    v[0] = bf16_widen(__builtin_nontemporal_load(p));
+}
+
+// Sum over the 64 lanes of a wavefront in a fixed butterfly order; every lane gets the total.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+}  // namespace adacons

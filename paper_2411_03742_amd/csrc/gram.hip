@@ -1,0 +1,526 @@
+// Stage A1 (K = G G^T) and stage A2 (coefficients, sorted momentum, normalisation).
+//
+// A1 computes every inner product <g_i, g_j> of Eq. 7 (third line) / the double sum of Eq. 8
+// in one pass over G.  Two kernels:
+//   gram_vec_kernel   N <= 8: one thread owns VEC consecutive columns of all N rows
+//                     (N 128-bit loads in flight) and keeps the N(N+1)/2 sums in fp64 registers.
+//   gram_mfma_kernel  8 < N <= 64: rows grouped in tiles of 16; one wavefront feeds
+//                     v_mfma_f32_16x16x4_f32 with the same registers as A and B operand
+//                     (K is G times its own transpose), fp32 tile accumulators flushed into
+//                     fp64 every kFlush steps.
+// Both are persistent grids; every workgroup writes one row of partial sums, there are no
+// floating-point atomics, and the rows are added in a fixed order, so results are
+// bit-identical from run to run for a given launch shape.
+//
+// A2 is a single workgroup (the last one of A1 to finish, or a launch of its own).
+#include "adacons_internal.h"
+#include "device_util.h"
+
+namespace adacons {
+
+// ------------------------------------------------------------------------------------------
+// Reduction of the partial rows and the coefficient update
+// ------------------------------------------------------------------------------------------
+
+// Unpack p (position in the packed upper triangle) into (i, j), i <= j.
+__device__ __forceinline__ void unpack_pair(int p, int N, int &i, int &j) {
+    int row = 0, left = p;
+    while (left >= N - row) {
+        left -= N - row;
+        ++row;
+    }
+    i = row;
+    j = row + left;
+}
+
+// sum over rows b = first, first + step, ... (< nrows) of partials[b][p], b ascending; the loads
+// of eight rows are issued together, the additions keep the row order
+__device__ __forceinline__ double sum_rows(const double *partials, int np, int p, int first, int step, int nrows) {
+    double acc = 0.0;
+    int b = first;
+    for (; b + 7 * step < nrows; b += 8 * step) {
+        double t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t[k] = partials[(size_t)(b + k * step) * np + p];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc += t[k];
+    }
+    for (; b < nrows; b += step) acc += partials[(size_t)b * np + p];
+    return acc;
+}
+
+// K[i][j] = K[j][i] = sum over rows of partials[.][p]: kBlock / np interleaved sub-sums per pair,
+// added in slice order.  One workgroup, N(N+1)/2 <= kBlock; lds >= kBlock doubles.
+__device__ void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds) {
+    const int np = num_pairs(N);
+    const int tid = threadIdx.x;
+    const int slices = kBlock / np;
+    const int s = tid / np, p = tid - s * np;
+    if (s < slices) lds[s * np + p] = sum_rows(partials, np, p, s, slices, nrows);
+    __syncthreads();
+    if (tid < np) {
+        double tot = 0.0;
+        for (int q = 0; q < slices; ++q) tot += lds[q * np + tid];
+        int i, j;
+        unpack_pair(tid, N, i, j);
+        K[(size_t)i * N + j] = tot;
+        K[(size_t)j * N + i] = tot;
+    }
+    __syncthreads();
+}
+
+// Stage A2.  One workgroup of kBlock threads; thread i < N is worker i.  fp64 throughout.
+//   q_i = K_ii, r_i = sum_j K_ij                      (||g_i||^2 and N <g_i, gbar>)
+//   a_i = r_i / (N sqrt(q_i))                          Eq. 7, positive for a descent direction
+//   rank_i = #{j : a_j < a_i or (a_j = a_i and j < i)} ascending, ties to the lower index
+//   m[rank_i] <- beta m[rank_i] + (1 - beta) a_i ; a~_i = m[rank_i]      Eq. 11
+//   c_i = a~_i / sqrt(q_i)                             column normalisation, Eq. 8
+//   gamma_i = c_i / sum_k c_k                          Eq. 12-13 (weights sum to one)
+// Degenerate inputs: q_i = 0 gives a_i = c_i = 0; NaN/Inf in q or r, or |sum c| <= 1e-12 sum|c|,
+// gives gamma_i = 1/N; the EMA state is not touched when a statistic is non-finite.
+__device__ void update_coefficients(const double *K, DevState *ds, const CoeffParams cp, double *lds) {
+    const int N = cp.N;
+    const int tid = threadIdx.x;
+    double *a_sh = lds;          // [kNMax]
+    double *c_sh = lds + kNMax;  // [kNMax]
+    __shared__ int s_bad, s_zero;
+    __shared__ double s_sum, s_abs;
+    if (tid == 0) {
+        s_bad = 0;
+        s_zero = 0;
+    }
+    __syncthreads();
+
+    double q = 0.0, r = 0.0, a = 0.0;
+    if (tid < N) {
+        q = K[(size_t)tid * N + tid];
+        for (int j = 0; j < N; ++j) r += K[(size_t)tid * N + j];
+        if (!isfinite(q) || !isfinite(r)) atomicOr(&s_bad, 1);
+    }
+    __syncthreads();
+    const bool finite = (s_bad == 0);
+    if (tid < N) {
+        if (q > 0.0) {
+            a = r / ((double)N * sqrt(q));
+        } else {
+            a = 0.0;
+            if (finite) atomicOr(&s_zero, 1);
+        }
+        a_sh[tid] = a;
+    }
+    __syncthreads();
+
+    unsigned nf = 0;
+    if (!finite) {
+        nf = ADACONS_NUM_NONFINITE | ADACONS_NUM_UNIFORM_FALLBACK;
+        if (tid < N) {
+            const double g = 1.0 / (double)N;
+            ds->gamma[tid] = g;
+            ds->gamma32[tid] = (float)g;
+            ds->a_raw[tid] = a;
+            ds->a_smooth[tid] = a;
+        }
+    } else {
+        if (s_zero) nf |= ADACONS_NUM_ZERO_NORM;
+        double as = a;
+        if ((cp.flags & ADACONS_FLAG_MOMENTUM) && tid < N) {
+            int rank = 0;
+            for (int j = 0; j < N; ++j) {
+                const double aj = a_sh[j];
+                rank += (aj < a || (aj == a && j < tid)) ? 1 : 0;
+            }
+            // ranks are a permutation of 0..N-1: every state entry has exactly one writer
+            const double mk = cp.beta * ds->m[rank] + (1.0 - cp.beta) * a;
+            ds->m[rank] = mk;
+            as = mk;
+        }
+        double c = 0.0;
+        if (tid < N) {
+            c = (q > 0.0) ? as / sqrt(q) : 0.0;
+            c_sh[tid] = c;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double s = 0.0, sabs = 0.0;
+            for (int i = 0; i < N; ++i) {
+                s += c_sh[i];
+                sabs += fabs(c_sh[i]);
+            }
+            s_sum = s;
+            s_abs = sabs;
+        }
+        __syncthreads();
+        double g = c;
+        if (cp.flags & ADACONS_FLAG_NORMALIZE) {
+            const double s = s_sum, sabs = s_abs;
+            if (!isfinite(s) || sabs == 0.0 || fabs(s) <= 1e-12 * sabs) {
+                nf |= ADACONS_NUM_UNIFORM_FALLBACK;
+                g = 1.0 / (double)N;
+            } else {
+                g = c / s;
+            }
+        }
+        if (tid < N) {
+            ds->gamma[tid] = g;
+            ds->gamma32[tid] = (float)g;
+            ds->a_raw[tid] = a;
+            ds->a_smooth[tid] = as;
+        }
+    }
+    if (tid == 0) {
+        ds->numeric_flags = nf;
+        ds->step += 1ull;
+    }
+}
+
+// Called by every workgroup of a Gram kernel after its partial row is stored.  The workgroup
+// that takes the last ticket reduces all rows (and runs A2 when asked).  No workgroup waits for
+// another: every wave reaches the end of the kernel.
+__device__ void gram_tail(const GramTail &tail, double *lds) {
+    if (tail.mode == kGramPartialsOnly) return;
+    __shared__ unsigned s_ticket;
+    __threadfence();  // release: this workgroup's partial row is visible device-wide
+    __syncthreads();
+    if (threadIdx.x == 0) s_ticket = atomicAdd(&tail.ds->blocks_done, 1u);
+    __syncthreads();
+    if (s_ticket != gridDim.x - 1) return;
+    __threadfence();  // acquire: see every other workgroup's row
+    reduce_partial_rows(tail.partials, (int)gridDim.x, tail.cp.N, tail.K, lds);
+    if (tail.mode == kGramFinishCoeffs) update_coefficients(tail.K, tail.ds, tail.cp, lds);
+    if (threadIdx.x == 0) tail.ds->blocks_done = 0;  // ready for the next launch on this stream
+}
+
+// Reduction of the partial rows as a launch of its own (large N: more pairs than one workgroup
+// has threads).  Workgroup c owns pairs [64 c, 64 c + 64); four interleaved sub-sums per pair.
+__global__ void __launch_bounds__(kBlock) reduce_kernel(const double *partials, int nrows, int N, double *K) {
+    __shared__ double lds[kBlock];
+    const int np = num_pairs(N);
+    const int pl = threadIdx.x & 63, s = threadIdx.x >> 6;
+    const int p = blockIdx.x * 64 + pl;
+    lds[s * 64 + pl] = (p < np) ? sum_rows(partials, np, p, s, 4, nrows) : 0.0;
+    __syncthreads();
+    if (s == 0 && p < np) {
+        const double tot = ((lds[pl] + lds[64 + pl]) + lds[128 + pl]) + lds[192 + pl];
+        int i, j;
+        unpack_pair(p, N, i, j);
+        K[(size_t)i * N + j] = tot;
+        K[(size_t)j * N + i] = tot;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) coeff_kernel(const double *K, DevState *ds, CoeffParams cp) {
+    __shared__ double lds[kBlock];
+    update_coefficients(K, ds, cp, lds);
+}
+
+// ------------------------------------------------------------------------------------------
+// A1, N <= 8: fp64 register tile per thread
+// ------------------------------------------------------------------------------------------
+template <int N, typename T, int VEC>
+__global__ void __launch_bounds__(kBlock, 2)
+gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, GramTail tail) {
+    constexpr int NP = N * (N + 1) / 2;
+    __shared__ double lds[(4 * NP > kBlock) ? 4 * NP : kBlock];
+    double acc[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) acc[p] = 0.0;
+
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < ngroups; g += stride) {
+        float v[N][VEC];
+#pragma unroll
+        for (int i = 0; i < N; ++i) load_vec<T, VEC>(G + (int64_t)i * d + g * VEC, v[i]);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            double x[N];
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = (double)v[i][c];
+            int p = 0;
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+#pragma unroll
+                for (int j = i; j < N; ++j) {
+                    acc[p] = fma(x[i], x[j], acc[p]);
+                    ++p;
+                }
+        }
+    }
+
+    // workgroup sum: butterfly inside each wavefront, then the four wavefronts in order
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const double s = wave_sum(acc[p]);
+        if (lane == 0) lds[wave * NP + p] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < NP) {
+        const int p = threadIdx.x;
+        tail.partials[(size_t)blockIdx.x * NP + p] = ((lds[p] + lds[NP + p]) + lds[2 * NP + p]) + lds[3 * NP + p];
+    }
+    __syncthreads();
+    gram_tail(tail, lds);
+}
+
+// ------------------------------------------------------------------------------------------
+// A1, 8 < N <= 64: 16x16 tiles on the matrix cores
+// ------------------------------------------------------------------------------------------
+// v_mfma_f32_16x16x4_f32 operand layout (64 lanes):
+//   A (16x4):  lane l holds A[l % 16][l / 16]        B (4x16): lane l holds B[l / 16][l % 16]
+//   D (16x16): lane l, register r holds D[4 * (l / 16) + r][l % 16]
+// For a Gram tile pair (I, J): A[i][k] = G[16 I + i][col k], B[k][j] = G[16 J + j][col k], so
+// lane l supplies G[16 T + l % 16][col(l / 16)] for both operands.  A lane loads four consecutive
+// columns (one 128-bit load): its component c belongs to column  base + 4 (l / 16) + c,  and one
+// MFMA per component contracts four columns that sit 4 apart -- any pairing is valid as long as
+// A and B use the same one.
+constexpr int kFlush = 8;   // 16-column steps between flushes of the fp32 tile sums into fp64
+constexpr int kUnits = 4;   // 16-column steps a wavefront loads back to back
+
+template <int NT, typename T, int VEC4>
+__global__ void __launch_bounds__(kBlock, 2)
+gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, GramTail tail) {
+    constexpr int NPT = NT * (NT + 1) / 2;
+    __shared__ double lds[(NPT * 256 > kBlock) ? NPT * 256 : kBlock];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int r16 = lane & 15, kq = lane >> 4;
+
+    f32x4 acc32[NPT];
+    double acc64[NPT][4];
+#pragma unroll
+    for (int p = 0; p < NPT; ++p) {
+        acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
+    }
+
+    // a chunk = kUnits * 16 consecutive columns, taken by one wavefront
+    const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
+    int since_flush = 0;
+    for (int64_t ch = (int64_t)blockIdx.x * (kBlock / kWave) + wave; ch < nchunks; ch += wstride) {
+        float v[kUnits][NT][4];
+#pragma unroll
+        for (int u = 0; u < kUnits; ++u) {
+            const int64_t col = (ch * kUnits + u) * 16 + kq * 4;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int row = t * 16 + r16;
+                const T *p = G + (int64_t)row * d + col;
+                if constexpr (VEC4 != 0) {
+                    // d is a multiple of the vector width here, so col < d covers the 4 columns
+                    if (row < N && col < d) {
+                        if constexpr (sizeof(T) == 4) {
+                            load_vec<float, 4>(reinterpret_cast<const float *>(p), v[u][t]);
+                        } else {
+                            // 4 bf16 = one 64-bit load
+                            const uint2 x = *reinterpret_cast<const uint2 *>(p);
+                            v[u][t][0] = __uint_as_float(x.x << 16);
+                            v[u][t][1] = __uint_as_float(x.x & 0xffff0000u);
+                            v[u][t][2] = __uint_as_float(x.y << 16);
+                            v[u][t][3] = __uint_as_float(x.y & 0xffff0000u);
+                        }
+                    } else {
+                        v[u][t][0] = v[u][t][1] = v[u][t][2] = v[u][t][3] = 0.f;
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        float one[1] = {0.f};
+                        if (row < N && col + c < d) load_vec<T, 1>(p + c, one);
+                        v[u][t][c] = one[0];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnits; ++u) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                int p = 0;
+#pragma unroll
+                for (int I = 0; I < NT; ++I)
+#pragma unroll
+                    for (int J = I; J < NT; ++J) {
+                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[u][I][c], v[u][J][c], acc32[p], 0, 0, 0);
+                        ++p;
+                    }
+            }
+        }
+        since_flush += kUnits;
+        if (since_flush >= kFlush) {
+            since_flush = 0;
+#pragma unroll
+            for (int p = 0; p < NPT; ++p) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+                acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < NPT; ++p)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+
+    // add the four wavefronts in order through LDS: lds[(p * 4 + r) * 64 + lane]
+    for (int w = 0; w < kBlock / kWave; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int p = 0; p < NPT; ++p)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int e = (p * 4 + r) * kWave + lane;
+                    lds[e] = (w == 0) ? acc64[p][r] : lds[e] + acc64[p][r];
+                }
+        }
+        __syncthreads();
+    }
+    // scatter the tile sums into this workgroup's packed-upper-triangle row
+    const int np = num_pairs(N);
+    double *row_out = tail.partials + (size_t)blockIdx.x * np;
+    for (int e = threadIdx.x; e < NPT * 256; e += kBlock) {
+        const int l = e & (kWave - 1), r = (e >> 6) & 3, p = e >> 8;
+        int I = 0, left = p;
+        while (left >= NT - I) {
+            left -= NT - I;
+            ++I;
+        }
+        const int J = I + left;
+        const int i = I * 16 + 4 * (l >> 4) + r;
+        const int j = J * 16 + (l & 15);
+        if (i < N && j < N && i <= j) row_out[pair_index(i, j, N)] = lds[e];
+    }
+    __syncthreads();
+    gram_tail(tail, lds);
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------
+template <typename Kern>
+static int occupancy(Kern k) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k, kBlock, 0) != hipSuccess || nb < 1) nb = 1;
+    return nb;
+}
+
+static int grid_for(int64_t work_blocks, const LaunchShape &shape, int occ) {
+    int per_cu = (shape.blocks_per_cu > 0 && shape.blocks_per_cu < occ) ? shape.blocks_per_cu : occ;
+    int64_t grid = (int64_t)shape.num_cu * per_cu;
+    if (grid > work_blocks) grid = work_blocks;
+    if (grid > shape.max_rows) grid = shape.max_rows;
+    if (grid < 1) grid = 1;
+    return (int)grid;
+}
+
+int gram_rows_needed(int N, int num_cu) {
+    (void)N;
+    return num_cu * 8;  // upper bound on workgroups per CU for any Gram kernel
+}
+
+template <int N, typename T, int VEC>
+static hipError_t run_vec(const void *G, int64_t d, const LaunchShape &shape, const GramTail &tail, hipStream_t s,
+                          int *grid_out) {
+    static const int occ = occupancy(gram_vec_kernel<N, T, VEC>);
+    const int64_t ngroups = (d + VEC - 1) / VEC;
+    const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ);
+    *grid_out = grid;
+    hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC>), dim3(grid), dim3(kBlock), 0, s,
+                       static_cast<const T *>(G), d, ngroups, tail);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+static hipError_t dispatch_vec(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
+                               hipStream_t s, int *grid_out) {
+    switch (N) {
+        case 1: return run_vec<1, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 2: return run_vec<2, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 3: return run_vec<3, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 4: return run_vec<4, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 5: return run_vec<5, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 6: return run_vec<6, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 7: return run_vec<7, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 8: return run_vec<8, T, VEC>(G, d, shape, tail, s, grid_out);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int NT, typename T, int VEC4>
+static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
+                           hipStream_t s, int *grid_out) {
+    static const int occ = occupancy(gram_mfma_kernel<NT, T, VEC4>);
+    const int64_t cols_per_chunk = 16 * kUnits;
+    const int64_t nchunks = (d + cols_per_chunk - 1) / cols_per_chunk;
+    const int waves = kBlock / kWave;
+    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ);
+    *grid_out = grid;
+    hipLaunchKernelGGL((gram_mfma_kernel<NT, T, VEC4>), dim3(grid), dim3(kBlock), 0, s,
+                       static_cast<const T *>(G), N, d, nchunks, tail);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC4>
+static hipError_t dispatch_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
+                                hipStream_t s, int *grid_out) {
+    switch ((N + 15) / 16) {
+        case 1: return run_mfma<1, T, VEC4>(G, N, d, shape, tail, s, grid_out);
+        case 2: return run_mfma<2, T, VEC4>(G, N, d, shape, tail, s, grid_out);
+        case 3: return run_mfma<3, T, VEC4>(G, N, d, shape, tail, s, grid_out);
+        case 4: return run_mfma<4, T, VEC4>(G, N, d, shape, tail, s, grid_out);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// tail.mode names the state wanted at the end (K reduced, or K and the coefficient update).
+// With `fuse` and N(N+1)/2 <= kBlock the Gram kernel's last workgroup does it; otherwise the
+// partial rows are reduced, and the coefficients updated, by launches of their own.
+hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
+                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream) {
+    GramTail tail = want;
+    const bool fused = fuse && num_pairs(N) <= kBlock;
+    if (!fused) tail.mode = kGramPartialsOnly;
+    int grid = 0;
+    hipError_t e;
+    if (N <= 8) {
+        if (dtype == ADACONS_F32)
+            e = vec_ok ? dispatch_vec<float, 4>(G, N, d, shape, tail, stream, &grid)
+                       : dispatch_vec<float, 1>(G, N, d, shape, tail, stream, &grid);
+        else
+            e = vec_ok ? dispatch_vec<bf16_bits, 8>(G, N, d, shape, tail, stream, &grid)
+                       : dispatch_vec<bf16_bits, 1>(G, N, d, shape, tail, stream, &grid);
+    } else {
+        if (dtype == ADACONS_F32)
+            e = vec_ok ? dispatch_mfma<float, 1>(G, N, d, shape, tail, stream, &grid)
+                       : dispatch_mfma<float, 0>(G, N, d, shape, tail, stream, &grid);
+        else
+            e = vec_ok ? dispatch_mfma<bf16_bits, 1>(G, N, d, shape, tail, stream, &grid)
+                       : dispatch_mfma<bf16_bits, 0>(G, N, d, shape, tail, stream, &grid);
+    }
+    if (e != hipSuccess || fused) return e;
+    hipLaunchKernelGGL(reduce_kernel, dim3((num_pairs(N) + 63) / 64), dim3(kBlock), 0, stream,
+                       want.partials, grid, N, want.K);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (want.mode == kGramFinishCoeffs) return launch_coeffs(want.cp, want.K, want.ds, stream);
+    return hipSuccess;
+}
+
+// Zero the device state with a kernel (a fill kernel, unlike a memset node, is safe for a caller
+// that captures the stream into a HIP graph).
+__global__ void __launch_bounds__(kBlock) clear_state_kernel(DevState *ds, double *K, int nn) {
+    unsigned *w = reinterpret_cast<unsigned *>(ds);
+    for (unsigned i = threadIdx.x; i < sizeof(DevState) / sizeof(unsigned); i += kBlock) w[i] = 0u;
+    if (K)
+        for (int i = threadIdx.x; i < nn; i += kBlock) K[i] = 0.0;
+}
+
+hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t stream) {
+    hipLaunchKernelGGL(clear_state_kernel, dim3(1), dim3(kBlock), 0, stream, ds, K, nn);
+    return hipGetLastError();
+}
+
+hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStream_t stream) {
+    hipLaunchKernelGGL(coeff_kernel, dim3(1), dim3(kBlock), 0, stream, K, ds, cp);
+    return hipGetLastError();
+}
+
+}  // namespace adacons

@@ -1,0 +1,119 @@
+// Stage A3: out[k] = sum_i gamma_i G[i][k]  (Eq. 12), fp32 accumulate, fp32 out.
+//
+// A streaming kernel: one thread owns VEC consecutive columns, loads them from all N rows
+// (128-bit loads, eight rows in flight at a time), applies the weights in worker order
+// i = 0..N-1 with fused multiply-adds, and writes VEC floats.  G is read for the last time
+// here and `out` is not read back by this library, so both use non-temporal accesses.
+// With `reverse` the columns are walked from the end: the second pass then starts on the
+// part of G the first pass touched last, which is still in the memory-side cache.
+#include "adacons_internal.h"
+#include "device_util.h"
+
+namespace adacons {
+
+constexpr int kRowsInFlight = 8;
+
+template <int VEC>
+__device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, const float (&acc)[VEC]) {
+    if constexpr (VEC == 1) {
+        __builtin_nontemporal_store(acc[0], out + col);
+    } else {
+#pragma unroll
+        for (int c = 0; c < VEC; c += 4) {
+            const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+            __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + col + c));
+        }
+    }
+}
+
+// NCT > 0: N known at compile time (fully unrolled, N <= 16); NCT == 0: N taken from n_rt and
+// the rows are walked eight at a time.
+template <int NCT, typename T, int VEC, int UNR>
+__global__ void __launch_bounds__(kBlock)
+wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
+            float *__restrict__ out, int reverse) {
+    const int N = (NCT > 0) ? NCT : n_rt;
+    __shared__ float gam[kNMax];
+    if (threadIdx.x < N) gam[threadIdx.x] = gamma[threadIdx.x];
+    __syncthreads();
+
+    const int64_t stride = (int64_t)gridDim.x * kBlock * UNR;
+    for (int64_t g0 = (int64_t)blockIdx.x * kBlock * UNR + threadIdx.x; g0 < ngroups; g0 += stride) {
+        float acc[UNR][VEC];
+        int64_t col[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t g = g0 + (int64_t)u * kBlock;
+            col[u] = (g < ngroups) ? (reverse ? (ngroups - 1 - g) : g) * VEC : -1;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
+        }
+#pragma clang loop unroll_count(NCT > 0 ? (kNMax / kRowsInFlight) : 1)
+        for (int i0 = 0; i0 < N; i0 += kRowsInFlight) {
+            float v[UNR][kRowsInFlight][VEC];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int ii = 0; ii < kRowsInFlight; ++ii)
+                    if (i0 + ii < N && col[u] >= 0)
+                        load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + col[u], v[u][ii]);
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int ii = 0; ii < kRowsInFlight; ++ii)
+                    if (i0 + ii < N && col[u] >= 0) {
+                        const float w = gam[i0 + ii];
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w, v[u][ii][c], acc[u][c]);
+                    }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+            if (col[u] >= 0) store_out<VEC>(out, col[u], acc[u]);
+    }
+}
+
+template <typename Kern>
+static int occupancy(Kern k) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k, kBlock, 0) != hipSuccess || nb < 1) nb = 1;
+    return nb;
+}
+
+template <int NCT, typename T, int VEC, int UNR>
+static hipError_t run(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
+                      bool reverse, hipStream_t s) {
+    static const int occ = occupancy(wsum_kernel<NCT, T, VEC, UNR>);
+    const int64_t ngroups = (d + VEC - 1) / VEC;
+    const int64_t work = (ngroups + (int64_t)kBlock * UNR - 1) / ((int64_t)kBlock * UNR);
+    const int per_cu = (shape.blocks_per_cu > 0 && shape.blocks_per_cu < occ) ? shape.blocks_per_cu : occ;
+    int64_t grid = (int64_t)shape.num_cu * per_cu;
+    if (grid > work) grid = work;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL((wsum_kernel<NCT, T, VEC, UNR>), dim3((unsigned)grid), dim3(kBlock), 0, s,
+                       static_cast<const T *>(G), N, d, ngroups, gamma, out, reverse ? 1 : 0);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC, int UNR>
+static hipError_t dispatch(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
+                           bool reverse, hipStream_t s) {
+    switch (N) {
+        case 4: return run<4, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
+        case 8: return run<8, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
+        case 16: return run<16, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
+        default: return run<0, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
+    }
+}
+
+hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
+                       const LaunchShape &shape, const float *gamma, float *out, bool reverse,
+                       hipStream_t stream) {
+    if (dtype == ADACONS_F32)
+        return vec_ok ? dispatch<float, 4, 2>(G, N, d, shape, gamma, out, reverse, stream)
+                      : dispatch<float, 1, 2>(G, N, d, shape, gamma, out, reverse, stream);
+    return vec_ok ? dispatch<bf16_bits, 8, 1>(G, N, d, shape, gamma, out, reverse, stream)
+                  : dispatch<bf16_bits, 1, 2>(G, N, d, shape, gamma, out, reverse, stream);
+}
+
+}  // namespace adacons

@@ -1,0 +1,87 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, and rejects
+bad arguments before touching a GPU.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "adacons.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2411_03742_amd as pkg
+    return pkg
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adacons_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_named_entry_points():
+    syms = _declared_symbols()
+    for name in ("adacons_init_state", "adacons_aggregate", "adacons_coeffs"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol(lib):
+    cdll = ctypes.CDLL(lib.library_path())
+    declared = _declared_symbols()
+    assert len(declared) >= 15
+    for name in declared:
+        assert hasattr(cdll, name), f"{name} declared in adacons.h but not exported"
+    assert sorted(lib.EXPORTS) == declared
+
+
+def test_status_strings(lib):
+    cdll = ctypes.CDLL(lib.library_path())
+    cdll.adacons_status_string.restype = ctypes.c_char_p
+    seen = {cdll.adacons_status_string(i) for i in range(6)}
+    assert len(seen) == 6 and b"ok" in seen
+
+
+def test_argument_validation_needs_no_gpu(lib):
+    cdll = ctypes.CDLL(lib.library_path())
+    cdll.adacons_init_state.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_int64,
+                                        ctypes.c_double, ctypes.c_uint, ctypes.c_void_p]
+    cdll.adacons_last_error.restype = ctypes.c_char_p
+    st = ctypes.c_void_p()
+    EINVAL, EUNSUPPORTED = 1, 2
+    assert cdll.adacons_init_state(None, 4, 10, 0.9, 3, None) == EINVAL
+    assert cdll.adacons_init_state(ctypes.byref(st), 0, 10, 0.9, 3, None) == EINVAL
+    assert cdll.adacons_init_state(ctypes.byref(st), 65, 10, 0.9, 3, None) == EUNSUPPORTED
+    assert b"ADACONS_N_MAX" in cdll.adacons_last_error()
+    assert cdll.adacons_init_state(ctypes.byref(st), 4, 0, 0.9, 3, None) == EINVAL
+    assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, 1.0, 3, None) == EINVAL
+    assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, float("nan"), 3, None) == EINVAL
+    assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, 0.9, 8, None) == EINVAL
+    assert st.value is None
+    # NULL state handles are rejected by every call that takes one
+    cdll.adacons_aggregate.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert cdll.adacons_aggregate(None, 4, 10, 0, None, None, None) == EINVAL
+    assert cdll.adacons_destroy_state(None) == 0
+
+
+def test_product_path_never_touches_the_oracle():
+    """The GPU package and the benchmark's GPU leg must not route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2411_03742_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    otext = open(os.path.join(ROOT, "oracle", "adacons_oracle.py")).read()
+    assert "paper_2411_03742_amd" not in otext and "libadacons" not in otext
+
+
+def test_no_cuda_shims_or_dual_paths():
+    pkg = os.path.join(ROOT, "paper_2411_03742_amd", "csrc")
+    for f in os.listdir(pkg):
+        text = open(os.path.join(pkg, f)).read()
+        for banned in ("__HIP_PLATFORM_AMD__", "__CUDACC__", "cuda_runtime", "hipify"):
+            assert banned not in text

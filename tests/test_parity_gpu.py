@@ -1,0 +1,342 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 CPU oracle, element by element,
+on the same seeded inputs.  Sizes here are ones the oracle finishes in seconds, spanning several
+tiles and ragged tails; full-size configurations live in test_full_size_gpu.py.
+
+Tolerances (stated by the benchmark definition): out relative L2 error <= 1e-5 for fp32 inputs and
+<= 2e-3 for bf16 inputs; coefficients <= 1e-6 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import adacons_oracle as o
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3}
+GAMMA_TOL = 1e-6
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the GPU")
+    import paper_2411_03742_amd as p
+    return p
+
+
+def rel_l2(x, ref):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return np.linalg.norm(x - ref) / den if den > 0 else np.linalg.norm(x)
+
+
+def assert_gamma_close(got, ref, tol=GAMMA_TOL):
+    assert rel_l2(got, ref) <= tol, (got, ref)
+    scale = np.maximum(np.abs(ref), 1e-3 * np.abs(ref).max())
+    assert (np.abs(got - ref) / scale).max() <= tol, (got, ref)
+
+
+def rank_gap_is_safe(raw, tol=1e-9):
+    """The sort of Eq. 11 is a discrete decision taken on floating-point values: parity of the
+    coefficients is only defined when no two of them are closer than the arithmetic error."""
+    s = np.sort(raw)
+    if len(s) < 2:
+        return True
+    return np.diff(s).min() > tol * np.abs(s).max()
+
+
+def randG(N, d, dtype=torch.float32, sigma=1.0, seed=0):
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    s = torch.randn(d, generator=g, device=DEV)
+    G = s[None, :] + sigma * torch.randn(N, d, generator=g, device=DEV)
+    return G.to(dtype).contiguous()
+
+
+def both(pkg, G, agg, ost, check_out=True):
+    out = agg.aggregate(G)
+    info = agg.coeffs()
+    oout, oinfo = o.aggregate(workloads.to_oracle_input(G), ost, want_out=check_out)
+    assert info["numeric_flags"] == oinfo["numeric_flags"]
+    if rank_gap_is_safe(oinfo["raw"]) or not (ost.flags & o.FLAG_MOMENTUM):
+        assert_gamma_close(info["gamma"], oinfo["gamma"])
+        assert_gamma_close(info["raw"], oinfo["raw"])
+        assert_gamma_close(info["smoothed"], oinfo["smoothed"])
+        if check_out:
+            assert rel_l2(out.cpu().numpy(), oout) <= OUT_TOL[G.dtype]
+    return out, info, oinfo
+
+
+# ------------------------------------------------------------------------------ stage A1 ----
+GRAM_SHAPES = [(1, 1), (1, 1000), (2, 5), (3, 4096), (4, 100_003), (5, 262_144 + 64), (7, 33_333),
+               (8, 1_048_576 + 4), (8, 1023), (9, 70_000), (16, 200_000), (16, 17), (17, 50_001),
+               (32, 65_536 + 12), (33, 10_000), (48, 30_000), (63, 9_999), (64, 131_072 + 20)]
+
+
+@pytest.mark.parametrize("N,d", GRAM_SHAPES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_gram_matches_oracle(pkg, N, d, dtype):
+    G = randG(N, d, dtype, sigma=2.0, seed=N * 1000 + d % 997)
+    agg = pkg.AdaCons(N, d)
+    K = agg.gram(G)
+    Kref = o.gram(workloads.to_oracle_input(G))
+    scale = np.sqrt(np.outer(np.diag(Kref), np.diag(Kref)))
+    # N <= 8 accumulates in fp64; larger N sums 128 fp32 products on the matrix cores between
+    # fp64 flushes
+    tol = 1e-12 if N <= 8 else 3e-7
+    assert (np.abs(K - Kref) / scale).max() <= tol
+    assert np.array_equal(K, K.T)
+    agg.close()
+
+
+def test_gram_distinct_rows_exact(pkg):
+    """Small integers: every product and sum is exact in any precision, so a transposed tile or a
+    wrong row/column mapping shows as an exact mismatch."""
+    for N, d in [(3, 5), (8, 64), (16, 40), (40, 100), (64, 257)]:
+        G = ((torch.arange(N * d, device=DEV) * 7 + 3) % 11 - 5).float().reshape(N, d).contiguous()
+        agg = pkg.AdaCons(N, d)
+        K = agg.gram(G)
+        G64 = G.cpu().numpy().astype(np.float64)
+        assert np.array_equal(K, G64 @ G64.T), (N, d)
+        assert np.array_equal(K, o.gram(G.cpu().numpy()))
+        agg.close()
+
+
+# ------------------------------------------------------------------------------ stage A3 ----
+@pytest.mark.parametrize("N,d", [(1, 7), (4, 1_048_576), (8, 100_003), (8, 2_097_152 + 8), (13, 50_000),
+                                 (16, 300_000), (64, 70_004)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_weighted_sum_with_given_weights(pkg, N, d, dtype):
+    G = randG(N, d, dtype, sigma=1.5, seed=d % 1009)
+    gamma = np.random.default_rng(N).standard_normal(N) / N
+    agg = pkg.AdaCons(N, d)
+    out = agg.weighted_sum(G, gamma).cpu().numpy()
+    ref = o.weighted_sum(workloads.to_oracle_input(G), gamma.astype(np.float32).astype(np.float64))
+    assert rel_l2(out, ref) <= 1e-6
+    ref64 = o.weighted_sum(workloads.to_oracle_input(G), gamma)
+    assert rel_l2(out, ref64) <= OUT_TOL[dtype]
+    agg.close()
+
+
+# --------------------------------------------------------------------- whole aggregation ----
+@pytest.mark.parametrize("name,d,steps", [("C1", None, 1), ("C2", 1_048_576 + 40, 20), ("C3", 2_097_152 + 3072, 1),
+                                          ("C4", 262_144 + 8, 10), ("C5", 524_288 + 64, 100)])
+def test_config_streams_at_test_size(pkg, name, d, steps):
+    """The five benchmark recipes (same N, dtype, value distribution, step count) at a length the
+    oracle handles in seconds; coefficients checked at every step, outputs at every step."""
+    w = workloads.CONFIGS[name]
+    w = w if d is None else w.scaled(d, steps)
+    agg = pkg.AdaCons(w.N, w.d, beta=0.99)
+    ost = o.OracleState(w.N, beta=0.99)
+    safe_steps = 0
+    for t, G in enumerate(workloads.stream(w, DEV)):
+        _, info, oinfo = both(pkg, G, agg, ost, check_out=(t % 10 == 0 or t == steps - 1))
+        safe_steps += rank_gap_is_safe(oinfo["raw"])
+        assert abs(info["gamma"].sum() - 1.0) <= 1e-9
+        if name == "C5":
+            assert info["gamma"].min() < 0 and (info["gamma"] > 0).sum() == w.N - 1
+    assert safe_steps == steps          # no near-tie in these seeded streams
+    m, step = agg.export_state()
+    assert step == steps
+    assert_gamma_close(m, ost.m)
+    agg.close()
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("N", [5, 8, 16])
+def test_ablation_variants(pkg, flags, N):
+    """The four columns of Table 2: momentum and normalisation on/off."""
+    d = 150_000
+    agg = pkg.AdaCons(N, d, beta=0.9, flags=flags)
+    ost = o.OracleState(N, beta=0.9, flags=flags)
+    for t in range(4):
+        both(pkg, randG(N, d, sigma=2.0, seed=100 + t), agg, ost)
+    agg.close()
+
+
+def test_identical_gradients_reduce_to_averaging(pkg):
+    N, d = 8, 500_000
+    g = torch.randn(d, device=DEV)
+    G = g[None, :].repeat(N, 1).contiguous()
+    agg = pkg.AdaCons(N, d)
+    out = agg.aggregate(G)
+    info = agg.coeffs()
+    assert np.allclose(info["gamma"], 1.0 / N, rtol=1e-12)
+    assert rel_l2(out.cpu().numpy(), g.cpu().numpy()) <= 1e-6
+    agg.close()
+
+
+def test_permuting_workers_permutes_weights_only(pkg):
+    N, d, T = 16, 200_000, 6
+    a1, a2 = pkg.AdaCons(N, d, beta=0.9), pkg.AdaCons(N, d, beta=0.9)
+    rng = np.random.default_rng(5)
+    for t in range(T):
+        G = randG(N, d, sigma=2.0, seed=40 + t)
+        perm = torch.from_numpy(rng.permutation(N)).to(DEV)
+        o1, o2 = a1.aggregate(G), a2.aggregate(G.index_select(0, perm).contiguous())
+        g1, g2 = a1.coeffs()["gamma"], a2.coeffs()["gamma"]
+        assert_gamma_close(g2, g1[perm.cpu().numpy()], 1e-9)
+        assert rel_l2(o2.cpu().numpy(), o1.cpu().numpy()) <= 1e-6
+    a1.close(); a2.close()
+
+
+def test_runs_are_bit_identical_and_direction_of_second_pass_is_invisible(pkg):
+    N, d = 8, 3_000_000
+    G = randG(N, d, seed=9)
+    outs, gams = [], []
+    for rev in (1, 1, 0):
+        agg = pkg.AdaCons(N, d)
+        agg.tune(pkg.ADACONS_TUNE_REVERSE_SECOND_PASS, rev)
+        outs.append(agg.aggregate(G).clone())
+        gams.append(agg.coeffs()["gamma"])
+        agg.close()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert np.array_equal(gams[0], gams[1]) and np.array_equal(gams[0], gams[2])
+
+
+@pytest.mark.parametrize("N", [8, 16])
+def test_fused_and_separate_coefficient_update_agree(pkg, N):
+    d = 1_000_000
+    G = randG(N, d, seed=3)
+    res = []
+    for fuse in (1, 0):
+        agg = pkg.AdaCons(N, d)
+        agg.tune(pkg.ADACONS_TUNE_FUSE_COEFFS, fuse)
+        out = agg.aggregate(G)
+        res.append((out.clone(), agg.coeffs()["gamma"]))
+        agg.close()
+    assert_gamma_close(res[0][1], res[1][1], 1e-12)
+    assert rel_l2(res[0][0].cpu().numpy(), res[1][0].cpu().numpy()) <= 1e-6
+
+
+@pytest.mark.parametrize("per_cu", [1, 2, 3])
+def test_launch_shape_does_not_change_results_beyond_rounding(pkg, per_cu):
+    N, d = 8, 2_000_000
+    G = randG(N, d, seed=11)
+    ost = o.OracleState(N)
+    agg = pkg.AdaCons(N, d)
+    agg.tune(pkg.ADACONS_TUNE_GRAM_BLOCKS_PER_CU, per_cu)
+    agg.tune(pkg.ADACONS_TUNE_WSUM_BLOCKS_PER_CU, per_cu)
+    both(pkg, G, agg, ost)
+    agg.close()
+
+
+# --------------------------------------------------------------------------- edge cases ----
+@pytest.mark.parametrize("N,d", [(1, 1), (1, 513), (2, 1), (8, 3), (16, 1), (64, 2), (4, 255), (4, 1025)])
+def test_tiny_and_ragged_shapes(pkg, N, d):
+    G = randG(N, d, sigma=1.0, seed=N + d)
+    agg = pkg.AdaCons(N, d)
+    both(pkg, G, agg, o.OracleState(N))
+    agg.close()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("N", [4, 16])
+def test_unaligned_base_and_odd_length(pkg, N, dtype):
+    """G starting one element past a 16-byte boundary, odd d: the element-wise path."""
+    d = 100_001
+    flat = torch.randn(N * d + 1, device=DEV).to(dtype)
+    G = flat[1:].view(N, d)
+    assert G.data_ptr() % 16 != 0 and G.is_contiguous()
+    agg = pkg.AdaCons(N, d)
+    both(pkg, G, agg, o.OracleState(N))
+    outbuf = torch.empty(d + 1, device=DEV)
+    agg2 = pkg.AdaCons(N, d)
+    out2 = agg2.aggregate(G, out=outbuf[1:])
+    assert rel_l2(out2.cpu().numpy(), agg.aggregate(G).cpu().numpy()) <= 1e-6
+    agg.close(); agg2.close()
+
+
+def test_d_smaller_than_d_max_and_state_reuse(pkg):
+    N = 8
+    agg = pkg.AdaCons(N, 1_000_000, beta=0.5)
+    ost = o.OracleState(N, beta=0.5)
+    for d in (1_000_000, 12, 400_004, 999_999):
+        both(pkg, randG(N, d, seed=d % 13), agg, ost)
+    agg.close()
+
+
+def test_degenerate_inputs_match_oracle_flags(pkg):
+    N, d = 4, 10_000
+    agg = pkg.AdaCons(N, d, beta=0.5)
+    ost = o.OracleState(N, beta=0.5)
+    G = randG(N, d, seed=1)
+    both(pkg, G, agg, ost)
+    Gz = G.clone(); Gz[2] = 0
+    _, info, _ = both(pkg, Gz, agg, ost)
+    assert info["numeric_flags"] & pkg.ADACONS_NUM_ZERO_NORM and info["gamma"][2] == 0.0
+    m_before, _ = agg.export_state()
+    Gn = G.clone(); Gn[1, 77] = float("inf")
+    out = agg.aggregate(Gn)
+    info = agg.coeffs()
+    oout, oinfo = o.aggregate(workloads.to_oracle_input(Gn), ost, want_out=False)
+    assert info["numeric_flags"] == oinfo["numeric_flags"] == (pkg.ADACONS_NUM_NONFINITE | pkg.ADACONS_NUM_UNIFORM_FALLBACK)
+    assert np.allclose(info["gamma"], 0.25)
+    m_after, step = agg.export_state()
+    assert np.array_equal(m_before, m_after) and step == 3 == ost.t
+    _, info, _ = both(pkg, torch.zeros(N, d, device=DEV), agg, ost)
+    assert info["numeric_flags"] & pkg.ADACONS_NUM_UNIFORM_FALLBACK
+    g = torch.randn(d, device=DEV)
+    agg2, ost2 = pkg.AdaCons(2, d), o.OracleState(2)
+    _, info, _ = both(pkg, torch.stack([g, -g]).contiguous(), agg2, ost2)
+    assert info["numeric_flags"] & pkg.ADACONS_NUM_UNIFORM_FALLBACK and np.allclose(info["gamma"], 0.5)
+    agg.close(); agg2.close()
+
+
+def test_checkpoint_resume_and_reset(pkg):
+    N, d = 8, 200_000
+    a = pkg.AdaCons(N, d, beta=0.9)
+    Gs = [randG(N, d, sigma=2.0, seed=70 + t) for t in range(6)]
+    for G in Gs[:3]:
+        a.aggregate(G)
+    m, step = a.export_state()
+    b = pkg.AdaCons(N, d, beta=0.9)
+    b.import_state(m, step)
+    for G in Gs[3:]:
+        oa, ob = a.aggregate(G), b.aggregate(G)
+        assert torch.equal(oa, ob)
+        assert np.array_equal(a.coeffs()["gamma"], b.coeffs()["gamma"])
+    a.reset()
+    m0, s0 = a.export_state()
+    assert not m0.any() and s0 == 0
+    c = pkg.AdaCons(N, d, beta=0.9)
+    assert torch.equal(a.aggregate(Gs[0]), c.aggregate(Gs[0]))
+    a.close(); b.close(); c.close()
+
+
+def test_error_codes_on_the_gpu(pkg):
+    N, d = 4, 1000
+    agg = pkg.AdaCons(N, d)
+    G = randG(N, d)
+    out = torch.empty(d, device=DEV)
+    with pytest.raises(pkg.AdaConsError) as e:
+        pkg.adacons_aggregate(randG(N, d + 1), agg._st, torch.empty(d + 1, device=DEV))
+    assert e.value.status == 1
+    with pytest.raises(pkg.AdaConsError) as e:
+        pkg.adacons_aggregate(randG(N + 1, d), agg._st, out)
+    assert e.value.status == 1
+    with pytest.raises(pkg.AdaConsError) as e:                     # out aliases the last row of G
+        pkg.adacons_aggregate(G, agg._st, G[N - 1])
+    assert e.value.status == 1
+    agg.aggregate(G, out=out)                                       # still usable afterwards
+    assert torch.isfinite(out).all()
+    agg.close()
+
+
+def test_non_default_stream(pkg):
+    N, d = 8, 500_000
+    G = randG(N, d, seed=21)
+    ref = pkg.AdaCons(N, d)
+    want = ref.aggregate(G).clone()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    agg = pkg.AdaCons(N, d, stream=s)
+    with torch.cuda.stream(s):
+        out = agg.aggregate(G)
+        gam = agg.coeffs()["gamma"]
+    s.synchronize()
+    assert torch.equal(out, want) and np.array_equal(gam, ref.coeffs()["gamma"])
+    agg.close(); ref.close()
