@@ -23,6 +23,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
+# Bytes per launch that crossed the L2 <-> memory fabric, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script, scaled by the readings of a plain device copy of known size
+# (profiles/c2_n8_d25557032_f32_hbm_traffic_pmc.txt).  Fetched + written.
+PMC_TRAFFIC_BYTES = {
+    ("C2", "gram_kernel (A1)"): 837_090_000 + 70_000,
+    ("C2", "wsum_kernel (A3)"): 859_630_000 + 102_230_000,
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -31,6 +39,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="REPS",
+                    help="after the timed region, run REPS plain device copies of G (known size) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled to bytes")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass")
     args = ap.parse_args()
@@ -95,19 +106,26 @@ def main() -> int:
     gbps = floor / (ms_per_step * 1e-3) / 1e9
     eb = w.elem_bytes
     stages = {
-        "gram (A1+A2)": (w.N * w.d * eb, prof["gram_ms"]),
-        "wsum (A3)": (w.N * w.d * eb + 4 * w.d, prof["wsum_ms"]),
+        "gram_kernel (A1)": (w.N * w.d * eb, prof["gram_ms"]),
+        "wsum_kernel (A3)": (w.N * w.d * eb + 4 * w.d, prof["wsum_ms"]),
     }
     dom = max(stages, key=lambda k: stages[k][1])
     dom_bytes, dom_ms = stages[dom]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": PMC_TRAFFIC_BYTES.get((args.workload, dom)),
         "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 5),
-        "stages_ms": {k: round(v[1], 5) for k, v in stages.items()},
+        "stages_ms": dict({k: round(v[1], 5) for k, v in stages.items()}, **{"finish_kernel (A2)": round(prof["coeff_ms"], 5)}),
         "stages_GBps": {k: round(v[0] / (v[1] * 1e-3) / 1e9, 1) for k, v in stages.items()},
     }
+
+    if args.copy_calibration > 0:
+        scratch = torch.empty_like(bufs[0])
+        for _ in range(args.copy_calibration):
+            scratch.copy_(bufs[0])          # reads and writes N*d*elem bytes each
+        torch.cuda.synchronize()
+        del scratch
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -143,19 +161,18 @@ def cpu_baseline(w, G) -> dict:
 
     Gh = workloads.to_oracle_input(G)
     times = []
-    budget_s, t_start = 20.0, time.perf_counter()
-    while len(times) < 3 or (time.perf_counter() - t_start < budget_s and len(times) < 10):
-        st = o.OracleState(w.N, beta=0.99)
+    budget_s, t_start = 15.0, time.perf_counter()
+    st = o.OracleState(w.N, beta=0.99)
+    while len(times) < 3 or time.perf_counter() - t_start < budget_s:
         t0 = time.perf_counter()
         o.aggregate(Gh, st, want_out=True)
         times.append(time.perf_counter() - t0)
-        if time.perf_counter() - t_start > 3 * budget_s:
-            break
     med = float(np.median(times))
     return {"value": round(w.floor_bytes / med / 1e9, 3), "unit": "GB/s", "cores": o.num_threads(),
             "kind": "oracle", "seconds_per_aggregation": round(med, 4),
             "aggregations_per_s": round(1.0 / med, 4),
-            "sample": "%d whole aggregations of the full %s input (one step of the stream), median" % (len(times), w.name)}
+            "sample": "%d whole aggregations of the full %s input (one step of the stream) in %.0f s, median time"
+                      % (len(times), w.name, sum(times))}
 
 
 if __name__ == "__main__":

@@ -160,8 +160,8 @@ adacons_status adacons_state_import(adacons_state *st, const double *m_host, int
 typedef enum {
     ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0,  /* persistent workgroups per CU in stage A1 */
     ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1,  /* persistent workgroups per CU in stage A3 */
-    ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2; 0: A2 is its own launch */
-    ADACONS_TUNE_REVERSE_SECOND_PASS = 3, /* 1: A3 walks the columns backwards (cache reuse) */
+    ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2; 0 (default): A2 is its own launch */
+    ADACONS_TUNE_REVERSE_SECOND_PASS = 3, /* 1: A3 walks its column tiles backwards; 0 (default): forwards */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);
@@ -170,13 +170,15 @@ adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);
  * Per-kernel timing with HIP events on the caller's stream, for roofline reporting.
  * adacons_profile_begin() creates event pairs for up to max_calls aggregations (this
  * allocates; call it outside any timed region); later adacons_aggregate() calls record an
- * event before stage A1, between A2 and A3, and after A3.  adacons_profile_end() waits for the
- * stream, returns the mean duration in milliseconds of A1+A2 (gram_ms) and of A3 (wsum_ms) over
- * the recorded calls and their count, and stops recording.  Any output pointer may be NULL.
+ * event before stage A1, after the Gram kernel, after A2 and after A3.  adacons_profile_end()
+ * waits for the stream, returns the mean duration in milliseconds of the Gram kernel (gram_ms), of
+ * the partial-sum reduction + coefficient update (coeff_ms; 0 when the Gram kernel's last
+ * workgroup does that work) and of A3 (wsum_ms) over the recorded calls and their count, and
+ * stops recording.  Any output pointer may be NULL.
  */
 adacons_status adacons_profile_begin(adacons_state *st, int max_calls);
-adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *wsum_ms, int *calls,
-                                   void *hip_stream);
+adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *coeff_ms, double *wsum_ms,
+                                   int *calls, void *hip_stream);
 
 const char *adacons_status_string(adacons_status s);
 const char *adacons_last_error(void);

@@ -61,7 +61,7 @@ def _load() -> ctypes.CDLL:
         "adacons_state_import": [vp, dp, i64, vp],
         "adacons_tune": [vp, i32, i32],
         "adacons_profile_begin": [vp, i32],
-        "adacons_profile_end": [vp, dp, dp, ctypes.POINTER(i32), vp],
+        "adacons_profile_end": [vp, dp, dp, dp, ctypes.POINTER(i32), vp],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -189,10 +189,10 @@ def adacons_profile_begin(st, max_calls: int) -> None:
 
 
 def adacons_profile_end(st, stream=None) -> dict:
-    g, w, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int(0)
-    _check(_lib.adacons_profile_end(st, ctypes.byref(g), ctypes.byref(w), ctypes.byref(n), _stream(stream)),
-           "adacons_profile_end")
-    return {"gram_ms": g.value, "wsum_ms": w.value, "calls": n.value}
+    g, c, w, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int(0)
+    _check(_lib.adacons_profile_end(st, ctypes.byref(g), ctypes.byref(c), ctypes.byref(w), ctypes.byref(n),
+                                    _stream(stream)), "adacons_profile_end")
+    return {"gram_ms": g.value, "coeff_ms": c.value, "wsum_ms": w.value, "calls": n.value}
 
 
 # ---- a small convenience wrapper that owns a state ----------------------------------------

@@ -59,7 +59,8 @@ struct LaunchShape {
 
 // gram.hip
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
-                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream);
+                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream,
+                       hipEvent_t between = nullptr);  // `between`: recorded after the main Gram kernel
 hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStream_t stream);
 int gram_rows_needed(int N, int num_cu);
 hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t stream);  // K may be NULL

@@ -24,7 +24,7 @@ struct adacons_state {
     int max_rows;
     int tune[ADACONS_TUNE_COUNT_];
     // per-kernel timing (adacons_profile_begin/end)
-    std::vector<hipEvent_t> events;  // 3 per call: before A1, after A1+A2, after A3
+    std::vector<hipEvent_t> events;  // 4 per call: before A1, after the Gram kernel, after A2, after A3
     int prof_capacity;
     int prof_calls;
 };
@@ -51,7 +51,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* occupancy */, 0 /* occupancy */, 1, 1};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 
@@ -190,16 +190,17 @@ adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype 
     if (rc != ADACONS_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const bool prof = st->prof_capacity > 0 && st->prof_calls < st->prof_capacity;
-    hipEvent_t *ev = prof ? &st->events[(size_t)st->prof_calls * 3] : nullptr;
+    hipEvent_t *ev = prof ? &st->events[(size_t)st->prof_calls * 4] : nullptr;
 
     if (prof) HIP_TRY(hipEventRecord(ev[0], s));
     HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
-                        tail_of(st, kGramFinishCoeffs), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s));
-    if (prof) HIP_TRY(hipEventRecord(ev[1], s));
+                        tail_of(st, kGramFinishCoeffs), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s,
+                        prof ? ev[1] : nullptr));
+    if (prof) HIP_TRY(hipEventRecord(ev[2], s));
     HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out,
                         st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s));
     if (prof) {
-        HIP_TRY(hipEventRecord(ev[2], s));
+        HIP_TRY(hipEventRecord(ev[3], s));
         st->prof_calls += 1;
     }
     return ADACONS_OK;
@@ -295,7 +296,7 @@ adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value) 
 adacons_status adacons_profile_begin(adacons_state *st, int max_calls) {
     if (!st) return fail(ADACONS_EINVAL, "state is NULL");
     if (max_calls < 1 || max_calls > 4096) return fail(ADACONS_EINVAL, "max_calls outside [1, 4096]");
-    while ((int)st->events.size() < 3 * max_calls) {
+    while ((int)st->events.size() < 4 * max_calls) {
         hipEvent_t ev;
         HIP_TRY(hipEventCreate(&ev));
         st->events.push_back(ev);
@@ -305,20 +306,23 @@ adacons_status adacons_profile_begin(adacons_state *st, int max_calls) {
     return ADACONS_OK;
 }
 
-adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *wsum_ms, int *calls,
-                                   void *hip_stream) {
+adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *coeff_ms, double *wsum_ms,
+                                   int *calls, void *hip_stream) {
     if (!st) return fail(ADACONS_EINVAL, "state is NULL");
     HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
-    double a = 0.0, w = 0.0;
+    double a = 0.0, b = 0.0, w = 0.0;
     for (int c = 0; c < st->prof_calls; ++c) {
         float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, st->events[3 * c], st->events[3 * c + 1]));
+        HIP_TRY(hipEventElapsedTime(&ms, st->events[4 * c], st->events[4 * c + 1]));
         a += ms;
-        HIP_TRY(hipEventElapsedTime(&ms, st->events[3 * c + 1], st->events[3 * c + 2]));
+        HIP_TRY(hipEventElapsedTime(&ms, st->events[4 * c + 1], st->events[4 * c + 2]));
+        b += ms;
+        HIP_TRY(hipEventElapsedTime(&ms, st->events[4 * c + 2], st->events[4 * c + 3]));
         w += ms;
     }
     const int n = st->prof_calls;
     if (gram_ms) *gram_ms = n ? a / n : 0.0;
+    if (coeff_ms) *coeff_ms = n ? b / n : 0.0;
     if (wsum_ms) *wsum_ms = n ? w / n : 0.0;
     if (calls) *calls = n;
     st->prof_capacity = 0;

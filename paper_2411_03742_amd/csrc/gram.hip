@@ -49,12 +49,12 @@ __device__ __forceinline__ double sum_rows(const double *partials, int np, int p
     return acc;
 }
 
-// K[i][j] = K[j][i] = sum over rows of partials[.][p]: kBlock / np interleaved sub-sums per pair,
-// added in slice order.  One workgroup, N(N+1)/2 <= kBlock; lds >= kBlock doubles.
+// K[i][j] = K[j][i] = sum over rows of partials[.][p]: blockDim.x / np interleaved sub-sums per
+// pair, added in slice order.  One workgroup, N(N+1)/2 <= blockDim.x; lds >= blockDim.x doubles.
 __device__ void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds) {
     const int np = num_pairs(N);
     const int tid = threadIdx.x;
-    const int slices = kBlock / np;
+    const int slices = (int)blockDim.x / np;
     const int s = tid / np, p = tid - s * np;
     if (s < slices) lds[s * np + p] = sum_rows(partials, np, p, s, slices, nrows);
     __syncthreads();
@@ -69,7 +69,7 @@ __device__ void reduce_partial_rows(const double *partials, int nrows, int N, do
     __syncthreads();
 }
 
-// Stage A2.  One workgroup of kBlock threads; thread i < N is worker i.  fp64 throughout.
+// Stage A2.  One workgroup (at least kNMax threads); thread i < N is worker i.  fp64 throughout.
 //   q_i = K_ii, r_i = sum_j K_ij                      (||g_i||^2 and N <g_i, gbar>)
 //   a_i = r_i / (N sqrt(q_i))                          Eq. 7, positive for a descent direction
 //   rank_i = #{j : a_j < a_i or (a_j = a_i and j < i)} ascending, ties to the lower index
@@ -206,6 +206,16 @@ __global__ void __launch_bounds__(kBlock) reduce_kernel(const double *partials, 
         K[(size_t)i * N + j] = tot;
         K[(size_t)j * N + i] = tot;
     }
+}
+
+// Reduction of the partial rows and (optionally) the coefficient update in one workgroup of
+// kFinishBlock threads, for N(N+1)/2 <= kFinishBlock: the launch between the two streaming passes.
+constexpr int kFinishBlock = 1024;
+__global__ void __launch_bounds__(kFinishBlock)
+finish_kernel(const double *partials, int nrows, double *K, DevState *ds, CoeffParams cp, int with_coeffs) {
+    __shared__ double lds[kFinishBlock];
+    reduce_partial_rows(partials, nrows, cp.N, K, lds);
+    if (with_coeffs) update_coefficients(K, ds, cp, lds);
 }
 
 __global__ void __launch_bounds__(kBlock) coeff_kernel(const double *K, DevState *ds, CoeffParams cp) {
@@ -403,8 +413,10 @@ static int occupancy(Kern k) {
     return nb;
 }
 
-static int grid_for(int64_t work_blocks, const LaunchShape &shape, int occ) {
-    int per_cu = (shape.blocks_per_cu > 0 && shape.blocks_per_cu < occ) ? shape.blocks_per_cu : occ;
+// blocks_per_cu <= 0 picks `dflt` workgroups per CU (never more than the occupancy allows).
+static int grid_for(int64_t work_blocks, const LaunchShape &shape, int occ, int dflt) {
+    int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : dflt;
+    if (per_cu > occ) per_cu = occ;
     int64_t grid = (int64_t)shape.num_cu * per_cu;
     if (grid > work_blocks) grid = work_blocks;
     if (grid > shape.max_rows) grid = shape.max_rows;
@@ -422,7 +434,7 @@ static hipError_t run_vec(const void *G, int64_t d, const LaunchShape &shape, co
                           int *grid_out) {
     static const int occ = occupancy(gram_vec_kernel<N, T, VEC>);
     const int64_t ngroups = (d + VEC - 1) / VEC;
-    const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ);
+    const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ, 1);
     *grid_out = grid;
     hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC>), dim3(grid), dim3(kBlock), 0, s,
                        static_cast<const T *>(G), d, ngroups, tail);
@@ -452,7 +464,7 @@ static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &s
     const int64_t cols_per_chunk = 16 * kUnits;
     const int64_t nchunks = (d + cols_per_chunk - 1) / cols_per_chunk;
     const int waves = kBlock / kWave;
-    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ);
+    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, 2);
     *grid_out = grid;
     hipLaunchKernelGGL((gram_mfma_kernel<NT, T, VEC4>), dim3(grid), dim3(kBlock), 0, s,
                        static_cast<const T *>(G), N, d, nchunks, tail);
@@ -472,10 +484,11 @@ static hipError_t dispatch_mfma(const void *G, int N, int64_t d, const LaunchSha
 }
 
 // tail.mode names the state wanted at the end (K reduced, or K and the coefficient update).
-// With `fuse` and N(N+1)/2 <= kBlock the Gram kernel's last workgroup does it; otherwise the
-// partial rows are reduced, and the coefficients updated, by launches of their own.
+// With `fuse` and N(N+1)/2 <= kBlock the Gram kernel's last workgroup does it; otherwise one
+// finish_kernel launch does (N <= 44), or a multi-workgroup reduction followed by coeff_kernel.
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
-                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream) {
+                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream,
+                       hipEvent_t between) {
     GramTail tail = want;
     const bool fused = fuse && num_pairs(N) <= kBlock;
     if (!fused) tail.mode = kGramPartialsOnly;
@@ -496,7 +509,13 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
             e = vec_ok ? dispatch_mfma<bf16_bits, 1>(G, N, d, shape, tail, stream, &grid)
                        : dispatch_mfma<bf16_bits, 0>(G, N, d, shape, tail, stream, &grid);
     }
+    if (e == hipSuccess && between) e = hipEventRecord(between, stream);
     if (e != hipSuccess || fused) return e;
+    if (num_pairs(N) <= kFinishBlock) {
+        hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kFinishBlock), 0, stream, want.partials, grid, want.K,
+                           want.ds, want.cp, want.mode == kGramFinishCoeffs ? 1 : 0);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(reduce_kernel, dim3((num_pairs(N) + 63) / 64), dim3(kBlock), 0, stream,
                        want.partials, grid, N, want.K);
     if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -4,8 +4,9 @@
 // (128-bit loads, eight rows in flight at a time), applies the weights in worker order
 // i = 0..N-1 with fused multiply-adds, and writes VEC floats.  G is read for the last time
 // here and `out` is not read back by this library, so both use non-temporal accesses.
-// With `reverse` the columns are walked from the end: the second pass then starts on the
-// part of G the first pass touched last, which is still in the memory-side cache.
+// With `reverse` the tiles of kBlock * UNR column groups are walked from the end (columns still
+// ascend inside a tile): the second pass then starts on the part of G the first pass touched last,
+// which is still in the memory-side cache.
 #include "adacons_internal.h"
 #include "device_util.h"
 
@@ -26,50 +27,73 @@ __device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, 
     }
 }
 
-// NCT > 0: N known at compile time (fully unrolled, N <= 16); NCT == 0: N taken from n_rt and
-// the rows are walked eight at a time.
+// One tile = kBlock * UNR column groups: thread t owns groups base + u * kBlock, u < UNR.
+// FULL: every group of the tile exists, so the loads carry no predicate and are all issued
+// before the first use.
+template <int NCT, typename T, int VEC, int UNR, bool FULL>
+__device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, const int64_t d, const int64_t ngroups,
+                                          const int64_t base, const float *gam, float *__restrict__ out) {
+    float acc[UNR][VEC];
+    bool live[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        live[u] = FULL || (base + (int64_t)u * kBlock < ngroups);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
+    }
+#pragma clang loop unroll_count(NCT > 0 ? (kNMax / kRowsInFlight) : 1)
+    for (int i0 = 0; i0 < N; i0 += kRowsInFlight) {
+        float v[UNR][kRowsInFlight][VEC];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int ii = 0; ii < kRowsInFlight; ++ii)
+                if ((NCT > 0 || i0 + ii < N) && (NCT == 0 || i0 + ii < NCT) && live[u])
+                    load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + (base + (int64_t)u * kBlock) * VEC, v[u][ii]);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int ii = 0; ii < kRowsInFlight; ++ii)
+                if ((NCT > 0 || i0 + ii < N) && (NCT == 0 || i0 + ii < NCT) && live[u]) {
+                    const float w = gam[i0 + ii];
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w, v[u][ii][c], acc[u][c]);
+                }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+        if (live[u]) store_out<VEC>(out, (base + (int64_t)u * kBlock) * VEC, acc[u]);
+}
+
+// NCT > 0: N known at compile time (rows fully unrolled, weights in registers, N <= 16);
+// NCT == 0: N taken from n_rt, rows walked eight at a time, weights in LDS.
 template <int NCT, typename T, int VEC, int UNR>
 __global__ void __launch_bounds__(kBlock)
 wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
             float *__restrict__ out, int reverse) {
     const int N = (NCT > 0) ? NCT : n_rt;
-    __shared__ float gam[kNMax];
-    if (threadIdx.x < N) gam[threadIdx.x] = gamma[threadIdx.x];
-    __syncthreads();
-
-    const int64_t stride = (int64_t)gridDim.x * kBlock * UNR;
-    for (int64_t g0 = (int64_t)blockIdx.x * kBlock * UNR + threadIdx.x; g0 < ngroups; g0 += stride) {
-        float acc[UNR][VEC];
-        int64_t col[UNR];
+    __shared__ float gam_lds[kNMax];
+    float gam_reg[NCT > 0 ? NCT : 1];
+    const float *gam;
+    if constexpr (NCT > 0) {
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int64_t g = g0 + (int64_t)u * kBlock;
-            col[u] = (g < ngroups) ? (reverse ? (ngroups - 1 - g) : g) * VEC : -1;
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
-        }
-#pragma clang loop unroll_count(NCT > 0 ? (kNMax / kRowsInFlight) : 1)
-        for (int i0 = 0; i0 < N; i0 += kRowsInFlight) {
-            float v[UNR][kRowsInFlight][VEC];
-#pragma unroll
-            for (int u = 0; u < UNR; ++u)
-#pragma unroll
-                for (int ii = 0; ii < kRowsInFlight; ++ii)
-                    if (i0 + ii < N && col[u] >= 0)
-                        load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + col[u], v[u][ii]);
-#pragma unroll
-            for (int u = 0; u < UNR; ++u)
-#pragma unroll
-                for (int ii = 0; ii < kRowsInFlight; ++ii)
-                    if (i0 + ii < N && col[u] >= 0) {
-                        const float w = gam[i0 + ii];
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w, v[u][ii][c], acc[u][c]);
-                    }
-        }
-#pragma unroll
-        for (int u = 0; u < UNR; ++u)
-            if (col[u] >= 0) store_out<VEC>(out, col[u], acc[u]);
+        for (int i = 0; i < NCT; ++i) gam_reg[i] = gamma[i];
+        gam = gam_reg;
+    } else {
+        if (threadIdx.x < N) gam_lds[threadIdx.x] = gamma[threadIdx.x];
+        __syncthreads();
+        gam = gam_lds;
+    }
+    constexpr int64_t kTile = (int64_t)kBlock * UNR;
+    const int64_t ntiles = (ngroups + kTile - 1) / kTile;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        // reverse: tiles in descending order, columns ascending inside a tile
+        const int64_t tt = reverse ? (ntiles - 1 - t) : t;
+        const int64_t base = tt * kTile + threadIdx.x;
+        if ((tt + 1) * kTile <= ngroups)
+            wsum_tile<NCT, T, VEC, UNR, true>(G, N, d, ngroups, base, gam, out);
+        else
+            wsum_tile<NCT, T, VEC, UNR, false>(G, N, d, ngroups, base, gam, out);
     }
 }
 
@@ -86,7 +110,8 @@ static hipError_t run(const void *G, int N, int64_t d, const LaunchShape &shape,
     static const int occ = occupancy(wsum_kernel<NCT, T, VEC, UNR>);
     const int64_t ngroups = (d + VEC - 1) / VEC;
     const int64_t work = (ngroups + (int64_t)kBlock * UNR - 1) / ((int64_t)kBlock * UNR);
-    const int per_cu = (shape.blocks_per_cu > 0 && shape.blocks_per_cu < occ) ? shape.blocks_per_cu : occ;
+    int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 8;
+    if (per_cu > occ) per_cu = occ;
     int64_t grid = (int64_t)shape.num_cu * per_cu;
     if (grid > work) grid = work;
     if (grid < 1) grid = 1;
