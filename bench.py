@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # WRITE_SIZE runs of this script, scaled by the readings of a plain device copy of known size
 # (profiles/c2_n8_d25557032_f32_hbm_traffic_pmc.txt).  Fetched + written.
 PMC_TRAFFIC_BYTES = {
-    ("C2", "gram_kernel (A1)"): 837_090_000 + 70_000,
-    ("C2", "wsum_kernel (A3)"): 859_630_000 + 102_230_000,
+    ("C2", "gram_kernel (A1)"): 827_070_000 + 70_000,
+    ("C2", "wsum_kernel (A3)"): 857_330_000 + 102_230_000,
 }
 
 
@@ -43,7 +43,7 @@ def main() -> int:
                     help="after the timed region, run REPS plain device copies of G (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled to bytes")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
-                    help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass")
+                    help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass / cached_head_mb")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 "
@@ -70,7 +70,8 @@ def main() -> int:
     keys = {"gram_blocks_per_cu": ada.ADACONS_TUNE_GRAM_BLOCKS_PER_CU,
             "wsum_blocks_per_cu": ada.ADACONS_TUNE_WSUM_BLOCKS_PER_CU,
             "fuse_coeffs": ada.ADACONS_TUNE_FUSE_COEFFS,
-            "reverse_second_pass": ada.ADACONS_TUNE_REVERSE_SECOND_PASS}
+            "reverse_second_pass": ada.ADACONS_TUNE_REVERSE_SECOND_PASS,
+            "cached_head_mb": ada.ADACONS_TUNE_CACHED_HEAD_MB}
     tuned = {}
     for kv in args.tune:
         k, v = kv.split("=")

@@ -162,6 +162,10 @@ typedef enum {
     ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1,  /* persistent workgroups per CU in stage A3 */
     ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2; 0 (default): A2 is its own launch */
     ADACONS_TUNE_REVERSE_SECOND_PASS = 3, /* 1: A3 walks its column tiles backwards; 0 (default): forwards */
+    ADACONS_TUNE_CACHED_HEAD_MB = 4,      /* A1 (N <= 8) reads the first `value` MiB of G with cache-allocating
+                                             loads and streams the rest past the caches (non-temporal), so
+                                             that A3 finds the head in the 256 MB memory-side cache.
+                                             Default 320; >= 2^20 means all of G */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);

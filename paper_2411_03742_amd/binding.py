@@ -24,6 +24,7 @@ ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0
 ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1
 ADACONS_TUNE_FUSE_COEFFS = 2
 ADACONS_TUNE_REVERSE_SECOND_PASS = 3
+ADACONS_TUNE_CACHED_HEAD_MB = 4
 
 EXPORTS = [
     "adacons_init_state", "adacons_destroy_state", "adacons_reset_state", "adacons_aggregate",

@@ -55,6 +55,7 @@ struct LaunchShape {
     int num_cu;
     int blocks_per_cu;  // <= 0: let the launcher decide
     int max_rows;       // capacity of the partials workspace in rows
+    int cached_head_mb; // stage A1: MiB at the head of G read with cache-allocating loads; < 0: all
 };
 
 // gram.hip

@@ -34,24 +34,28 @@ __device__ __forceinline__ void unpack_pair(int p, int N, int &i, int &j) {
 }
 
 // sum over rows b = first, first + step, ... (< nrows) of partials[b][p], b ascending; the loads
-// of eight rows are issued together, the additions keep the row order
+// of up to sixteen rows are issued together (rows past the end read as +0.0, which leaves a sum
+// unchanged), the additions keep the row order
 __device__ __forceinline__ double sum_rows(const double *partials, int np, int p, int first, int step, int nrows) {
     double acc = 0.0;
-    int b = first;
-    for (; b + 7 * step < nrows; b += 8 * step) {
-        double t[8];
+    for (int b = first; b < nrows; b += 16 * step) {
+        double t[16];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) t[k] = partials[(size_t)(b + k * step) * np + p];
+        for (int k = 0; k < 16; ++k) {
+            const int row = b + k * step;
+            t[k] = (row < nrows) ? partials[(size_t)row * np + p] : 0.0;
+        }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc += t[k];
+        for (int k = 0; k < 16; ++k) acc += t[k];
     }
-    for (; b < nrows; b += step) acc += partials[(size_t)b * np + p];
     return acc;
 }
 
 // K[i][j] = K[j][i] = sum over rows of partials[.][p]: blockDim.x / np interleaved sub-sums per
 // pair, added in slice order.  One workgroup, N(N+1)/2 <= blockDim.x; lds >= blockDim.x doubles.
-__device__ void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds) {
+// When K_lds is given, K is also left there (N x N) for the coefficient update that follows.
+__device__ void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds,
+                                    double *K_lds = nullptr) {
     const int np = num_pairs(N);
     const int tid = threadIdx.x;
     const int slices = (int)blockDim.x / np;
@@ -65,6 +69,10 @@ __device__ void reduce_partial_rows(const double *partials, int nrows, int N, do
         unpack_pair(tid, N, i, j);
         K[(size_t)i * N + j] = tot;
         K[(size_t)j * N + i] = tot;
+        if (K_lds) {
+            K_lds[i * N + j] = tot;
+            K_lds[j * N + i] = tot;
+        }
     }
     __syncthreads();
 }
@@ -78,9 +86,14 @@ __device__ void reduce_partial_rows(const double *partials, int nrows, int N, do
 //   gamma_i = c_i / sum_k c_k                          Eq. 12-13 (weights sum to one)
 // Degenerate inputs: q_i = 0 gives a_i = c_i = 0; NaN/Inf in q or r, or |sum c| <= 1e-12 sum|c|,
 // gives gamma_i = 1/N; the EMA state is not touched when a statistic is non-finite.
-__device__ void update_coefficients(const double *K, DevState *ds, const CoeffParams cp, double *lds) {
+// m_old: the state entry m[tid] loaded by the caller ahead of time (thread tid < N), so that the
+// global-memory latency of the state overlaps the reduction; it is exchanged through LDS.
+__device__ void update_coefficients(const double *K, DevState *ds, const CoeffParams cp, double *lds,
+                                    double m_old) {
     const int N = cp.N;
     const int tid = threadIdx.x;
+    double *m_sh = lds + 2 * kNMax;  // [kNMax]
+    if (tid < N) m_sh[tid] = m_old;
     double *a_sh = lds;          // [kNMax]
     double *c_sh = lds + kNMax;  // [kNMax]
     __shared__ int s_bad, s_zero;
@@ -130,7 +143,7 @@ __device__ void update_coefficients(const double *K, DevState *ds, const CoeffPa
                 rank += (aj < a || (aj == a && j < tid)) ? 1 : 0;
             }
             // ranks are a permutation of 0..N-1: every state entry has exactly one writer
-            const double mk = cp.beta * ds->m[rank] + (1.0 - cp.beta) * a;
+            const double mk = cp.beta * m_sh[rank] + (1.0 - cp.beta) * a;
             ds->m[rank] = mk;
             as = mk;
         }
@@ -185,8 +198,9 @@ __device__ void gram_tail(const GramTail &tail, double *lds) {
     __syncthreads();
     if (s_ticket != gridDim.x - 1) return;
     __threadfence();  // acquire: see every other workgroup's row
+    const double m_old = ((int)threadIdx.x < tail.cp.N) ? tail.ds->m[threadIdx.x] : 0.0;
     reduce_partial_rows(tail.partials, (int)gridDim.x, tail.cp.N, tail.K, lds);
-    if (tail.mode == kGramFinishCoeffs) update_coefficients(tail.K, tail.ds, tail.cp, lds);
+    if (tail.mode == kGramFinishCoeffs) update_coefficients(tail.K, tail.ds, tail.cp, lds, m_old);
     if (threadIdx.x == 0) tail.ds->blocks_done = 0;  // ready for the next launch on this stream
 }
 
@@ -211,50 +225,77 @@ __global__ void __launch_bounds__(kBlock) reduce_kernel(const double *partials, 
 // Reduction of the partial rows and (optionally) the coefficient update in one workgroup of
 // kFinishBlock threads, for N(N+1)/2 <= kFinishBlock: the launch between the two streaming passes.
 constexpr int kFinishBlock = 1024;
+constexpr int kFinishMaxN = 44;  // largest N with N(N+1)/2 <= kFinishBlock
 __global__ void __launch_bounds__(kFinishBlock)
 finish_kernel(const double *partials, int nrows, double *K, DevState *ds, CoeffParams cp, int with_coeffs) {
     __shared__ double lds[kFinishBlock];
-    reduce_partial_rows(partials, nrows, cp.N, K, lds);
-    if (with_coeffs) update_coefficients(K, ds, cp, lds);
+    __shared__ double K_lds[kFinishMaxN * kFinishMaxN];
+    const double m_old = ((int)threadIdx.x < cp.N) ? ds->m[threadIdx.x] : 0.0;
+    reduce_partial_rows(partials, nrows, cp.N, K, lds, K_lds);
+    if (with_coeffs) update_coefficients(K_lds, ds, cp, lds, m_old);
 }
 
 __global__ void __launch_bounds__(kBlock) coeff_kernel(const double *K, DevState *ds, CoeffParams cp) {
     __shared__ double lds[kBlock];
-    update_coefficients(K, ds, cp, lds);
+    const double m_old = ((int)threadIdx.x < cp.N) ? ds->m[threadIdx.x] : 0.0;
+    update_coefficients(K, ds, cp, lds, m_old);
+}
+
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8) and every XCD
+// has its own L2.  Rows of G are in general not aligned to a 128-byte line relative to each
+// other, so the line at the boundary of two neighbouring column segments is needed by two
+// workgroups; giving each XCD a contiguous run of segments makes those two share an L2.
+// Returns the segment (0 .. grid-1) workgroup b takes inside one sweep of the grid.
+__device__ __forceinline__ int xcd_contiguous_slot(int b, int grid) {
+    constexpr int kXcds = 8;
+    if (grid % kXcds) return b;
+    return (b % kXcds) * (grid / kXcds) + b / kXcds;
 }
 
 // ------------------------------------------------------------------------------------------
 // A1, N <= 8: fp64 register tile per thread
 // ------------------------------------------------------------------------------------------
+// One column group: N 128-bit loads, then N(N+1)/2 fp64 FMAs per column.
+template <int N, typename T, int VEC, bool NT>
+__device__ __forceinline__ void gram_vec_step(const T *__restrict__ G, int64_t d, int64_t g,
+                                              double (&acc)[N * (N + 1) / 2]) {
+    float v[N][VEC];
+#pragma unroll
+    for (int i = 0; i < N; ++i) load_vec<T, VEC, NT>(G + (int64_t)i * d + g * VEC, v[i]);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        double x[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) x[i] = (double)v[i][c];
+        int p = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int j = i; j < N; ++j) {
+                acc[p] = fma(x[i], x[j], acc[p]);
+                ++p;
+            }
+    }
+}
+
 template <int N, typename T, int VEC>
 __global__ void __launch_bounds__(kBlock, 2)
-gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, GramTail tail) {
+gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cached_groups, GramTail tail) {
     constexpr int NP = N * (N + 1) / 2;
     __shared__ double lds[(4 * NP > kBlock) ? 4 * NP : kBlock];
     double acc[NP];
 #pragma unroll
     for (int p = 0; p < NP; ++p) acc[p] = 0.0;
 
+    // The head of G is read with ordinary loads, so that it stays in the memory-side cache for
+    // the second pass (which starts there); the rest streams through with non-temporal loads.
+    // Two loops, so that the two kinds of load are not merged into one.
     const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < ngroups; g += stride) {
-        float v[N][VEC];
-#pragma unroll
-        for (int i = 0; i < N; ++i) load_vec<T, VEC>(G + (int64_t)i * d + g * VEC, v[i]);
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            double x[N];
-#pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = (double)v[i][c];
-            int p = 0;
-#pragma unroll
-            for (int i = 0; i < N; ++i)
-#pragma unroll
-                for (int j = i; j < N; ++j) {
-                    acc[p] = fma(x[i], x[j], acc[p]);
-                    ++p;
-                }
-        }
-    }
+    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
+    int64_t g = (int64_t)slot * kBlock + threadIdx.x;
+    const int64_t head_end = cached_groups < ngroups ? cached_groups : ngroups;
+    for (; g < head_end; g += stride) gram_vec_step<N, T, VEC, false>(G, d, g, acc);
+    for (; g < ngroups; g += stride) gram_vec_step<N, T, VEC, true>(G, d, g, acc);
 
     // workgroup sum: butterfly inside each wavefront, then the four wavefronts in order
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -306,7 +347,8 @@ gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, Gra
     // a chunk = kUnits * 16 consecutive columns, taken by one wavefront
     const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
     int since_flush = 0;
-    for (int64_t ch = (int64_t)blockIdx.x * (kBlock / kWave) + wave; ch < nchunks; ch += wstride) {
+    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
+    for (int64_t ch = (int64_t)slot * (kBlock / kWave) + wave; ch < nchunks; ch += wstride) {
         float v[kUnits][NT][4];
 #pragma unroll
         for (int u = 0; u < kUnits; ++u) {
@@ -436,8 +478,12 @@ static hipError_t run_vec(const void *G, int64_t d, const LaunchShape &shape, co
     const int64_t ngroups = (d + VEC - 1) / VEC;
     const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ, 1);
     *grid_out = grid;
+    // shape.cached_head_mb < 0: everything with ordinary loads
+    int64_t cached_groups = ngroups;
+    if (shape.cached_head_mb >= 0)
+        cached_groups = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
     hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC>), dim3(grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), d, ngroups, tail);
+                       static_cast<const T *>(G), d, ngroups, cached_groups, tail);
     return hipGetLastError();
 }
 
@@ -511,7 +557,7 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
     }
     if (e == hipSuccess && between) e = hipEventRecord(between, stream);
     if (e != hipSuccess || fused) return e;
-    if (num_pairs(N) <= kFinishBlock) {
+    if (N <= kFinishMaxN) {
         hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kFinishBlock), 0, stream, want.partials, grid, want.K,
                            want.ds, want.cp, want.mode == kGramFinishCoeffs ? 1 : 0);
         return hipGetLastError();

@@ -86,7 +86,11 @@ wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const
     }
     constexpr int64_t kTile = (int64_t)kBlock * UNR;
     const int64_t ntiles = (ngroups + kTile - 1) / kTile;
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    // each XCD (workgroup index % 8) takes a contiguous run of tiles inside one sweep of the grid,
+    // so that the 128-byte lines shared by neighbouring tiles are shared inside one L2
+    const int grid = (int)gridDim.x, b = (int)blockIdx.x;
+    const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;
+    for (int64_t t = slot; t < ntiles; t += gridDim.x) {
         // reverse: tiles in descending order, columns ascending inside a tile
         const int64_t tt = reverse ? (ntiles - 1 - t) : t;
         const int64_t base = tt * kTile + threadIdx.x;
