@@ -325,10 +325,62 @@ gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cac
 // MFMA per component contracts four columns that sit 4 apart -- any pairing is valid as long as
 // A and B use the same one.
 constexpr int kFlush = 8;   // 16-column steps between flushes of the fp32 tile sums into fp64
-constexpr int kUnits = 4;   // 16-column steps a wavefront loads back to back
+constexpr int kUnits = 4;   // 16-column steps a wavefront loads back to back (one chunk)
 
-template <int NT, typename T, int VEC4>
-__global__ void __launch_bounds__(kBlock, 2)
+// Load one chunk (kUnits * 16 columns of all NT row tiles) in operand layout.  Rows >= N and
+// columns >= d count as zero: the load itself goes to a clamped (valid) address and the value is
+// replaced afterwards, so that the loads stay free of branches and the waits on them exact.
+// STREAM: non-temporal loads.
+template <int NT, typename T, int VEC4, bool STREAM>
+__device__ __forceinline__ void mfma_load_chunk(const T *__restrict__ G, int N, int64_t d, int64_t ch, int r16,
+                                                int kq, float (&v)[kUnits][NT][4]) {
+#pragma unroll
+    for (int u = 0; u < kUnits; ++u) {
+        const int64_t col = (ch * kUnits + u) * 16 + kq * 4;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int row = t * 16 + r16;
+            const int rowc = row < N ? row : N - 1;
+            if constexpr (VEC4 != 0) {
+                // d is a multiple of the vector width here (>= 4 for fp32, >= 8 for bf16)
+                const bool live = row < N && col < d;
+                const int64_t colc = col < d ? col : d - 4;
+                const T *p = G + (int64_t)rowc * d + colc;
+                float w[4];
+                if constexpr (sizeof(T) == 4) {
+                    load_vec<float, 4, STREAM>(reinterpret_cast<const float *>(p), w);
+                } else {
+                    // 4 bf16 = one 64-bit load
+                    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 *q = reinterpret_cast<const u32x2 *>(p);
+                    u32x2 x;
+                    if constexpr (STREAM) x = __builtin_nontemporal_load(q); else x = *q;
+                    w[0] = __uint_as_float(x.x << 16);
+                    w[1] = __uint_as_float(x.x & 0xffff0000u);
+                    w[2] = __uint_as_float(x.y << 16);
+                    w[3] = __uint_as_float(x.y & 0xffff0000u);
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[u][t][c] = live ? w[c] : 0.f;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bool live = row < N && col + c < d;
+                    const int64_t colc = col + c < d ? col + c : d - 1;
+                    float one[1];
+                    load_vec<T, 1, STREAM>(G + (int64_t)rowc * d + colc, one);
+                    v[u][t][c] = live ? one[0] : 0.f;
+                }
+            }
+        }
+    }
+}
+
+// STREAM selects non-temporal loads (kept for measurement; the launcher uses ordinary loads).
+// The next chunk's loads are issued before the current chunk's MFMAs, so that the matrix
+// cores and the memory pipeline work at the same time even with one wavefront per SIMD.
+template <int NT, typename T, int VEC4, bool STREAM>
+__global__ void __launch_bounds__(kBlock, (NT >= 3) ? 1 : 2)
 gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, GramTail tail) {
     constexpr int NPT = NT * (NT + 1) / 2;
     __shared__ double lds[(NPT * 256 > kBlock) ? NPT * 256 : kBlock];
@@ -348,41 +400,13 @@ gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, Gra
     const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
     int since_flush = 0;
     const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
-    for (int64_t ch = (int64_t)slot * (kBlock / kWave) + wave; ch < nchunks; ch += wstride) {
-        float v[kUnits][NT][4];
-#pragma unroll
-        for (int u = 0; u < kUnits; ++u) {
-            const int64_t col = (ch * kUnits + u) * 16 + kq * 4;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int row = t * 16 + r16;
-                const T *p = G + (int64_t)row * d + col;
-                if constexpr (VEC4 != 0) {
-                    // d is a multiple of the vector width here, so col < d covers the 4 columns
-                    if (row < N && col < d) {
-                        if constexpr (sizeof(T) == 4) {
-                            load_vec<float, 4>(reinterpret_cast<const float *>(p), v[u][t]);
-                        } else {
-                            // 4 bf16 = one 64-bit load
-                            const uint2 x = *reinterpret_cast<const uint2 *>(p);
-                            v[u][t][0] = __uint_as_float(x.x << 16);
-                            v[u][t][1] = __uint_as_float(x.x & 0xffff0000u);
-                            v[u][t][2] = __uint_as_float(x.y << 16);
-                            v[u][t][3] = __uint_as_float(x.y & 0xffff0000u);
-                        }
-                    } else {
-                        v[u][t][0] = v[u][t][1] = v[u][t][2] = v[u][t][3] = 0.f;
-                    }
-                } else {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        float one[1] = {0.f};
-                        if (row < N && col + c < d) load_vec<T, 1>(p + c, one);
-                        v[u][t][c] = one[0];
-                    }
-                }
-            }
-        }
+    int64_t ch = (int64_t)slot * (kBlock / kWave) + wave;
+    float cur[kUnits][NT][4], nxt[kUnits][NT][4];
+    if (ch < nchunks) mfma_load_chunk<NT, T, VEC4, STREAM>(G, N, d, ch, r16, kq, cur);
+    while (ch < nchunks) {
+        const int64_t chn = ch + wstride;
+        // past the end the last chunk is simply loaded again (in bounds, never used)
+        mfma_load_chunk<NT, T, VEC4, STREAM>(G, N, d, chn < nchunks ? chn : nchunks - 1, r16, kq, nxt);
 #pragma unroll
         for (int u = 0; u < kUnits; ++u) {
 #pragma unroll
@@ -392,7 +416,7 @@ gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, Gra
                 for (int I = 0; I < NT; ++I)
 #pragma unroll
                     for (int J = I; J < NT; ++J) {
-                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[u][I][c], v[u][J][c], acc32[p], 0, 0, 0);
+                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur[u][I][c], cur[u][J][c], acc32[p], 0, 0, 0);
                         ++p;
                     }
             }
@@ -407,6 +431,13 @@ gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, Gra
                 acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         }
+#pragma unroll
+        for (int u = 0; u < kUnits; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) cur[u][t][c] = nxt[u][t][c];
+        ch = chn;
     }
 #pragma unroll
     for (int p = 0; p < NPT; ++p)
@@ -476,7 +507,8 @@ static hipError_t run_vec(const void *G, int64_t d, const LaunchShape &shape, co
                           int *grid_out) {
     static const int occ = occupancy(gram_vec_kernel<N, T, VEC>);
     const int64_t ngroups = (d + VEC - 1) / VEC;
-    const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ, 1);
+    // measured best: one workgroup per CU for fp32, two for bf16 (twice the FMAs per byte)
+    const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ, sizeof(T) == 2 ? 2 : 1);
     *grid_out = grid;
     // shape.cached_head_mb < 0: everything with ordinary loads
     int64_t cached_groups = ngroups;
@@ -503,18 +535,27 @@ static hipError_t dispatch_vec(const void *G, int N, int64_t d, const LaunchShap
     }
 }
 
-template <int NT, typename T, int VEC4>
-static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
-                           hipStream_t s, int *grid_out) {
-    static const int occ = occupancy(gram_mfma_kernel<NT, T, VEC4>);
+template <int NT, typename T, int VEC4, bool STREAM>
+static hipError_t run_mfma_as(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
+                              hipStream_t s, int *grid_out) {
+    static const int occ = occupancy(gram_mfma_kernel<NT, T, VEC4, STREAM>);
     const int64_t cols_per_chunk = 16 * kUnits;
     const int64_t nchunks = (d + cols_per_chunk - 1) / cols_per_chunk;
     const int waves = kBlock / kWave;
-    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, 2);
+    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, NT >= 3 ? 1 : 2);
     *grid_out = grid;
-    hipLaunchKernelGGL((gram_mfma_kernel<NT, T, VEC4>), dim3(grid), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL((gram_mfma_kernel<NT, T, VEC4, STREAM>), dim3(grid), dim3(kBlock), 0, s,
                        static_cast<const T *>(G), N, d, nchunks, tail);
     return hipGetLastError();
+}
+
+template <int NT, typename T, int VEC4>
+static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
+                           hipStream_t s, int *grid_out) {
+    // Ordinary loads only: one load instruction takes 64 contiguous bytes of each of 16 rows, so
+    // the other half of every 128-byte line is needed by the next instruction; non-temporal loads
+    // do not keep the line and measured 20 % slower here.
+    return run_mfma_as<NT, T, VEC4, false>(G, N, d, shape, tail, s, grid_out);
 }
 
 template <typename T, int VEC4>

@@ -130,7 +130,7 @@ static hipError_t dispatch(const void *G, int N, int64_t d, const LaunchShape &s
     switch (N) {
         case 4: return run<4, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
         case 8: return run<8, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
-        case 16: return run<16, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
+        case 16: return run<16, T, VEC, 1>(G, N, d, shape, gamma, out, reverse, s);  // 16 loads in flight already
         default: return run<0, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
     }
 }
