@@ -71,7 +71,8 @@ def main() -> int:
             "wsum_blocks_per_cu": ada.ADACONS_TUNE_WSUM_BLOCKS_PER_CU,
             "fuse_coeffs": ada.ADACONS_TUNE_FUSE_COEFFS,
             "reverse_second_pass": ada.ADACONS_TUNE_REVERSE_SECOND_PASS,
-            "cached_head_mb": ada.ADACONS_TUNE_CACHED_HEAD_MB}
+            "cached_head_mb": ada.ADACONS_TUNE_CACHED_HEAD_MB,
+            "mfma_direct_loads": ada.ADACONS_TUNE_MFMA_DIRECT_LOADS}
     tuned = {}
     for kv in args.tune:
         k, v = kv.split("=")

@@ -51,7 +51,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 1};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 
@@ -87,6 +87,7 @@ LaunchShape shape_of(const adacons_state *st, adacons_tune_key key) {
     s.max_rows = st->max_rows;
     const int head = st->tune[ADACONS_TUNE_CACHED_HEAD_MB];
     s.cached_head_mb = head >= (1 << 20) ? -1 : head;  // a huge value means all of G
+    s.mfma_direct = st->tune[ADACONS_TUNE_MFMA_DIRECT_LOADS];
     return s;
 }
 

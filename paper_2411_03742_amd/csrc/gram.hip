@@ -324,8 +324,46 @@ gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cac
 // columns (one 128-bit load): its component c belongs to column  base + 4 (l / 16) + c,  and one
 // MFMA per component contracts four columns that sit 4 apart -- any pairing is valid as long as
 // A and B use the same one.
-constexpr int kFlush = 8;   // 16-column steps between flushes of the fp32 tile sums into fp64
+// 16-column steps between flushes of the fp32 tile sums into fp64.  The matrix cores' fp32
+// accumulation rounds with a small systematic bias (measured ~2e-7 relative on a sum of squares
+// after 128 products, ~4e-7 after 256), so the fp32 chains are kept to 8 steps = 128 products.
+constexpr int kFlush = 8;
 constexpr int kUnits = 4;   // 16-column steps a wavefront loads back to back (one chunk)
+
+// Block-level end of an MFMA Gram kernel: add the four wavefronts' tile sums in order through LDS
+// (lds[(p * 4 + r) * 64 + lane], NT(NT+1)/2 * 256 doubles) and scatter them into this workgroup's
+// packed-upper-triangle row.  Lane l, register r of tile pair (I, J) holds
+// K[16 I + 4 (l / 16) + r][16 J + l % 16].
+template <int NT>
+__device__ __forceinline__ void mfma_store_partial_row(const double (&acc64)[NT * (NT + 1) / 2][4], double *lds, int N,
+                                                       double *row_out) {
+    constexpr int NPT = NT * (NT + 1) / 2;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (int w = 0; w < kBlock / kWave; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int p = 0; p < NPT; ++p)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int e = (p * 4 + r) * kWave + lane;
+                    lds[e] = (w == 0) ? acc64[p][r] : lds[e] + acc64[p][r];
+                }
+        }
+        __syncthreads();
+    }
+    for (int e = threadIdx.x; e < NPT * 256; e += kBlock) {
+        const int l = e & (kWave - 1), r = (e >> 6) & 3, p = e >> 8;
+        int I = 0, left = p;
+        while (left >= NT - I) {
+            left -= NT - I;
+            ++I;
+        }
+        const int J = I + left;
+        const int i = I * 16 + 4 * (l >> 4) + r;
+        const int j = J * 16 + (l & 15);
+        if (i < N && j < N && i <= j) row_out[pair_index(i, j, N)] = lds[e];
+    }
+}
 
 // Load one chunk (kUnits * 16 columns of all NT row tiles) in operand layout.  Rows >= N and
 // columns >= d count as zero: the load itself goes to a clamped (valid) address and the value is
@@ -444,36 +482,138 @@ gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, Gra
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
 
-    // add the four wavefronts in order through LDS: lds[(p * 4 + r) * 64 + lane]
-    for (int w = 0; w < kBlock / kWave; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int p = 0; p < NPT; ++p)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int e = (p * 4 + r) * kWave + lane;
-                    lds[e] = (w == 0) ? acc64[p][r] : lds[e] + acc64[p][r];
-                }
-        }
-        __syncthreads();
-    }
-    // scatter the tile sums into this workgroup's packed-upper-triangle row
-    const int np = num_pairs(N);
-    double *row_out = tail.partials + (size_t)blockIdx.x * np;
-    for (int e = threadIdx.x; e < NPT * 256; e += kBlock) {
-        const int l = e & (kWave - 1), r = (e >> 6) & 3, p = e >> 8;
-        int I = 0, left = p;
-        while (left >= NT - I) {
-            left -= NT - I;
-            ++I;
-        }
-        const int J = I + left;
-        const int i = I * 16 + 4 * (l >> 4) + r;
-        const int j = J * 16 + (l & 15);
-        if (i < N && j < N && i <= j) row_out[pair_index(i, j, N)] = lds[e];
-    }
+    mfma_store_partial_row<NT>(acc64, lds, N, tail.partials + (size_t)blockIdx.x * num_pairs(N));
     __syncthreads();
     gram_tail(tail, lds);
+}
+
+
+// ------------------------------------------------------------------------------------------
+// A1, 8 < N <= 64, 128-bit path: tiles staged through LDS
+// ------------------------------------------------------------------------------------------
+// The direct kernel above touches 16 rows with every load instruction and cycles through all
+// 16 NT rows sixteen times per 64 columns; with rows ~100 MB apart that thrashes the per-CU
+// address-translation cache (measured at N = 64: one miss per four requests).  Here the
+// workgroup stages a tile of 16 NT rows x kSegs KB per row in LDS: every load instruction reads
+// 1 KB of ONE row, fully coalesced, and each row is visited once per tile.  Then each wavefront
+// takes a quarter of the tile's columns and feeds the matrix cores from LDS (ds_read in operand
+// layout).  The 16-byte chunks of a tile row are XOR-swizzled with the row number so that the
+// column-wise operand reads hit distinct banks.  The next tile's global loads are in flight
+// while the current tile is multiplied.
+template <int NT> struct LdsTileShape {
+    static constexpr int kRows = 16 * NT;
+    static constexpr int kSegs = (NT == 1) ? 4 : (NT == 2) ? 2 : 1;   // 1 KB segments per tile row
+    static constexpr int kLoads = kRows * kSegs / (kBlock / kWave);   // load instructions per wavefront
+    static constexpr int kRowBytes = kSegs * 1024;
+    static constexpr int kTileBytes = kRows * kRowBytes;              // <= 64 KB
+};
+
+template <int NT, typename T>
+__global__ void __launch_bounds__(kBlock, (NT >= 4) ? 1 : 2)
+gram_mfma_lds_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ntiles, double *__restrict__ partials) {
+    typedef LdsTileShape<NT> S;
+    constexpr int NPT = NT * (NT + 1) / 2;
+    constexpr int kVec = 16 / (int)sizeof(T);                 // elements per 16-byte chunk
+    constexpr int kTileCols = S::kRowBytes / (int)sizeof(T);  // columns per tile
+    constexpr int kUnitsPerWave = kTileCols / 64;             // 16-column MFMA steps per wavefront and tile
+    static_assert(NPT * 256 * 8 <= S::kTileBytes, "the final reduction reuses the tile buffer");
+    __shared__ __attribute__((aligned(16))) unsigned char tile[S::kTileBytes];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int r16 = lane & 15, kq = lane >> 4;
+
+    f32x4 acc32[NPT];
+    double acc64[NPT][4];
+#pragma unroll
+    for (int p = 0; p < NPT; ++p) {
+        acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
+    }
+
+    // stage registers: load j of this wavefront covers tile row (wave * kLoads + j) / kSegs,
+    // segment (wave * kLoads + j) % kSegs, bytes [16 lane, 16 lane + 16) of that segment
+    u32x4 stage[S::kLoads];
+    auto load_tile = [&](int64_t t) {
+#pragma unroll
+        for (int j = 0; j < S::kLoads; ++j) {
+            const int idx = wave * S::kLoads + j;
+            const int row = idx / S::kSegs, seg = idx % S::kSegs;
+            const int64_t col = t * kTileCols + (int64_t)seg * (1024 / (int)sizeof(T)) + lane * kVec;
+            const bool live = row < N && col < d;   // d is a multiple of kVec on this path
+            const int rowc = row < N ? row : N - 1;
+            const int64_t colc = col < d ? col : d - kVec;
+            const u32x4 x = *reinterpret_cast<const u32x4 *>(G + (int64_t)rowc * d + colc);
+            stage[j] = live ? x : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+
+    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
+    int64_t t = slot;
+    int since_flush = 0;
+    if (t < ntiles) load_tile(t);
+    while (t < ntiles) {   // t is uniform over the workgroup: every thread takes the same trips
+#pragma unroll
+        for (int j = 0; j < S::kLoads; ++j) {
+            const int idx = wave * S::kLoads + j;
+            const int row = idx / S::kSegs, seg = idx % S::kSegs;
+            const int chunk = (seg * 64 + lane) ^ (row & 15);
+            *reinterpret_cast<u32x4 *>(tile + row * S::kRowBytes + chunk * 16) = stage[j];
+        }
+        __syncthreads();
+        const int64_t tn = t + gridDim.x;
+        load_tile(tn < ntiles ? tn : ntiles - 1);   // past the end: the last tile again, never used
+
+#pragma unroll
+        for (int u = 0; u < kUnitsPerWave; ++u) {
+            float v[NT][4];
+            const int col = wave * (kTileCols / 4) + u * 16 + kq * 4;   // first of this lane's 4 columns
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                const int row = tt * 16 + r16;
+                const int byte = col * (int)sizeof(T);
+                const int chunk = (byte >> 4) ^ (row & 15);
+                const unsigned char *src = tile + row * S::kRowBytes + chunk * 16 + (byte & 15);
+                if constexpr (sizeof(T) == 4) {
+                    const f32x4 x = *reinterpret_cast<const f32x4 *>(src);
+                    v[tt][0] = x.x; v[tt][1] = x.y; v[tt][2] = x.z; v[tt][3] = x.w;
+                } else {
+                    const uint2 x = *reinterpret_cast<const uint2 *>(src);
+                    v[tt][0] = __uint_as_float(x.x << 16);
+                    v[tt][1] = __uint_as_float(x.x & 0xffff0000u);
+                    v[tt][2] = __uint_as_float(x.y << 16);
+                    v[tt][3] = __uint_as_float(x.y & 0xffff0000u);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                int p = 0;
+#pragma unroll
+                for (int I = 0; I < NT; ++I)
+#pragma unroll
+                    for (int J = I; J < NT; ++J) {
+                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[I][c], v[J][c], acc32[p], 0, 0, 0);
+                        ++p;
+                    }
+            }
+            if (++since_flush == kFlush) {
+                since_flush = 0;
+#pragma unroll
+                for (int p = 0; p < NPT; ++p) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+                    acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        }
+        __syncthreads();   // all operand reads done before the tile buffer is overwritten
+        t = tn;
+    }
+#pragma unroll
+    for (int p = 0; p < NPT; ++p)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+    mfma_store_partial_row<NT>(acc64, reinterpret_cast<double *>(tile), N,
+                               partials + (size_t)blockIdx.x * num_pairs(N));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -549,9 +689,24 @@ static hipError_t run_mfma_as(const void *G, int N, int64_t d, const LaunchShape
     return hipGetLastError();
 }
 
+template <int NT, typename T>
+static hipError_t run_mfma_lds(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
+                               hipStream_t s, int *grid_out) {
+    const int64_t tile_cols = LdsTileShape<NT>::kRowBytes / (int64_t)sizeof(T);
+    const int64_t ntiles = (d + tile_cols - 1) / tile_cols;
+    const int grid = grid_for(ntiles, shape, NT >= 4 ? 1 : 2, NT >= 4 ? 1 : 2);   // 64 KB of LDS per workgroup
+    *grid_out = grid;
+    hipLaunchKernelGGL((gram_mfma_lds_kernel<NT, T>), dim3(grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N,
+                       d, ntiles, tail.partials);
+    return hipGetLastError();
+}
+
 template <int NT, typename T, int VEC4>
 static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                            hipStream_t s, int *grid_out) {
+    // the LDS-staged kernel needs the 128-bit path and leaves the reduction to a later launch
+    if (VEC4 != 0 && tail.mode == kGramPartialsOnly && shape.mfma_direct == 0)
+        return run_mfma_lds<NT, T>(G, N, d, shape, tail, s, grid_out);
     // Ordinary loads only: one load instruction takes 64 contiguous bytes of each of 16 rows, so
     // the other half of every 128-byte line is needed by the next instruction; non-temporal loads
     // do not keep the line and measured 20 % slower here.

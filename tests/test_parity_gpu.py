@@ -92,6 +92,20 @@ def test_gram_matches_oracle(pkg, N, d, dtype):
     agg.close()
 
 
+@pytest.mark.parametrize("N,d", [(12, 1024), (16, 4096 + 16), (24, 100_000), (40, 20_000), (64, 65_536 + 256)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_gram_lds_staged_variant_matches_oracle(pkg, N, d, dtype):
+    """The matrix-core kernel that stages coalesced tiles through LDS (tuning option)."""
+    G = randG(N, d, dtype, sigma=2.0, seed=N + d % 991)
+    agg = pkg.AdaCons(N, d)
+    agg.tune(pkg.ADACONS_TUNE_MFMA_DIRECT_LOADS, 0)
+    K = agg.gram(G)
+    Kref = o.gram(workloads.to_oracle_input(G))
+    scale = np.sqrt(np.outer(np.diag(Kref), np.diag(Kref)))
+    assert (np.abs(K - Kref) / scale).max() <= 3e-7
+    agg.close()
+
+
 def test_gram_distinct_rows_exact(pkg):
     """Small integers: every product and sum is exact in any precision, so a transposed tile or a
     wrong row/column mapping shows as an exact mismatch."""
@@ -208,6 +222,7 @@ def test_fused_and_separate_coefficient_update_agree(pkg, N):
         out = agg.aggregate(G)
         res.append((out.clone(), agg.coeffs()["gamma"]))
         agg.close()
+    # the same Gram kernel either way; only the order of the final row sums differs
     assert_gamma_close(res[0][1], res[1][1], 1e-12)
     assert rel_l2(res[0][0].cpu().numpy(), res[1][0].cpu().numpy()) <= 1e-6
 
