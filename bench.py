@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="REPS",
                     help="after the timed region, run REPS plain device copies of G (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled to bytes")
+    ap.add_argument("--layers", choices=["resnet50"], default=None,
+                    help="time the layer-wise entry point instead (C2 only): one coefficient set per "
+                         "parameter tensor of a ResNet-50; not the headline metric")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass / cached_head_mb")
     args = ap.parse_args()
@@ -66,6 +69,8 @@ def main() -> int:
     for G in workloads.stream(w.scaled(w.d, 2), dev):
         bufs.append(G.clone())
     out = torch.empty(w.d, dtype=torch.float32, device=dev)
+    if args.layers:
+        return bench_layers(args, w, bufs, out)
     agg = ada.AdaCons(w.N, w.d, beta=0.99)
     keys = {"gram_blocks_per_cu": ada.ADACONS_TUNE_GRAM_BLOCKS_PER_CU,
             "wsum_blocks_per_cu": ada.ADACONS_TUNE_WSUM_BLOCKS_PER_CU,
@@ -150,6 +155,44 @@ def main() -> int:
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+    agg.close()
+    return 0
+
+
+def bench_layers(args, w, bufs, out) -> int:
+    """Layer-wise aggregation over the 161 parameter tensors of a ResNet-50 (same bytes as C2)."""
+    import numpy as np
+    import torch
+    import workloads
+    import paper_2411_03742_amd as ada
+
+    if args.workload != "C2":
+        print("bench.py: --layers resnet50 goes with --workload C2", file=sys.stderr)
+        return 2
+    off = np.concatenate([[0], np.cumsum(workloads.resnet50_layer_sizes())]).astype(np.int64)
+    agg = ada.AdaConsLayers(w.N, off, beta=0.99)
+    stream = torch.cuda.current_stream()
+    for i in range(args.warmup):
+        agg.aggregate(bufs[i % 2], out=out, stream=stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(args.steps):
+        agg.aggregate(bufs[i % 2], out=out, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / args.steps
+    gam = agg.coeffs()["gamma"]
+    assert np.abs(gam.sum(axis=1) - 1.0).max() < 1e-6
+    gbps = w.floor_bytes / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "layer-wise aggregation effective HBM bandwidth (N=%d, d=%d, %s, %d layers)" % (w.N, w.d, w.dtype, len(off) - 1),
+        "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s cut into the 161 parameter tensors of a ResNet-50, layer-wise coefficients" % w.name},
+        "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2), "roofline": None, "cpu_baseline": None}))
     agg.close()
     return 0
 

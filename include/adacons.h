@@ -186,6 +186,47 @@ adacons_status adacons_profile_begin(adacons_state *st, int max_calls);
 adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *coeff_ms, double *wsum_ms,
                                    int *calls, void *hip_stream);
 
+/*
+ * ---- Layer-wise aggregation --------------------------------------------------------------
+ * Sec. 4 of the paper computes the aggregation model-wise and notes that layer-wise aggregation
+ * performs similarly.  Here the d columns are split into L contiguous segments ("layers"); every
+ * layer gets its own Gram matrix, its own coefficients and its own Eq. 11 momentum state, i.e. the
+ * steps A1-A3 above run independently on G[:, offsets[l] : offsets[l+1]) for every l, in three
+ * launches for all layers together.  Supported for N <= 8 on the 128-bit path.
+ */
+typedef struct adacons_layers adacons_layers; /* opaque, library-owned */
+
+/*
+ * Build the per-layer state (L zero-initialised momentum vectors, tile tables, workspaces) on the
+ * current device.  Allocates; synchronises `hip_stream` once.
+ *   ls            out: receives the handle
+ *   N             workers, 1 <= N <= 8
+ *   L             number of layers, >= 1
+ *   offsets_host  host pointer, L + 1 ascending column offsets, offsets[0] = 0, offsets[L] = d;
+ *                 empty layers (equal consecutive offsets) are not allowed
+ *   dtype         element type later calls will pass (fixes the tile geometry)
+ *   beta, flags   as in adacons_init_state
+ * Errors: EINVAL, EUNSUPPORTED (N > 8), ENOMEM, EHIP.
+ */
+adacons_status adacons_init_layers(adacons_layers **ls, int N, int L, const int64_t *offsets_host,
+                                   adacons_dtype dtype, double beta, unsigned flags, void *hip_stream);
+adacons_status adacons_destroy_layers(adacons_layers *ls);
+
+/*
+ * One layer-wise aggregation: out[k] = sum_i gamma[layer(k)][i] G[i][k].  Asynchronous, allocates
+ * nothing.  G, N, d, dtype, out as in adacons_aggregate, with d == offsets[L] and dtype as given at
+ * init; G and out must be 16-byte aligned and d * sizeof(elem) a multiple of 16 (else EALIGN).
+ */
+adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons_dtype dtype,
+                                        adacons_layers *ls, float *out, void *hip_stream);
+
+/*
+ * Coefficients of the most recent adacons_aggregate_layers(): L x N doubles each, row l = layer l.
+ * raw_host, smoothed_host, numeric_flags (L words) may be NULL.  Synchronises the stream.
+ */
+adacons_status adacons_layer_coeffs(const adacons_layers *ls, double *gamma_host, double *raw_host,
+                                    double *smoothed_host, uint32_t *numeric_flags, void *hip_stream);
+
 const char *adacons_status_string(adacons_status s);
 const char *adacons_last_error(void);
 

@@ -165,3 +165,24 @@ def aggregate(G, state: OracleState, want_out: bool = True) -> tuple[np.ndarray 
     info = coefficients(gram(G), state)
     out = weighted_sum(G, info["gamma"]) if want_out else None
     return out, info
+
+
+def aggregate_layers(G, offsets, states: list, want_out: bool = True):
+    """Layer-wise aggregation (Sec. 4 of the paper): steps O1-O7 applied independently to every
+    contiguous column segment G[:, offsets[l]:offsets[l+1]], each with its own state.
+    Returns (out or None, list of per-layer info dicts)."""
+    G = np.asarray(G)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    L = offsets.shape[0] - 1
+    if len(states) != L:
+        raise ValueError("one OracleState per layer")
+    out = np.empty(G.shape[1], dtype=np.float64) if want_out else None
+    infos = []
+    for l in range(L):
+        a, b = int(offsets[l]), int(offsets[l + 1])
+        seg = np.ascontiguousarray(G[:, a:b])
+        o_l, info = aggregate(seg, states[l], want_out=want_out)
+        if want_out:
+            out[a:b] = o_l
+        infos.append(info)
+    return out, infos

@@ -32,6 +32,7 @@ EXPORTS = [
     "adacons_coeffs", "adacons_gram", "adacons_read_gram", "adacons_weighted_sum",
     "adacons_state_export", "adacons_state_import", "adacons_tune", "adacons_profile_begin",
     "adacons_profile_end", "adacons_status_string", "adacons_last_error",
+    "adacons_init_layers", "adacons_destroy_layers", "adacons_aggregate_layers", "adacons_layer_coeffs",
 ]
 
 
@@ -64,6 +65,10 @@ def _load() -> ctypes.CDLL:
         "adacons_tune": [vp, i32, i32],
         "adacons_profile_begin": [vp, i32],
         "adacons_profile_end": [vp, dp, dp, dp, ctypes.POINTER(i32), vp],
+        "adacons_init_layers": [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(i64), i32, dbl, u32, vp],
+        "adacons_destroy_layers": [vp],
+        "adacons_aggregate_layers": [vp, i32, i64, i32, vp, vp, vp],
+        "adacons_layer_coeffs": [vp, dp, dp, dp, ctypes.POINTER(ctypes.c_uint32), vp],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -197,7 +202,71 @@ def adacons_profile_end(st, stream=None) -> dict:
     return {"gram_ms": g.value, "coeff_ms": c.value, "wsum_ms": w.value, "calls": n.value}
 
 
-# ---- a small convenience wrapper that owns a state ----------------------------------------
+def adacons_init_layers(N: int, offsets, dtype: int, beta: float = 0.99, flags: int = ADACONS_FLAG_DEFAULT,
+                        stream=None) -> ctypes.c_void_p:
+    off = np.ascontiguousarray(offsets, dtype=np.int64)
+    ls = ctypes.c_void_p()
+    _check(_lib.adacons_init_layers(ctypes.byref(ls), N, off.shape[0] - 1,
+                                    off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), dtype, beta, flags,
+                                    _stream(stream)), "adacons_init_layers")
+    return ls
+
+
+def adacons_destroy_layers(ls) -> None:
+    _check(_lib.adacons_destroy_layers(ls), "adacons_destroy_layers")
+
+
+def adacons_aggregate_layers(G: torch.Tensor, ls, out: torch.Tensor, stream=None) -> None:
+    g, N, d, dt = _matrix(G)
+    if out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous() or out.numel() != d:
+        raise ValueError("out must be a contiguous float32 device tensor of d elements")
+    _check(_lib.adacons_aggregate_layers(g, N, d, dt, ls, ctypes.c_void_p(out.data_ptr()), _stream(stream)),
+           "adacons_aggregate_layers")
+
+
+def adacons_layer_coeffs(ls, N: int, L: int, stream=None) -> dict:
+    gamma, raw, smooth = np.empty((L, N)), np.empty((L, N)), np.empty((L, N))
+    nf = np.zeros(L, dtype=np.uint32)
+    _check(_lib.adacons_layer_coeffs(ls, _dptr(gamma), _dptr(raw), _dptr(smooth),
+                                     nf.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _stream(stream)),
+           "adacons_layer_coeffs")
+    return {"gamma": gamma, "raw": raw, "smoothed": smooth, "numeric_flags": nf}
+
+
+# ---- small convenience wrappers that own a state ------------------------------------------
+class AdaConsLayers:
+    """Layer-wise aggregation: one coefficient stream per contiguous column segment (N <= 8)."""
+
+    def __init__(self, N: int, offsets, dtype: torch.dtype = torch.float32, beta: float = 0.99,
+                 flags: int = ADACONS_FLAG_DEFAULT, stream=None):
+        self.N = int(N)
+        self.offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        self.L = int(self.offsets.shape[0] - 1)
+        dt = ADACONS_BF16 if dtype == torch.bfloat16 else ADACONS_F32
+        self._ls = adacons_init_layers(self.N, self.offsets, dt, beta, flags, stream)
+
+    def close(self) -> None:
+        if getattr(self, "_ls", None):
+            adacons_destroy_layers(self._ls)
+            self._ls = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def aggregate(self, G: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty(G.shape[1], dtype=torch.float32, device=G.device)
+        adacons_aggregate_layers(G, self._ls, out, stream)
+        return out
+
+    def coeffs(self, stream=None) -> dict:
+        return adacons_layer_coeffs(self._ls, self.N, self.L, stream)
+
+
+
 class AdaCons:
     """One coefficient stream (Eq. 11 state) for N workers; thin owner of an adacons_state."""
 

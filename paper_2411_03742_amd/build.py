@@ -9,8 +9,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 LIB_PATH = os.path.join(_PKG, "libadacons.so")
-SOURCES = ["api.hip", "gram.hip", "wsum.hip"]
-HEADERS = ["adacons_internal.h", "device_util.h"]
+SOURCES = ["api.hip", "gram.hip", "wsum.hip", "layers.hip"]
+HEADERS = ["adacons_internal.h", "device_util.h", "coeff_device.h"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -67,6 +67,9 @@ hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStre
 int gram_rows_needed(int N, int num_cu);
 hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t stream);  // K may be NULL
 
+// api.hip: record the thread-local text adacons_last_error() returns; gives back `s`
+adacons_status set_error(adacons_status s, const char *fmt, ...);
+
 // wsum.hip
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const float *gamma, float *out, bool reverse,

@@ -105,6 +105,14 @@ GramTail tail_of(adacons_state *st, int mode) {
 
 }  // namespace
 
+adacons_status adacons::set_error(adacons_status s, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
 extern "C" {
 
 const char *adacons_status_string(adacons_status s) {

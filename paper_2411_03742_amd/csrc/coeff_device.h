@@ -1,0 +1,119 @@
+// Stage A2 as a device function shared by every kernel that ends in a coefficient update.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "adacons_internal.h"
+
+namespace adacons {
+
+// Stage A2.  One workgroup (at least kNMax threads); thread i < N is worker i.  fp64 throughout.
+//   q_i = K_ii, r_i = sum_j K_ij                      (||g_i||^2 and N <g_i, gbar>)
+//   a_i = r_i / (N sqrt(q_i))                          Eq. 7, positive for a descent direction
+//   rank_i = #{j : a_j < a_i or (a_j = a_i and j < i)} ascending, ties to the lower index
+//   m[rank_i] <- beta m[rank_i] + (1 - beta) a_i ; a~_i = m[rank_i]      Eq. 11
+//   c_i = a~_i / sqrt(q_i)                             column normalisation, Eq. 8
+//   gamma_i = c_i / sum_k c_k                          Eq. 12-13 (weights sum to one)
+// Degenerate inputs: q_i = 0 gives a_i = c_i = 0; NaN/Inf in q or r, or |sum c| <= 1e-12 sum|c|,
+// gives gamma_i = 1/N; the EMA state is not touched when a statistic is non-finite.
+// m_old: the state entry m[tid] loaded by the caller ahead of time (thread tid < N), so that the
+// global-memory latency of the state overlaps the reduction; it is exchanged through LDS.
+__device__ inline void update_coefficients(const double *K, DevState *ds, const CoeffParams cp, double *lds,
+                                    double m_old) {
+    const int N = cp.N;
+    const int tid = threadIdx.x;
+    double *m_sh = lds + 2 * kNMax;  // [kNMax]
+    if (tid < N) m_sh[tid] = m_old;
+    double *a_sh = lds;          // [kNMax]
+    double *c_sh = lds + kNMax;  // [kNMax]
+    __shared__ int s_bad, s_zero;
+    __shared__ double s_sum, s_abs;
+    if (tid == 0) {
+        s_bad = 0;
+        s_zero = 0;
+    }
+    __syncthreads();
+
+    double q = 0.0, r = 0.0, a = 0.0;
+    if (tid < N) {
+        q = K[(size_t)tid * N + tid];
+        for (int j = 0; j < N; ++j) r += K[(size_t)tid * N + j];
+        if (!isfinite(q) || !isfinite(r)) atomicOr(&s_bad, 1);
+    }
+    __syncthreads();
+    const bool finite = (s_bad == 0);
+    if (tid < N) {
+        if (q > 0.0) {
+            a = r / ((double)N * sqrt(q));
+        } else {
+            a = 0.0;
+            if (finite) atomicOr(&s_zero, 1);
+        }
+        a_sh[tid] = a;
+    }
+    __syncthreads();
+
+    unsigned nf = 0;
+    if (!finite) {
+        nf = ADACONS_NUM_NONFINITE | ADACONS_NUM_UNIFORM_FALLBACK;
+        if (tid < N) {
+            const double g = 1.0 / (double)N;
+            ds->gamma[tid] = g;
+            ds->gamma32[tid] = (float)g;
+            ds->a_raw[tid] = a;
+            ds->a_smooth[tid] = a;
+        }
+    } else {
+        if (s_zero) nf |= ADACONS_NUM_ZERO_NORM;
+        double as = a;
+        if ((cp.flags & ADACONS_FLAG_MOMENTUM) && tid < N) {
+            int rank = 0;
+            for (int j = 0; j < N; ++j) {
+                const double aj = a_sh[j];
+                rank += (aj < a || (aj == a && j < tid)) ? 1 : 0;
+            }
+            // ranks are a permutation of 0..N-1: every state entry has exactly one writer
+            const double mk = cp.beta * m_sh[rank] + (1.0 - cp.beta) * a;
+            ds->m[rank] = mk;
+            as = mk;
+        }
+        double c = 0.0;
+        if (tid < N) {
+            c = (q > 0.0) ? as / sqrt(q) : 0.0;
+            c_sh[tid] = c;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double s = 0.0, sabs = 0.0;
+            for (int i = 0; i < N; ++i) {
+                s += c_sh[i];
+                sabs += fabs(c_sh[i]);
+            }
+            s_sum = s;
+            s_abs = sabs;
+        }
+        __syncthreads();
+        double g = c;
+        if (cp.flags & ADACONS_FLAG_NORMALIZE) {
+            const double s = s_sum, sabs = s_abs;
+            if (!isfinite(s) || sabs == 0.0 || fabs(s) <= 1e-12 * sabs) {
+                nf |= ADACONS_NUM_UNIFORM_FALLBACK;
+                g = 1.0 / (double)N;
+            } else {
+                g = c / s;
+            }
+        }
+        if (tid < N) {
+            ds->gamma[tid] = g;
+            ds->gamma32[tid] = (float)g;
+            ds->a_raw[tid] = a;
+            ds->a_smooth[tid] = as;
+        }
+    }
+    if (tid == 0) {
+        ds->numeric_flags = nf;
+        ds->step += 1ull;
+    }
+}
+
+}  // namespace adacons

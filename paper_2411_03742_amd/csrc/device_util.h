@@ -70,4 +70,42 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+// Sums NP per-lane values over the 64 lanes of a wavefront by recursive halving: in the step with
+// lane distance 32, 16, ..., 1 a lane keeps the values whose index has the same parity as its
+// lane bit and sends the others to its partner, so the number of values halves each step
+// (NP/2 + NP/4 + ... exchanges instead of 6 NP).  Afterwards lane l holds the total of value
+// index bitrev6(l) -- wave_scatter_index(l) -- when that is < NP, and 0 otherwise.  The order of
+// the additions is fixed, so results are reproducible.
+__device__ __forceinline__ int wave_scatter_index(int lane) {
+    return ((lane >> 5) & 1) | (((lane >> 4) & 1) << 1) | (((lane >> 3) & 1) << 2) | (((lane >> 2) & 1) << 3) |
+           (((lane >> 1) & 1) << 4) | ((lane & 1) << 5);
+}
+
+template <int M, int DIST>
+__device__ __forceinline__ double wave_reduce_scatter_step(const double (&in)[M], int lane) {
+    constexpr int H = (M + 1) / 2;
+    const bool odd = (lane & DIST) != 0;
+    double out[H];
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+        const double lo = in[2 * k];
+        const double hi = (2 * k + 1 < M) ? in[2 * k + 1] : 0.0;
+        const double keep = odd ? hi : lo;
+        const double send = odd ? lo : hi;
+        out[k] = keep + __shfl_xor(send, DIST, 64);
+    }
+    if constexpr (DIST == 1) {
+        static_assert(H == 1, "at most 64 values per wavefront");
+        return out[0];
+    } else {
+        return wave_reduce_scatter_step<H, DIST / 2>(out, lane);
+    }
+}
+
+template <int NP>
+__device__ __forceinline__ double wave_reduce_scatter(const double (&v)[NP], int lane) {
+    static_assert(NP <= 64, "one value per lane at the end");
+    return wave_reduce_scatter_step<NP, 32>(v, lane);
+}
+
 }  // namespace adacons

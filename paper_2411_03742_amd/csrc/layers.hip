@@ -1,0 +1,406 @@
+// Layer-wise AdaCons aggregation (Sec. 4 of the paper: "layer-wise aggregation presents similar
+// performance"): steps A1-A3 run independently on every contiguous column segment of G, with one
+// coefficient set and one Eq. 11 momentum state per layer -- in three launches for all layers.
+//
+// Every layer is cut into runs of at most kRunGroups column groups (one group = one 128-bit load per
+// row); a run never crosses a layer boundary.  Layer boundaries need not be multiples of the group
+// width: the group that straddles two layers belongs to a run of each, and the columns that
+// belong to the other layer are masked (zeroed in A1, not stored in A3).
+//   A1  workgroups take runs from a ticket counter in column order (so that at any time all
+//       workgroups read one compact window of every row, and long and short runs balance out).
+//       Inside a run the N(N+1)/2 fp64 sums stay in registers; one partial row is written per
+//       run, indexed by the run, so the result does not depend on which workgroup took which run.
+//       Runs are numbered in column order, so the runs of one layer are consecutive.  The loop
+//       ends when the ticket passes the last run: no workgroup ever waits for another.
+//   A2  one workgroup per layer adds that layer's partial rows in a fixed order and runs the
+//       coefficient update on the layer's own state.
+//   A3  grid-stride over the runs; the run's layer selects the weights.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "adacons_internal.h"
+#include "coeff_device.h"
+#include "device_util.h"
+
+namespace adacons {
+
+struct LayerRun {
+    int64_t g0;      // first column group (group = VEC columns)
+    int64_t cb, ce;  // the layer's column range [cb, ce)
+    int n;           // groups in this run, 1..kRunGroups
+    int layer;
+};
+
+constexpr int kLayersMaxN = 8;
+constexpr int kRunGroups = 16 * kBlock;   // column groups per run: 16 sweeps of a workgroup
+
+// ------------------------------------------------------------------------------------------
+// A1
+// ------------------------------------------------------------------------------------------
+// N 128-bit loads of column group g and the N(N+1)/2 fp64 FMAs per column; columns outside
+// [cb, ce) (the other layer's part of a straddling group) count as zero.
+template <int N, typename T, int VEC, bool EDGE>
+__device__ __forceinline__ void gram_layers_step(const T *__restrict__ G, int64_t d, int64_t g, int64_t cb, int64_t ce,
+                                                 double (&acc)[N * (N + 1) / 2]) {
+    const int64_t c0 = g * VEC;
+    float v[N][VEC];
+#pragma unroll
+    for (int i = 0; i < N; ++i) load_vec<T, VEC, false>(G + (int64_t)i * d + c0, v[i]);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        const bool live = !EDGE || (c0 + c >= cb && c0 + c < ce);
+        double x[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) x[i] = live ? (double)v[i][c] : 0.0;
+        int p = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int j = i; j < N; ++j) {
+                acc[p] = fma(x[i], x[j], acc[p]);
+                ++p;
+            }
+    }
+}
+
+template <int N, typename T, int VEC>
+__global__ void __launch_bounds__(kBlock, 2)
+gram_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restrict__ runs, int nruns,
+                   const int *__restrict__ order, unsigned *__restrict__ ticket, double *__restrict__ partials) {
+    constexpr int NP = N * (N + 1) / 2;
+    __shared__ double lds[4 * NP];
+    __shared__ unsigned s_next;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);
+    __syncthreads();
+    unsigned tk = s_next;
+    while (tk < (unsigned)nruns) {   // tk is workgroup-uniform
+        __syncthreads();             // everyone has read s_next
+        if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);   // next ticket: in flight during this run
+        const int r = order[tk];
+        const LayerRun run = runs[r];
+        double acc[NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) acc[p] = 0.0;
+        const int64_t g_end = run.g0 + run.n;
+        // only the first and the last group of a run can straddle a layer boundary
+        for (int64_t g = run.g0 + threadIdx.x; g < g_end; g += kBlock) {
+            if (g == run.g0 || g == g_end - 1)
+                gram_layers_step<N, T, VEC, true>(G, d, g, run.cb, run.ce, acc);
+            else
+                gram_layers_step<N, T, VEC, false>(G, d, g, run.cb, run.ce, acc);
+        }
+        // workgroup sum in a fixed order into this run's partial row
+        {
+            const double tot = wave_reduce_scatter<NP>(acc, lane);
+            const int p = wave_scatter_index(lane);
+            if (p < NP) lds[wave * NP + p] = tot;
+        }
+        __syncthreads();
+        if (threadIdx.x < NP) {
+            const int p = threadIdx.x;
+            partials[(size_t)r * NP + p] = ((lds[p] + lds[NP + p]) + lds[2 * NP + p]) + lds[3 * NP + p];
+        }
+        tk = s_next;   // written by thread 0 before the barrier above
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// A2: one workgroup per layer
+// ------------------------------------------------------------------------------------------
+constexpr int kLayerFinishBlock = 1024;
+__global__ void __launch_bounds__(kLayerFinishBlock)
+finish_layers_kernel(const double *__restrict__ partials, const int *__restrict__ layer_entry0, double *K_all,
+                     DevState *ds_all, CoeffParams cp, unsigned *ticket) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;   // A1 is over: ready for the next call
+    __shared__ double lds[4 * kNMax];
+    __shared__ double K_lds[kLayersMaxN * kLayersMaxN];
+    const int l = blockIdx.x, N = cp.N, np = num_pairs(N);
+    DevState *ds = ds_all + l;
+    const double m_old = ((int)threadIdx.x < N) ? ds->m[threadIdx.x] : 0.0;
+    const int e0 = layer_entry0[l], e1 = layer_entry0[l + 1];
+    // interleaved sub-sums over this layer's entries (entry order inside a slice), then the slices in order
+    __shared__ double slice_sum[kLayerFinishBlock];
+    const int slices = kLayerFinishBlock / np, sl = (int)threadIdx.x / np, pp = (int)threadIdx.x - sl * np;
+    if (sl < slices) {
+        double acc = 0.0;
+        for (int e = e0 + sl; e < e1; e += slices) acc += partials[(size_t)e * np + pp];
+        slice_sum[sl * np + pp] = acc;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < np) {
+        const int p = threadIdx.x;
+        double tot = 0.0;
+        for (int q = 0; q < slices; ++q) tot += slice_sum[q * np + p];
+        int i = 0, left = p;
+        while (left >= N - i) {
+            left -= N - i;
+            ++i;
+        }
+        const int j = i + left;
+        double *K = K_all + (size_t)l * N * N;
+        K[i * N + j] = tot;
+        K[j * N + i] = tot;
+        K_lds[i * N + j] = tot;
+        K_lds[j * N + i] = tot;
+    }
+    __syncthreads();
+    update_coefficients(K_lds, ds, cp, lds, m_old);
+}
+
+// ------------------------------------------------------------------------------------------
+// A3
+// ------------------------------------------------------------------------------------------
+template <int N, typename T, int VEC>
+__global__ void __launch_bounds__(kBlock)
+wsum_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restrict__ runs, int nruns,
+                   const int64_t *__restrict__ offsets, const DevState *__restrict__ ds_all, float *__restrict__ out) {
+    // a run is split into kWsumSplit pieces, each taken by one workgroup sweep
+    constexpr int kWsumSplit = 8, kPiece = kRunGroups / kWsumSplit;
+    const int grid = (int)gridDim.x, b = (int)blockIdx.x;
+    const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;   // XCD-contiguous pieces
+    const int64_t npieces = (int64_t)nruns * kWsumSplit;
+    for (int64_t pc = slot; pc < npieces; pc += grid) {
+        const LayerRun run = runs[pc / kWsumSplit];
+        const int first = (int)(pc % kWsumSplit) * kPiece;
+        if (first >= run.n) continue;
+        const int last = (first + kPiece < run.n) ? first + kPiece : run.n;
+        const float *gam = ds_all[run.layer].gamma32;
+        float w[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) w[i] = gam[i];
+        const int64_t cb = run.cb, ce = run.ce;
+        for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
+            const int64_t c0 = (run.g0 + k) * VEC;
+            float v[N][VEC];
+#pragma unroll
+            for (int i = 0; i < N; ++i) load_vec<T, VEC, true>(G + (int64_t)i * d + c0, v[i]);
+            float acc[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w[i], v[i][c], acc[c]);
+            if (c0 >= cb && c0 + VEC <= ce) {
+#pragma unroll
+                for (int c = 0; c < VEC; c += 4) {
+                    const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+                    __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + c0 + c));
+                }
+            } else {
+                // group shared with a neighbouring layer: store only this layer's columns
+#pragma unroll
+                for (int c = 0; c < VEC; ++c)
+                    if (c0 + c >= cb && c0 + c < ce) out[c0 + c] = acc[c];
+            }
+        }
+    }
+}
+
+template <int N, typename T, int VEC>
+static hipError_t run_layers(const void *G, int64_t d, const LayerRun *runs, int nruns, const int *order, int gram_grid, int wsum_grid,
+                             const int64_t *offsets, const int *layer_entry0, int L, double *partials, double *K_all,
+                             DevState *ds_all, unsigned *ticket, CoeffParams cp, float *out, hipStream_t s) {
+    hipLaunchKernelGGL((gram_layers_kernel<N, T, VEC>), dim3(gram_grid), dim3(kBlock), 0, s,
+                       static_cast<const T *>(G), d, runs, nruns, order, ticket, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(finish_layers_kernel, dim3(L), dim3(kLayerFinishBlock), 0, s, partials, layer_entry0, K_all,
+                       ds_all, cp, ticket);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((wsum_layers_kernel<N, T, VEC>), dim3(wsum_grid), dim3(kBlock), 0, s,
+                       static_cast<const T *>(G), d, runs, nruns, offsets, ds_all, out);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC, typename... A>
+static hipError_t dispatch_layers(int N, A... a) {
+    switch (N) {
+        case 1: return run_layers<1, T, VEC>(a...);
+        case 2: return run_layers<2, T, VEC>(a...);
+        case 3: return run_layers<3, T, VEC>(a...);
+        case 4: return run_layers<4, T, VEC>(a...);
+        case 5: return run_layers<5, T, VEC>(a...);
+        case 6: return run_layers<6, T, VEC>(a...);
+        case 7: return run_layers<7, T, VEC>(a...);
+        case 8: return run_layers<8, T, VEC>(a...);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace adacons
+
+using namespace adacons;
+
+struct adacons_layers {
+    int N, L;
+    int64_t d;
+    adacons_dtype dtype;
+    double beta;
+    unsigned flags;
+    int nruns, gram_grid, wsum_grid;
+    LayerRun *runs;       // device, nruns
+    int64_t *offsets;     // device, L + 1
+    int *layer_entry0;    // device, L + 1
+    double *partials;     // device, nruns x N(N+1)/2
+    double *K;            // device, L x N x N
+    DevState *ds;         // device, L
+    unsigned *ticket;     // device: run counter of stage A1, zero between calls
+    int *order;           // device, nruns: ticket -> run (full-length runs in column order, then the
+                          // shorter ones, longest first, so that the sweep ends on small pieces)
+};
+
+namespace {
+adacons_status lfail(adacons_status s, const char *msg) { return set_error(s, "%s", msg); }
+}  // namespace
+
+extern "C" {
+
+adacons_status adacons_destroy_layers(adacons_layers *ls) {
+    if (!ls) return ADACONS_OK;
+    void *bufs[] = {ls->runs, ls->offsets, ls->layer_entry0, ls->partials, ls->K, ls->ds, ls->ticket, ls->order};
+    for (void *p : bufs)
+        if (p) (void)hipFree(p);
+    delete ls;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const int64_t *offsets_host,
+                                   adacons_dtype dtype, double beta, unsigned flags, void *hip_stream) {
+    if (!out_ls) return lfail(ADACONS_EINVAL, "ls is NULL");
+    *out_ls = nullptr;
+    if (!offsets_host) return lfail(ADACONS_EINVAL, "offsets_host is NULL");
+    if (N < 1 || L < 1) return lfail(ADACONS_EINVAL, "N < 1 or L < 1");
+    if (N > kLayersMaxN) return lfail(ADACONS_EUNSUPPORTED, "layer-wise aggregation supports N <= 8");
+    if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return lfail(ADACONS_EUNSUPPORTED, "unknown dtype");
+    if (!(beta >= 0.0 && beta < 1.0)) return lfail(ADACONS_EINVAL, "beta outside [0, 1)");
+    if (flags & ~ADACONS_FLAG_DEFAULT) return lfail(ADACONS_EINVAL, "unknown flag bits");
+    if (offsets_host[0] != 0) return lfail(ADACONS_EINVAL, "offsets[0] must be 0");
+    for (int l = 0; l < L; ++l)
+        if (offsets_host[l + 1] <= offsets_host[l]) return lfail(ADACONS_EINVAL, "offsets must ascend strictly");
+    if (L > (1 << 20)) return lfail(ADACONS_EINVAL, "too many layers");
+
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+        return lfail(ADACONS_EHIP, "no HIP device");
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return lfail(ADACONS_EUNSUPPORTED, "built for gfx950 only");
+
+    const int vec = dtype == ADACONS_BF16 ? 8 : 4;
+    // runs: per layer, the groups that contain any of its columns, cut into pieces of kRunGroups
+    std::vector<LayerRun> runs;
+    std::vector<int> layer_entry0(L + 1);
+    for (int l = 0; l < L; ++l) {
+        layer_entry0[l] = (int)runs.size();
+        const int64_t g_first = offsets_host[l] / vec, g_last = (offsets_host[l + 1] + vec - 1) / vec;
+        for (int64_t g = g_first; g < g_last; g += kRunGroups) {
+            LayerRun r;
+            r.g0 = g;
+            r.cb = offsets_host[l];
+            r.ce = offsets_host[l + 1];
+            r.n = (int)((g_last - g < kRunGroups) ? g_last - g : kRunGroups);
+            r.layer = l;
+            runs.push_back(r);
+        }
+        if (runs.size() > (size_t)0x0fffffff) return lfail(ADACONS_EINVAL, "too many runs");
+    }
+    const int nruns = (int)runs.size();
+    layer_entry0[L] = nruns;
+    std::vector<int> order;
+    order.reserve(nruns);
+    for (int r = 0; r < nruns; ++r)
+        if (runs[r].n == kRunGroups) order.push_back(r);
+    {
+        std::vector<int> rest;
+        for (int r = 0; r < nruns; ++r)
+            if (runs[r].n != kRunGroups) rest.push_back(r);
+        std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return runs[a].n > runs[b].n; });
+        order.insert(order.end(), rest.begin(), rest.end());
+    }
+    int per_cu = 2;
+    if (const char *env = getenv("ADACONS_LAYERS_BLOCKS_PER_CU")) per_cu = atoi(env) > 0 ? atoi(env) : per_cu;
+    int gram_grid = prop.multiProcessorCount * per_cu;
+    if (gram_grid > nruns) gram_grid = nruns;
+
+    adacons_layers *ls = new (std::nothrow) adacons_layers();
+    if (!ls) return lfail(ADACONS_ENOMEM, "host allocation failed");
+    memset(ls, 0, sizeof *ls);
+    ls->N = N; ls->L = L; ls->d = offsets_host[L]; ls->dtype = dtype; ls->beta = beta; ls->flags = flags;
+    ls->nruns = nruns; ls->gram_grid = gram_grid;
+    ls->wsum_grid = prop.multiProcessorCount * 8;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int np = num_pairs(N);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&ls->runs), sizeof(LayerRun) * (size_t)nruns);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->offsets), sizeof(int64_t) * (size_t)(L + 1));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->layer_entry0), sizeof(int) * (size_t)(L + 1));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->partials), sizeof(double) * (size_t)nruns * np);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->K), sizeof(double) * (size_t)L * N * N);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->ds), sizeof(DevState) * (size_t)L);
+    if (e == hipSuccess) e = hipMemcpyAsync(ls->runs, runs.data(), sizeof(LayerRun) * (size_t)nruns, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(ls->offsets, offsets_host, sizeof(int64_t) * (size_t)(L + 1), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(ls->layer_entry0, layer_entry0.data(), sizeof(int) * (size_t)(L + 1), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->order), sizeof(int) * (size_t)nruns);
+    if (e == hipSuccess) e = hipMemcpyAsync(ls->order, order.data(), sizeof(int) * (size_t)nruns, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->ticket), sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemsetAsync(ls->ticket, 0, sizeof(unsigned), s);
+    if (e == hipSuccess) e = hipMemsetAsync(ls->ds, 0, sizeof(DevState) * (size_t)L, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ls->K, 0, sizeof(double) * (size_t)L * N * N, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);   // the host vectors above go out of scope
+    if (e != hipSuccess) {
+        adacons_destroy_layers(ls);
+        return lfail(e == hipErrorOutOfMemory ? ADACONS_ENOMEM : ADACONS_EHIP, hipGetErrorString(e));
+    }
+    *out_ls = ls;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons_dtype dtype, adacons_layers *ls,
+                                        float *out, void *hip_stream) {
+    if (!ls || !G || !out) return lfail(ADACONS_EINVAL, "NULL argument");
+    if (N != ls->N || d != ls->d || dtype != ls->dtype) return lfail(ADACONS_EINVAL, "N, d or dtype differ from init");
+    const size_t es = dtype == ADACONS_BF16 ? 2 : 4;
+    const uintptr_t g0 = reinterpret_cast<uintptr_t>(G), o0 = reinterpret_cast<uintptr_t>(out);
+    if (g0 % 16 || o0 % 16 || ((uint64_t)d * es) % 16) return lfail(ADACONS_EALIGN, "layer-wise path needs 16-byte alignment");
+    const uintptr_t g1 = g0 + (uint64_t)N * (uint64_t)d * es, o1 = o0 + (uint64_t)d * 4;
+    if (o0 < g1 && g0 < o1) return lfail(ADACONS_EINVAL, "out overlaps G");
+    CoeffParams cp;
+    cp.N = N; cp.beta = ls->beta; cp.flags = ls->flags;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (dtype == ADACONS_F32)
+        e = dispatch_layers<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
+                                      (const int64_t *)ls->offsets, (const int *)ls->layer_entry0, ls->L, ls->partials,
+                                      ls->K, ls->ds, ls->ticket, cp, out, s);
+    else
+        e = dispatch_layers<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
+                                          (const int64_t *)ls->offsets, (const int *)ls->layer_entry0, ls->L,
+                                          ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
+    if (e != hipSuccess) return lfail(ADACONS_EHIP, hipGetErrorString(e));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_layer_coeffs(const adacons_layers *ls, double *gamma_host, double *raw_host,
+                                    double *smoothed_host, uint32_t *numeric_flags, void *hip_stream) {
+    if (!ls || !gamma_host) return lfail(ADACONS_EINVAL, "NULL argument");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    std::vector<DevState> host((size_t)ls->L);
+    hipError_t e = hipMemcpyAsync(host.data(), ls->ds, sizeof(DevState) * (size_t)ls->L, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return lfail(ADACONS_EHIP, hipGetErrorString(e));
+    for (int l = 0; l < ls->L; ++l) {
+        for (int i = 0; i < ls->N; ++i) {
+            gamma_host[(size_t)l * ls->N + i] = host[l].gamma[i];
+            if (raw_host) raw_host[(size_t)l * ls->N + i] = host[l].a_raw[i];
+            if (smoothed_host) smoothed_host[(size_t)l * ls->N + i] = host[l].a_smooth[i];
+        }
+        if (numeric_flags) numeric_flags[l] = host[l].numeric_flags;
+    }
+    return ADACONS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+"""Layer-wise aggregation: CPU checks of the oracle's composition, and GPU parity of the segmented
+kernels against it."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import adacons_oracle as o
+
+DEV = "cuda:0"
+
+
+def _rand_layout(rng, d, L):
+    cuts = np.sort(rng.choice(np.arange(1, d), size=L - 1, replace=False))
+    return np.concatenate([[0], cuts, [d]]).astype(np.int64)
+
+
+# ------------------------------------------------------------------ CPU: oracle composition ----
+def test_single_layer_equals_model_wise():
+    rng = np.random.default_rng(1)
+    G = (rng.standard_normal(3000)[None, :] + 2 * rng.standard_normal((6, 3000))).astype(np.float32)
+    out_m, info_m = o.aggregate(G, o.OracleState(6))
+    out_l, infos = o.aggregate_layers(G, [0, 3000], [o.OracleState(6)])
+    assert np.array_equal(out_m, out_l) and np.array_equal(info_m["gamma"], infos[0]["gamma"])
+
+
+def test_layers_are_independent_and_keep_their_own_state():
+    rng = np.random.default_rng(2)
+    N, d = 5, 4000
+    off = np.array([0, 7, 1000, 1001, 2500, d])
+    states = [o.OracleState(N, beta=0.8) for _ in range(5)]
+    ref_states = [o.OracleState(N, beta=0.8) for _ in range(5)]
+    for t in range(4):
+        G = (rng.standard_normal(d)[None, :] + 2 * rng.standard_normal((N, d))).astype(np.float32)
+        out, infos = o.aggregate_layers(G, off, states)
+        for l in range(5):
+            a, b = off[l], off[l + 1]
+            out_l, info_l = o.aggregate(np.ascontiguousarray(G[:, a:b]), ref_states[l])
+            assert np.array_equal(out[a:b], out_l)
+            assert np.array_equal(infos[l]["gamma"], info_l["gamma"])
+            assert abs(infos[l]["gamma"].sum() - 1) < 1e-12
+        # changing one layer's data leaves every other layer's weights alone
+        G2 = G.copy(); G2[:, off[2]:off[3]] *= -3.0
+        _, infos2 = o.aggregate_layers(G2, off, [o.OracleState(N, beta=0.8) for _ in range(5)])
+        _, infos1 = o.aggregate_layers(G, off, [o.OracleState(N, beta=0.8) for _ in range(5)])
+        for l in (0, 1, 3, 4):
+            assert np.array_equal(infos1[l]["gamma"], infos2[l]["gamma"])
+
+
+def test_resnet50_layout_adds_up():
+    sizes = workloads.resnet50_layer_sizes()
+    assert len(sizes) == 161 and sum(sizes) == workloads.C2.d and min(sizes) == 64
+
+
+# --------------------------------------------------------------------------- GPU parity ----
+@pytest.fixture(scope="module")
+def pkg():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the GPU")
+    import paper_2411_03742_amd as p
+    return p
+
+
+def _check_layers(pkg, G, off, agg, states, out_tol, check_out=True):
+    out = agg.aggregate(G)
+    info = agg.coeffs()
+    oout, oinfos = o.aggregate_layers(workloads.to_oracle_input(G), off, states, want_out=check_out)
+    for l, oi in enumerate(oinfos):
+        assert info["numeric_flags"][l] == oi["numeric_flags"], l
+        for key in ("gamma", "raw", "smoothed"):
+            ref = oi[key]
+            scale = np.maximum(np.abs(ref), 1e-3 * np.abs(ref).max() + 1e-300)
+            assert (np.abs(info[key][l] - ref) / scale).max() <= 1e-6, (l, key, info[key][l], ref)
+    if check_out:
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(got - oout) / np.linalg.norm(oout) <= out_tol
+        # every layer on its own as well (a small layer must not hide in the global norm)
+        for l in range(len(oinfos)):
+            a, b = off[l], off[l + 1]
+            den = np.linalg.norm(oout[a:b])
+            if den > 0:
+                assert np.linalg.norm(got[a:b] - oout[a:b]) / den <= out_tol, l
+    return out
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("N,d,L", [(1, 64, 1), (2, 1000, 3), (4, 40_000, 17), (8, 300_000, 50), (8, 2_000_000, 9),
+                                   (5, 123_456, 200), (8, 1024, 1024)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_random_layouts_match_oracle(pkg, N, d, L, dtype):
+    rng = np.random.default_rng(N * 7 + L)
+    vec = 8 if dtype == torch.bfloat16 else 4
+    d = (d + vec - 1) // vec * vec
+    off = _rand_layout(rng, d, L) if L < d else np.arange(d + 1, dtype=np.int64)
+    g = torch.Generator(device=DEV).manual_seed(L)
+    agg = pkg.AdaConsLayers(N, off, dtype=dtype, beta=0.9)
+    states = [o.OracleState(N, beta=0.9) for _ in range(len(off) - 1)]
+    for t in range(3):
+        s = torch.randn(d, generator=g, device=DEV)
+        G = (s[None, :] + 2.0 * torch.randn(N, d, generator=g, device=DEV)).to(dtype).contiguous()
+        _check_layers(pkg, G, off, agg, states, 1e-5 if dtype == torch.float32 else 2e-3)
+    agg.close()
+
+
+@pytest.mark.gpu
+def test_resnet50_layout_full_size(pkg):
+    """C2's shape (N = 8, d = 25,557,032, fp32) cut into the 161 parameter tensors of a ResNet-50;
+    three steps of the C2 stream with momentum."""
+    w = workloads.C2.scaled(workloads.C2.d, 3)
+    off = np.concatenate([[0], np.cumsum(workloads.resnet50_layer_sizes())]).astype(np.int64)
+    agg = pkg.AdaConsLayers(w.N, off, beta=0.99)
+    states = [o.OracleState(w.N, beta=0.99) for _ in range(len(off) - 1)]
+    for t, G in enumerate(workloads.stream(w, DEV)):
+        _check_layers(pkg, G, off, agg, states, 1e-5, check_out=(t == 2))
+    agg.close()
+
+
+@pytest.mark.gpu
+def test_one_layer_equals_model_wise_kernel(pkg):
+    N, d = 8, 1_000_000
+    g = torch.Generator(device=DEV).manual_seed(5)
+    G = (torch.randn(d, generator=g, device=DEV)[None, :] + torch.randn(N, d, generator=g, device=DEV)).contiguous()
+    a = pkg.AdaCons(N, d)
+    b = pkg.AdaConsLayers(N, [0, d])
+    oa, ob = a.aggregate(G), b.aggregate(G)
+    ga, gb = a.coeffs()["gamma"], b.coeffs()["gamma"][0]
+    assert np.abs(ga - gb).max() <= 1e-12 * np.abs(ga).max()
+    assert torch.allclose(oa, ob, rtol=1e-6, atol=1e-7)
+    a.close(); b.close()
+
+
+@pytest.mark.gpu
+def test_layer_argument_errors(pkg):
+    with pytest.raises(pkg.AdaConsError) as e:
+        pkg.AdaConsLayers(9, [0, 100])
+    assert e.value.status == 2
+    with pytest.raises(pkg.AdaConsError):
+        pkg.AdaConsLayers(4, [0, 50, 50, 100])          # empty layer
+    with pytest.raises(pkg.AdaConsError):
+        pkg.AdaConsLayers(4, [1, 100])
+    agg = pkg.AdaConsLayers(4, [0, 40, 100])
+    with pytest.raises(pkg.AdaConsError):
+        agg.aggregate(torch.zeros(4, 104, device=DEV))  # d differs from the layout
+    agg.close()

@@ -1,4 +1,4 @@
 """Seeded synthetic input generators (no aggregation arithmetic lives here)."""
-from .synthetic import C1, C2, C3, C4, C5, CONFIGS, Workload, stream, to_oracle_input
+from .synthetic import C1, C2, C3, C4, C5, CONFIGS, Workload, resnet50_layer_sizes, stream, to_oracle_input
 
-__all__ = ["C1", "C2", "C3", "C4", "C5", "CONFIGS", "Workload", "stream", "to_oracle_input"]
+__all__ = ["C1", "C2", "C3", "C4", "C5", "CONFIGS", "Workload", "resnet50_layer_sizes", "stream", "to_oracle_input"]

@@ -126,3 +126,24 @@ def to_oracle_input(G: torch.Tensor):
     if G.dtype == torch.float32:
         return G.cpu().numpy()
     raise TypeError(G.dtype)
+
+
+def resnet50_layer_sizes() -> list[int]:
+    """Element counts of the 161 parameter tensors of a ResNet-50 v1 (conv weights, batch-norm
+    scale and shift, the final fully connected layer), in definition order, computed from the
+    architecture: stem 7x7x3x64, bottleneck stages of [3, 4, 6, 3] blocks with widths
+    [64, 128, 256, 512] and expansion 4, 1000-way classifier.  They add up to 25,557,032, the
+    flattened gradient length of the C2 / C4 workloads; used as the layer layout of the
+    layer-wise benchmark."""
+    sizes = [7 * 7 * 3 * 64, 64, 64]
+    inplanes = 64
+    for width, blocks in zip([64, 128, 256, 512], [3, 4, 6, 3]):
+        for b in range(blocks):
+            sizes += [inplanes * width, width, width]            # 1x1 reduce + bn
+            sizes += [3 * 3 * width * width, width, width]        # 3x3 + bn
+            sizes += [width * width * 4, width * 4, width * 4]    # 1x1 expand + bn
+            if b == 0:
+                sizes += [inplanes * width * 4, width * 4, width * 4]   # projection shortcut + bn
+            inplanes = width * 4
+    sizes += [2048 * 1000, 1000]
+    return sizes
