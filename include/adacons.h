@@ -112,6 +112,17 @@ adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype 
                                  adacons_state *st, float *out, void *hip_stream);
 
 /*
+ * The aggregation fused with the descent step it feeds (Eq. 4 with Eq. 12):
+ *     w[k] <- w[k] - lr * sum_i gamma_i G[i][k]
+ * Stages A1 and A2 as in adacons_aggregate; stage A3 reads and rewrites the fp32 parameter
+ * vector w (device pointer, d floats, caller-owned, must not overlap G) instead of writing `out`,
+ * which saves the d-sized write and re-read between aggregator and optimiser.  lr is the step
+ * size eta_t (finite).  Same argument rules, state changes and errors as adacons_aggregate.
+ */
+adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_dtype dtype,
+                                       adacons_state *st, float *w, float lr, void *hip_stream);
+
+/*
  * Read back the coefficients of the most recent adacons_aggregate() on this state
  * (the three stages of Fig. 7: first-order, after momentum, after normalisation).
  * Copies on `hip_stream` and waits for it: the only synchronising call of the hot API.

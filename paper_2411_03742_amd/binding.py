@@ -32,7 +32,7 @@ EXPORTS = [
     "adacons_coeffs", "adacons_gram", "adacons_read_gram", "adacons_weighted_sum",
     "adacons_state_export", "adacons_state_import", "adacons_tune", "adacons_profile_begin",
     "adacons_profile_end", "adacons_status_string", "adacons_last_error",
-    "adacons_init_layers", "adacons_destroy_layers", "adacons_aggregate_layers", "adacons_layer_coeffs",
+    "adacons_aggregate_apply", "adacons_init_layers", "adacons_destroy_layers", "adacons_aggregate_layers", "adacons_layer_coeffs",
 ]
 
 
@@ -56,6 +56,7 @@ def _load() -> ctypes.CDLL:
         "adacons_destroy_state": [vp],
         "adacons_reset_state": [vp, vp],
         "adacons_aggregate": [vp, i32, i64, i32, vp, vp, vp],
+        "adacons_aggregate_apply": [vp, i32, i64, i32, vp, vp, ctypes.c_float, vp],
         "adacons_coeffs": [vp, dp, dp, dp, ctypes.POINTER(ctypes.c_uint32), vp],
         "adacons_gram": [vp, i32, i64, i32, vp, vp],
         "adacons_read_gram": [vp, dp, vp],
@@ -143,6 +144,14 @@ def adacons_aggregate(G: torch.Tensor, st, out: torch.Tensor, stream=None) -> No
         raise ValueError("out must be a contiguous float32 device tensor of d elements")
     _check(_lib.adacons_aggregate(g, N, d, dt, st, ctypes.c_void_p(out.data_ptr()), _stream(stream)),
            "adacons_aggregate")
+
+
+def adacons_aggregate_apply(G: torch.Tensor, st, w: torch.Tensor, lr: float, stream=None) -> None:
+    g, N, d, dt = _matrix(G)
+    if w.dtype != torch.float32 or not w.is_cuda or not w.is_contiguous() or w.numel() != d:
+        raise ValueError("w must be a contiguous float32 device tensor of d elements")
+    _check(_lib.adacons_aggregate_apply(g, N, d, dt, st, ctypes.c_void_p(w.data_ptr()), float(lr), _stream(stream)),
+           "adacons_aggregate_apply")
 
 
 def adacons_coeffs(st, N: int, stream=None) -> dict:
@@ -290,6 +299,10 @@ class AdaCons:
             out = torch.empty(G.shape[1], dtype=torch.float32, device=G.device)
         adacons_aggregate(G, self._st, out, stream)
         return out
+
+    def aggregate_apply(self, G: torch.Tensor, w: torch.Tensor, lr: float, stream=None) -> torch.Tensor:
+        adacons_aggregate_apply(G, self._st, w, lr, stream)
+        return w
 
     def coeffs(self, stream=None) -> dict:
         return adacons_coeffs(self._st, self.N, stream)

@@ -73,6 +73,6 @@ adacons_status set_error(adacons_status s, const char *fmt, ...);
 // wsum.hip
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const float *gamma, float *out, bool reverse,
-                       hipStream_t stream);
+                       hipStream_t stream, bool apply = false, float lr = 0.f);  // apply: out -= lr * sum
 
 }  // namespace adacons

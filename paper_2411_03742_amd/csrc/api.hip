@@ -217,6 +217,20 @@ adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype 
     return ADACONS_OK;
 }
 
+adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_dtype dtype, adacons_state *st,
+                                       float *w, float lr, void *hip_stream) {
+    bool vec_ok = false;
+    adacons_status rc = check_call(G, N, d, dtype, st, w, true, &vec_ok);
+    if (rc != ADACONS_OK) return rc;
+    if (!std::isfinite(lr)) return fail(ADACONS_EINVAL, "lr is not finite");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
+                        tail_of(st, kGramFinishCoeffs), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s));
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, w,
+                        st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s, true, lr));
+    return ADACONS_OK;
+}
+
 adacons_status adacons_coeffs(const adacons_state *st, double *gamma_host, double *raw_host, double *smoothed_host,
                               uint32_t *numeric_flags, void *hip_stream) {
     if (!st) return fail(ADACONS_EINVAL, "state is NULL");

@@ -14,15 +14,27 @@ namespace adacons {
 
 constexpr int kRowsInFlight = 8;
 
-template <int VEC>
-__device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, const float (&acc)[VEC]) {
+// APPLY = false: out[col..] = acc (non-temporal).  APPLY = true: the descent step of Eq. 4 in
+// place, out[col..] = out[col..] - lr * acc (out is then the parameter vector w: read and written
+// with ordinary accesses, it is needed again next step).
+template <int VEC, bool APPLY>
+__device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, const float (&acc)[VEC], float lr) {
     if constexpr (VEC == 1) {
-        __builtin_nontemporal_store(acc[0], out + col);
+        if constexpr (APPLY) out[col] = fmaf(-lr, acc[0], out[col]);
+        else __builtin_nontemporal_store(acc[0], out + col);
     } else {
 #pragma unroll
         for (int c = 0; c < VEC; c += 4) {
-            const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
-            __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + col + c));
+            f32x4 *dst = reinterpret_cast<f32x4 *>(out + col + c);
+            if constexpr (APPLY) {
+                const f32x4 w = *dst;
+                const f32x4 x = {fmaf(-lr, acc[c], w.x), fmaf(-lr, acc[c + 1], w.y), fmaf(-lr, acc[c + 2], w.z),
+                                 fmaf(-lr, acc[c + 3], w.w)};
+                *dst = x;
+            } else {
+                const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+                __builtin_nontemporal_store(x, dst);
+            }
         }
     }
 }
@@ -30,9 +42,9 @@ __device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, 
 // One tile = kBlock * UNR column groups: thread t owns groups base + u * kBlock, u < UNR.
 // FULL: every group of the tile exists, so the loads carry no predicate and are all issued
 // before the first use.
-template <int NCT, typename T, int VEC, int UNR, bool FULL>
+template <int NCT, typename T, int VEC, int UNR, bool FULL, bool APPLY>
 __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, const int64_t d, const int64_t ngroups,
-                                          const int64_t base, const float *gam, float *__restrict__ out) {
+                                          const int64_t base, const float *gam, float *__restrict__ out, float lr) {
     float acc[UNR][VEC];
     bool live[UNR];
 #pragma unroll
@@ -62,15 +74,15 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
     }
 #pragma unroll
     for (int u = 0; u < UNR; ++u)
-        if (live[u]) store_out<VEC>(out, (base + (int64_t)u * kBlock) * VEC, acc[u]);
+        if (live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * kBlock) * VEC, acc[u], lr);
 }
 
 // NCT > 0: N known at compile time (rows fully unrolled, weights in registers, N <= 16);
 // NCT == 0: N taken from n_rt, rows walked eight at a time, weights in LDS.
-template <int NCT, typename T, int VEC, int UNR>
+template <int NCT, typename T, int VEC, int UNR, bool APPLY>
 __global__ void __launch_bounds__(kBlock)
 wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
-            float *__restrict__ out, int reverse) {
+            float *__restrict__ out, int reverse, float lr) {
     const int N = (NCT > 0) ? NCT : n_rt;
     __shared__ float gam_lds[kNMax];
     float gam_reg[NCT > 0 ? NCT : 1];
@@ -95,9 +107,9 @@ wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const
         const int64_t tt = reverse ? (ntiles - 1 - t) : t;
         const int64_t base = tt * kTile + threadIdx.x;
         if ((tt + 1) * kTile <= ngroups)
-            wsum_tile<NCT, T, VEC, UNR, true>(G, N, d, ngroups, base, gam, out);
+            wsum_tile<NCT, T, VEC, UNR, true, APPLY>(G, N, d, ngroups, base, gam, out, lr);
         else
-            wsum_tile<NCT, T, VEC, UNR, false>(G, N, d, ngroups, base, gam, out);
+            wsum_tile<NCT, T, VEC, UNR, false, APPLY>(G, N, d, ngroups, base, gam, out, lr);
     }
 }
 
@@ -108,10 +120,10 @@ static int occupancy(Kern k) {
     return nb;
 }
 
-template <int NCT, typename T, int VEC, int UNR>
-static hipError_t run(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
-                      bool reverse, hipStream_t s) {
-    static const int occ = occupancy(wsum_kernel<NCT, T, VEC, UNR>);
+template <int NCT, typename T, int VEC, int UNR, bool APPLY>
+static hipError_t run_as(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
+                         bool reverse, float lr, hipStream_t s) {
+    static const int occ = occupancy(wsum_kernel<NCT, T, VEC, UNR, APPLY>);
     const int64_t ngroups = (d + VEC - 1) / VEC;
     const int64_t work = (ngroups + (int64_t)kBlock * UNR - 1) / ((int64_t)kBlock * UNR);
     int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 8;
@@ -119,30 +131,44 @@ static hipError_t run(const void *G, int N, int64_t d, const LaunchShape &shape,
     int64_t grid = (int64_t)shape.num_cu * per_cu;
     if (grid > work) grid = work;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL((wsum_kernel<NCT, T, VEC, UNR>), dim3((unsigned)grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), N, d, ngroups, gamma, out, reverse ? 1 : 0);
+    hipLaunchKernelGGL((wsum_kernel<NCT, T, VEC, UNR, APPLY>), dim3((unsigned)grid), dim3(kBlock), 0, s,
+                       static_cast<const T *>(G), N, d, ngroups, gamma, out, reverse ? 1 : 0, lr);
     return hipGetLastError();
+}
+
+// apply = false: out = sum_i gamma_i g_i.  apply = true: out -= lr * sum_i gamma_i g_i (Eq. 4 fused).
+struct WsumMode {
+    bool reverse, apply;
+    float lr;
+};
+
+template <int NCT, typename T, int VEC, int UNR>
+static hipError_t run(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
+                      const WsumMode &m, hipStream_t s) {
+    return m.apply ? run_as<NCT, T, VEC, UNR, true>(G, N, d, shape, gamma, out, m.reverse, m.lr, s)
+                   : run_as<NCT, T, VEC, UNR, false>(G, N, d, shape, gamma, out, m.reverse, 0.f, s);
 }
 
 template <typename T, int VEC, int UNR>
 static hipError_t dispatch(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
-                           bool reverse, hipStream_t s) {
+                           const WsumMode &m, hipStream_t s) {
     switch (N) {
-        case 4: return run<4, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
-        case 8: return run<8, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
-        case 16: return run<16, T, VEC, 1>(G, N, d, shape, gamma, out, reverse, s);  // 16 loads in flight already
-        default: return run<0, T, VEC, UNR>(G, N, d, shape, gamma, out, reverse, s);
+        case 4: return run<4, T, VEC, UNR>(G, N, d, shape, gamma, out, m, s);
+        case 8: return run<8, T, VEC, UNR>(G, N, d, shape, gamma, out, m, s);
+        case 16: return run<16, T, VEC, 1>(G, N, d, shape, gamma, out, m, s);  // 16 loads in flight already
+        default: return run<0, T, VEC, UNR>(G, N, d, shape, gamma, out, m, s);
     }
 }
 
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const float *gamma, float *out, bool reverse,
-                       hipStream_t stream) {
+                       hipStream_t stream, bool apply, float lr) {
+    const WsumMode m = {reverse, apply, lr};
     if (dtype == ADACONS_F32)
-        return vec_ok ? dispatch<float, 4, 2>(G, N, d, shape, gamma, out, reverse, stream)
-                      : dispatch<float, 1, 2>(G, N, d, shape, gamma, out, reverse, stream);
-    return vec_ok ? dispatch<bf16_bits, 8, 1>(G, N, d, shape, gamma, out, reverse, stream)
-                  : dispatch<bf16_bits, 1, 2>(G, N, d, shape, gamma, out, reverse, stream);
+        return vec_ok ? dispatch<float, 4, 2>(G, N, d, shape, gamma, out, m, stream)
+                      : dispatch<float, 1, 2>(G, N, d, shape, gamma, out, m, stream);
+    return vec_ok ? dispatch<bf16_bits, 8, 1>(G, N, d, shape, gamma, out, m, stream)
+                  : dispatch<bf16_bits, 1, 2>(G, N, d, shape, gamma, out, m, stream);
 }
 
 }  // namespace adacons
