@@ -198,6 +198,42 @@ adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *c
                                    int *calls, void *hip_stream);
 
 /*
+ * ---- One worker's share of Algorithm 1 ---------------------------------------------------
+ * The arithmetic on either side of the paper's collectives, for a caller that keeps the
+ * gradients distributed (one worker per GPU) and runs the collectives itself:
+ *   after all-reducing the gradients (Alg. 1 step 1) a worker holds its own g and their sum;
+ *   adacons_worker_stats gives <g, gsum> and ||g||^2 in one pass over the two vectors;
+ *   with the N pairs gathered (step 2), adacons_update_from_stats runs the coefficient update
+ *   (Eq. 7, Eq. 11, Eq. 12-13; step 3) on the state; adacons_worker_scale rescales the local
+ *   gradient in place by its weight (step 4), ready for the final all-reduce.
+ */
+
+/*
+ *   g, gsum    device pointers, d elements of `dtype` each (may be the same pointer)
+ *   st         supplies the partial-sum workspace; d <= its d_max
+ *   stats_dev  device pointer, 3 doubles, 8-byte aligned: ||g||^2, <g, gsum>, ||gsum||^2
+ * Asynchronous, allocates nothing.  Errors: EINVAL, EUNSUPPORTED, EALIGN, EHIP.
+ */
+adacons_status adacons_worker_stats(const void *g, const void *gsum, int64_t d, adacons_dtype dtype,
+                                    adacons_state *st, double *stats_dev, void *hip_stream);
+
+/*
+ * Stage A2 from gathered statistics instead of a Gram matrix:
+ *   sq_host[i] = ||g_i||^2, dot_host[i] = <g_i, sum_j g_j>   (host pointers, N doubles each)
+ * Updates the state exactly as adacons_aggregate's coefficient step does (readable through
+ * adacons_coeffs).  Copies from the host arrays and waits for the copy once.
+ */
+adacons_status adacons_update_from_stats(adacons_state *st, const double *sq_host, const double *dot_host,
+                                         void *hip_stream);
+
+/*
+ * g <- gamma[worker] * g in place (device pointer, d elements; bf16 is rounded to nearest even),
+ * with the weight the state currently holds for `worker` (0 <= worker < N).  Asynchronous.
+ */
+adacons_status adacons_worker_scale(void *g, int64_t d, adacons_dtype dtype, const adacons_state *st,
+                                    int worker, void *hip_stream);
+
+/*
  * ---- Layer-wise aggregation --------------------------------------------------------------
  * Sec. 4 of the paper computes the aggregation model-wise and notes that layer-wise aggregation
  * performs similarly.  Here the d columns are split into L contiguous segments ("layers"); every

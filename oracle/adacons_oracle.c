@@ -150,33 +150,27 @@ int oracle_gram(const void *G, int N, int64_t d, int dtype, double *K)
 }
 
 /*
- * O2-O7 (coefficient part): from K to gamma, updating the sorted-order EMA
- * state m[N] and the call counter *t.  a_raw, a_smooth may be NULL.
+ * O3-O7 (weights) from the per-worker statistics q_i = ||g_i||^2 and r_i = <g_i, sum_j g_j>
+ * (what each worker of Algorithm 1 holds after step 1 and shares in step 2), updating the
+ * sorted-order EMA state m[N] and the call counter *t.  a_raw, a_smooth may be NULL.
  */
-int oracle_coefficients(const double *K, int N, double beta, unsigned flags,
-                        double *m, int64_t *t,
-                        double *gamma, double *a_raw, double *a_smooth,
-                        unsigned *numeric_flags)
+int oracle_coefficients_from_stats(const double *q, const double *r, int N, double beta, unsigned flags,
+                                   double *m, int64_t *t,
+                                   double *gamma, double *a_raw, double *a_smooth,
+                                   unsigned *numeric_flags)
 {
-    if (!K || !m || !t || !gamma || N < 1 || !(beta >= 0.0 && beta < 1.0))
+    if (!q || !r || !m || !t || !gamma || N < 1 || !(beta >= 0.0 && beta < 1.0))
         return 1;
     unsigned nf = 0;
-    double *q = (double *)malloc(sizeof(double) * (size_t)N * 5);
-    if (!q)
+    double *a = (double *)malloc(sizeof(double) * (size_t)N * 3);
+    if (!a)
         return 2;
-    double *r = q + N, *a = r + N, *as = a + N, *c = as + N;
+    double *as = a + N, *c = as + N;
 
-    /* O2 */
     int finite = 1;
-    for (int i = 0; i < N; ++i) {
-        q[i] = K[(size_t)i * N + i];
-        double acc = 0.0;
-        for (int j = 0; j < N; ++j)
-            acc += K[(size_t)i * N + j];
-        r[i] = acc;
+    for (int i = 0; i < N; ++i)
         if (!isfinite(q[i]) || !isfinite(r[i]))
             finite = 0;
-    }
 
     /* O3 */
     for (int i = 0; i < N; ++i) {
@@ -200,7 +194,7 @@ int oracle_coefficients(const double *K, int N, double beta, unsigned flags,
             if (a_smooth) a_smooth[i] = a[i];
         }
         if (numeric_flags) *numeric_flags = nf;
-        free(q);
+        free(a);
         return 0;
     }
 
@@ -248,8 +242,36 @@ int oracle_coefficients(const double *K, int N, double beta, unsigned flags,
         if (a_smooth) a_smooth[i] = as[i];
     }
     if (numeric_flags) *numeric_flags = nf;
-    free(q);
+    free(a);
     return 0;
+}
+
+/*
+ * O2-O7 (coefficient part): from K to gamma.  O2 reads the statistics off the Gram matrix
+ * (its diagonal and its row sums), the rest is oracle_coefficients_from_stats.
+ */
+int oracle_coefficients(const double *K, int N, double beta, unsigned flags,
+                        double *m, int64_t *t,
+                        double *gamma, double *a_raw, double *a_smooth,
+                        unsigned *numeric_flags)
+{
+    if (!K || N < 1)
+        return 1;
+    double *q = (double *)malloc(sizeof(double) * (size_t)N * 2);
+    if (!q)
+        return 2;
+    double *r = q + N;
+    /* O2 */
+    for (int i = 0; i < N; ++i) {
+        q[i] = K[(size_t)i * N + i];
+        double acc = 0.0;
+        for (int j = 0; j < N; ++j)
+            acc += K[(size_t)i * N + j];
+        r[i] = acc;
+    }
+    int rc = oracle_coefficients_from_stats(q, r, N, beta, flags, m, t, gamma, a_raw, a_smooth, numeric_flags);
+    free(q);
+    return rc;
 }
 
 static double elem(const void *G, int dtype, size_t idx)

@@ -53,6 +53,9 @@ def _bind(path: str):
     lib.oracle_coefficients.argtypes = [dp, ctypes.c_int, ctypes.c_double, ctypes.c_uint, dp,
                                         ctypes.POINTER(ctypes.c_int64), dp, dp, dp,
                                         ctypes.POINTER(ctypes.c_uint)]
+    lib.oracle_coefficients_from_stats.argtypes = [dp, dp, ctypes.c_int, ctypes.c_double, ctypes.c_uint, dp,
+                                                   ctypes.POINTER(ctypes.c_int64), dp, dp, dp,
+                                                   ctypes.POINTER(ctypes.c_uint)]
     lib.oracle_weighted_sum.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
                                         ctypes.c_int, dp, dp]
     lib.oracle_weighted_sum_at.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
@@ -131,6 +134,33 @@ def coefficients(K: np.ndarray, state: OracleState) -> dict:
         raise RuntimeError(f"oracle_coefficients failed rc={rc}")
     state.t = int(t.value)
     return {"gamma": gamma, "raw": raw, "smoothed": smooth, "numeric_flags": int(nf.value), "K": K}
+
+
+def coefficients_from_stats(q, r, state: OracleState) -> dict:
+    """Steps O3-O7 (weights) from q_i = ||g_i||^2 and r_i = <g_i, sum_j g_j>, the per-worker
+    statistics of Algorithm 1; advances ``state`` by one call."""
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    r = np.ascontiguousarray(r, dtype=np.float64)
+    N = state.N
+    if q.shape != (N,) or r.shape != (N,):
+        raise ValueError("q and r must have N entries")
+    gamma, raw, smooth = np.empty(N), np.empty(N), np.empty(N)
+    t = ctypes.c_int64(state.t)
+    nf = ctypes.c_uint(0)
+    rc = _load().oracle_coefficients_from_stats(_dp(q), _dp(r), N, state.beta, state.flags, _dp(state.m),
+                                                ctypes.byref(t), _dp(gamma), _dp(raw), _dp(smooth),
+                                                ctypes.byref(nf))
+    if rc:
+        raise RuntimeError(f"oracle_coefficients_from_stats failed rc={rc}")
+    state.t = int(t.value)
+    return {"gamma": gamma, "raw": raw, "smoothed": smooth, "numeric_flags": int(nf.value)}
+
+
+def worker_stats(g, gsum) -> tuple[float, float, float]:
+    """One worker's statistics in Algorithm 1: (||g||^2, <g, gsum>, ||gsum||^2) in float64, i.e. the
+    Gram matrix of the two vectors (gsum = the all-reduced sum of the gradients, as stored)."""
+    K = gram(np.ascontiguousarray(np.stack([np.asarray(g), np.asarray(gsum)])))
+    return float(K[0, 0]), float(K[0, 1]), float(K[1, 1])
 
 
 def weighted_sum(G, gamma) -> np.ndarray:

@@ -32,7 +32,8 @@ EXPORTS = [
     "adacons_coeffs", "adacons_gram", "adacons_read_gram", "adacons_weighted_sum",
     "adacons_state_export", "adacons_state_import", "adacons_tune", "adacons_profile_begin",
     "adacons_profile_end", "adacons_status_string", "adacons_last_error",
-    "adacons_aggregate_apply", "adacons_init_layers", "adacons_destroy_layers", "adacons_aggregate_layers", "adacons_layer_coeffs",
+    "adacons_aggregate_apply", "adacons_worker_stats", "adacons_update_from_stats", "adacons_worker_scale",
+    "adacons_init_layers", "adacons_destroy_layers", "adacons_aggregate_layers", "adacons_layer_coeffs",
 ]
 
 
@@ -57,6 +58,9 @@ def _load() -> ctypes.CDLL:
         "adacons_reset_state": [vp, vp],
         "adacons_aggregate": [vp, i32, i64, i32, vp, vp, vp],
         "adacons_aggregate_apply": [vp, i32, i64, i32, vp, vp, ctypes.c_float, vp],
+        "adacons_worker_stats": [vp, vp, i64, i32, vp, vp, vp],
+        "adacons_update_from_stats": [vp, dp, dp, vp],
+        "adacons_worker_scale": [vp, i64, i32, vp, i32, vp],
         "adacons_coeffs": [vp, dp, dp, dp, ctypes.POINTER(ctypes.c_uint32), vp],
         "adacons_gram": [vp, i32, i64, i32, vp, vp],
         "adacons_read_gram": [vp, dp, vp],
@@ -152,6 +156,40 @@ def adacons_aggregate_apply(G: torch.Tensor, st, w: torch.Tensor, lr: float, str
         raise ValueError("w must be a contiguous float32 device tensor of d elements")
     _check(_lib.adacons_aggregate_apply(g, N, d, dt, st, ctypes.c_void_p(w.data_ptr()), float(lr), _stream(stream)),
            "adacons_aggregate_apply")
+
+
+def _vector(v: torch.Tensor):
+    if v.dim() != 1 or not v.is_contiguous() or not v.is_cuda:
+        raise ValueError("expected a contiguous 1-D device tensor")
+    if v.dtype == torch.float32:
+        return ctypes.c_void_p(v.data_ptr()), int(v.numel()), ADACONS_F32
+    if v.dtype == torch.bfloat16:
+        return ctypes.c_void_p(v.data_ptr()), int(v.numel()), ADACONS_BF16
+    raise TypeError(f"unsupported dtype {v.dtype}")
+
+
+def adacons_worker_stats(g: torch.Tensor, gsum: torch.Tensor, st, stats: torch.Tensor, stream=None) -> None:
+    pg, d, dt = _vector(g)
+    ps, d2, dt2 = _vector(gsum)
+    if d != d2 or dt != dt2:
+        raise ValueError("g and gsum must have the same length and dtype")
+    if stats.dtype != torch.float64 or not stats.is_cuda or stats.numel() != 3 or not stats.is_contiguous():
+        raise ValueError("stats must be a device tensor of 3 float64")
+    _check(_lib.adacons_worker_stats(pg, ps, d, dt, st, ctypes.c_void_p(stats.data_ptr()), _stream(stream)),
+           "adacons_worker_stats")
+
+
+def adacons_update_from_stats(st, sq, dot, stream=None) -> None:
+    sq = np.ascontiguousarray(sq, dtype=np.float64)
+    dot = np.ascontiguousarray(dot, dtype=np.float64)
+    if sq.shape != dot.shape or sq.ndim != 1:
+        raise ValueError("sq and dot must be vectors of N entries")
+    _check(_lib.adacons_update_from_stats(st, _dptr(sq), _dptr(dot), _stream(stream)), "adacons_update_from_stats")
+
+
+def adacons_worker_scale(g: torch.Tensor, st, worker: int, stream=None) -> None:
+    pg, d, dt = _vector(g)
+    _check(_lib.adacons_worker_scale(pg, d, dt, st, int(worker), _stream(stream)), "adacons_worker_scale")
 
 
 def adacons_coeffs(st, N: int, stream=None) -> dict:
@@ -306,6 +344,20 @@ class AdaCons:
 
     def coeffs(self, stream=None) -> dict:
         return adacons_coeffs(self._st, self.N, stream)
+
+    def worker_stats(self, g: torch.Tensor, gsum: torch.Tensor, stream=None) -> torch.Tensor:
+        stats = torch.empty(3, dtype=torch.float64, device=g.device)
+        adacons_worker_stats(g, gsum, self._st, stats, stream)
+        return stats
+
+    def update_from_stats(self, sq, dot, stream=None) -> None:
+        if len(sq) != self.N or len(dot) != self.N:
+            raise ValueError("one pair per worker")
+        adacons_update_from_stats(self._st, sq, dot, stream)
+
+    def worker_scale(self, g: torch.Tensor, worker: int, stream=None) -> torch.Tensor:
+        adacons_worker_scale(g, self._st, worker, stream)
+        return g
 
     def gram(self, G: torch.Tensor, stream=None) -> np.ndarray:
         adacons_gram(G, self._st, stream)

@@ -70,6 +70,14 @@ hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t strea
 // api.hip: record the thread-local text adacons_last_error() returns; gives back `s`
 adacons_status set_error(adacons_status s, const char *fmt, ...);
 
+// worker.hip
+hipError_t launch_pair_stats(const void *x, const void *y, int64_t d, adacons_dtype dtype, bool vec_ok, int num_cu,
+                             int max_rows, double *partials, double *stats, hipStream_t s);
+hipError_t launch_coeffs_from_stats(const double *q, const double *r, DevState *ds, const CoeffParams &cp,
+                                    hipStream_t s);
+hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, bool vec_ok, int num_cu, const float *gamma,
+                        hipStream_t s);
+
 // wsum.hip
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const float *gamma, float *out, bool reverse,

@@ -164,8 +164,8 @@ adacons_status adacons_init_state(adacons_state **out_st, int N, int64_t d_max, 
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&st->ds), sizeof(DevState));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->partials), (size_t)st->max_rows * num_pairs(N) * sizeof(double));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->K), (size_t)N * N * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->partials), (size_t)st->max_rows * (num_pairs(N) < 3 ? 3 : num_pairs(N)) * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->K), ((size_t)N * N + 2 * (size_t)N) * sizeof(double));
     if (e == hipSuccess) e = launch_clear_state(st->ds, st->K, N * N, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
@@ -228,6 +228,48 @@ adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_
                         tail_of(st, kGramFinishCoeffs), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s));
     HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, w,
                         st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s, true, lr));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_worker_stats(const void *g, const void *gsum, int64_t d, adacons_dtype dtype,
+                                    adacons_state *st, double *stats_dev, void *hip_stream) {
+    if (!st || !g || !gsum || !stats_dev) return fail(ADACONS_EINVAL, "NULL argument");
+    if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return fail(ADACONS_EUNSUPPORTED, "unknown dtype %d", (int)dtype);
+    if (d < 1 || d > st->d_max) return fail(ADACONS_EINVAL, "d outside [1, d_max]");
+    const size_t es = elem_size(dtype);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(g), b = reinterpret_cast<uintptr_t>(gsum);
+    if (a % es || b % es || reinterpret_cast<uintptr_t>(stats_dev) % 8) return fail(ADACONS_EALIGN, "misaligned pointer");
+    const bool vec_ok = (a % 16 == 0) && (b % 16 == 0) && ((uint64_t)d * es % 16 == 0);
+    HIP_TRY(launch_pair_stats(g, gsum, d, dtype, vec_ok, st->num_cu, st->max_rows, st->partials, stats_dev,
+                              static_cast<hipStream_t>(hip_stream)));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_update_from_stats(adacons_state *st, const double *sq_host, const double *dot_host,
+                                         void *hip_stream) {
+    if (!st || !sq_host || !dot_host) return fail(ADACONS_EINVAL, "NULL argument");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    double *q = st->K + (size_t)st->N * st->N, *r = q + st->N;
+    HIP_TRY(hipMemcpyAsync(q, sq_host, (size_t)st->N * sizeof(double), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(r, dot_host, (size_t)st->N * sizeof(double), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));   // the host arrays are the caller's
+    CoeffParams cp;
+    cp.N = st->N; cp.beta = st->beta; cp.flags = st->flags;
+    HIP_TRY(launch_coeffs_from_stats(q, r, st->ds, cp, s));
+    return ADACONS_OK;
+}
+
+adacons_status adacons_worker_scale(void *g, int64_t d, adacons_dtype dtype, const adacons_state *st, int worker,
+                                    void *hip_stream) {
+    if (!st || !g) return fail(ADACONS_EINVAL, "NULL argument");
+    if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return fail(ADACONS_EUNSUPPORTED, "unknown dtype %d", (int)dtype);
+    if (worker < 0 || worker >= st->N) return fail(ADACONS_EINVAL, "worker %d outside [0, N)", worker);
+    if (d < 1) return fail(ADACONS_EINVAL, "d < 1");
+    const size_t es = elem_size(dtype);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(g);
+    if (a % es) return fail(ADACONS_EALIGN, "g not aligned to its element size");
+    const bool vec_ok = (a % 16 == 0) && ((uint64_t)d * es % 16 == 0);
+    HIP_TRY(launch_scale(g, d, dtype, vec_ok, st->num_cu, st->ds->gamma32 + worker, static_cast<hipStream_t>(hip_stream)));
     return ADACONS_OK;
 }
 

@@ -18,8 +18,9 @@ namespace adacons {
 // gives gamma_i = 1/N; the EMA state is not touched when a statistic is non-finite.
 // m_old: the state entry m[tid] loaded by the caller ahead of time (thread tid < N), so that the
 // global-memory latency of the state overlaps the reduction; it is exchanged through LDS.
-__device__ inline void update_coefficients(const double *K, DevState *ds, const CoeffParams cp, double *lds,
-                                    double m_old) {
+// Core: thread tid < N passes its own q = ||g_tid||^2 and r = <g_tid, sum_j g_j>.
+__device__ inline void update_coefficients_from_stats(double q, double r, DevState *ds, const CoeffParams cp,
+                                                      double *lds, double m_old) {
     const int N = cp.N;
     const int tid = threadIdx.x;
     double *m_sh = lds + 2 * kNMax;  // [kNMax]
@@ -34,10 +35,8 @@ __device__ inline void update_coefficients(const double *K, DevState *ds, const 
     }
     __syncthreads();
 
-    double q = 0.0, r = 0.0, a = 0.0;
+    double a = 0.0;
     if (tid < N) {
-        q = K[(size_t)tid * N + tid];
-        for (int j = 0; j < N; ++j) r += K[(size_t)tid * N + j];
         if (!isfinite(q) || !isfinite(r)) atomicOr(&s_bad, 1);
     }
     __syncthreads();
@@ -114,6 +113,18 @@ __device__ inline void update_coefficients(const double *K, DevState *ds, const 
         ds->numeric_flags = nf;
         ds->step += 1ull;
     }
+}
+
+// From the Gram matrix: q_i is its diagonal, r_i its row sum (j ascending).
+__device__ inline void update_coefficients(const double *K, DevState *ds, const CoeffParams cp, double *lds,
+                                           double m_old) {
+    const int N = cp.N, tid = threadIdx.x;
+    double q = 0.0, r = 0.0;
+    if (tid < N) {
+        q = K[(size_t)tid * N + tid];
+        for (int j = 0; j < N; ++j) r += K[(size_t)tid * N + j];
+    }
+    update_coefficients_from_stats(q, r, ds, cp, lds, m_old);
 }
 
 }  // namespace adacons
