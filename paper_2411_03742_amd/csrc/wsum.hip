@@ -167,7 +167,7 @@ hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, boo
     if (dtype == ADACONS_F32)
         return vec_ok ? dispatch<float, 4, 2>(G, N, d, shape, gamma, out, m, stream)
                       : dispatch<float, 1, 2>(G, N, d, shape, gamma, out, m, stream);
-    return vec_ok ? dispatch<bf16_bits, 8, 1>(G, N, d, shape, gamma, out, m, stream)
+    return vec_ok ? dispatch<bf16_bits, 8, 2>(G, N, d, shape, gamma, out, m, stream)
                   : dispatch<bf16_bits, 1, 2>(G, N, d, shape, gamma, out, m, stream);
 }
 
