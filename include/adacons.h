@@ -177,8 +177,10 @@ typedef enum {
                                              loads and streams the rest past the caches (non-temporal), so
                                              that A3 finds the head in the 256 MB memory-side cache.
                                              Default 320; >= 2^20 means all of G */
-    ADACONS_TUNE_MFMA_DIRECT_LOADS = 5,   /* A1, N > 8: 1 (default) = matrix-core operands loaded straight from
-                                             memory; 0 = tiles staged through LDS with coalesced loads */
+    ADACONS_TUNE_MFMA_DIRECT_LOADS = 5,   /* A1, N > 8: 1 = matrix-core operands loaded straight from memory;
+                                             0 = workgroup tiles staged through LDS with coalesced loads;
+                                             2 (default) = coalesced loads, per-wavefront transpose through
+                                             LDS (fp32 on the 128-bit path; other inputs take variant 1) */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);

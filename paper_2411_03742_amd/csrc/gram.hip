@@ -508,6 +508,110 @@ gram_mfma_lds_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ntiles, 
                                partials + (size_t)blockIdx.x * num_pairs(N));
 }
 
+
+// ------------------------------------------------------------------------------------------
+// A1, 8 < N <= 64, fp32, 128-bit path: coalesced loads, per-wavefront transpose through LDS
+// ------------------------------------------------------------------------------------------
+// Measured at N = 64: the operand-layout loads of gram_mfma_kernel alone (no MFMA) take longer
+// than its MFMAs alone (1.33 ms vs 0.92 ms for 6.5 GB): 64-byte pieces of 16 rows per
+// instruction reach only 4.9 TB/s, 256-byte pieces of 4 rows 6.1 TB/s.  Here a wavefront loads
+// its 64-column chunk with coalesced instructions (4 rows x 256 B each), parks it in its OWN
+// 16 NT x 256 B slice of LDS (16-byte pieces XOR-swizzled with the row number: conflict-free in
+// both directions) and reads it back in operand layout.  Nothing is shared between wavefronts,
+// so there is no workgroup barrier in the loop; the next chunk's loads are in flight while the
+// current chunk is multiplied.
+template <int NT>
+__global__ void __launch_bounds__(kBlock, (NT >= 4) ? 1 : 2)
+gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nchunks, double *__restrict__ partials) {
+    constexpr int NPT = NT * (NT + 1) / 2;
+    constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
+    constexpr int kSliceBytes = kRows * 256;                  // one wavefront's chunk: kRows x 64 floats
+    static_assert(NPT * 256 * 8 <= 4 * kSliceBytes, "the final reduction reuses the slices");
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * kSliceBytes];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int r16 = lane & 15, kq = lane >> 4;
+    unsigned char *slice = lds_raw + wave * kSliceBytes;
+
+    f32x4 acc32[NPT];
+    double acc64[NPT][4];
+#pragma unroll
+    for (int p = 0; p < NPT; ++p) {
+        acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
+    }
+
+    // load j of a chunk: row 4 j + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
+    f32x4 stage[kLoads];
+    auto load_chunk = [&](int64_t ch) {
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int row = 4 * j + (lane >> 4);
+            const int64_t col = ch * 64 + (lane & 15) * 4;
+            const bool live = row < N && col < d;   // d is a multiple of 4 on this path
+            const int rowc = row < N ? row : N - 1;
+            const int64_t colc = col < d ? col : d - 4;
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+            stage[j] = live ? x : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+
+    const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
+    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
+    int64_t ch = (int64_t)slot * (kBlock / kWave) + wave;
+    int since_flush = 0;
+    if (ch < nchunks) load_chunk(ch);
+    while (ch < nchunks) {
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int row = 4 * j + (lane >> 4);
+            const int piece = (lane & 15) ^ (row & 15);
+            *reinterpret_cast<f32x4 *>(slice + row * 256 + piece * 16) = stage[j];
+        }
+        const int64_t chn = ch + wstride;
+        load_chunk(chn < nchunks ? chn : nchunks - 1);   // past the end: the last chunk again, never used
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            f32x4 v[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int row = t * 16 + r16;
+                const int piece = (u * 4 + kq) ^ (row & 15);
+                v[t] = *reinterpret_cast<const f32x4 *>(slice + row * 256 + piece * 16);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                int p = 0;
+#pragma unroll
+                for (int I = 0; I < NT; ++I)
+#pragma unroll
+                    for (int J = I; J < NT; ++J) {
+                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[I][c], v[J][c], acc32[p], 0, 0, 0);
+                        ++p;
+                    }
+            }
+        }
+        since_flush += 4;
+        if (since_flush >= kFlush) {
+            since_flush = 0;
+#pragma unroll
+            for (int p = 0; p < NPT; ++p) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+                acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        ch = chn;
+    }
+#pragma unroll
+    for (int p = 0; p < NPT; ++p)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+    __syncthreads();   // every wavefront is done with its slice before the buffer is reused
+    mfma_store_partial_row<NT>(acc64, reinterpret_cast<double *>(lds_raw), N,
+                               partials + (size_t)blockIdx.x * num_pairs(N));
+}
+
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
@@ -593,9 +697,26 @@ static hipError_t run_mfma_lds(const void *G, int N, int64_t d, const LaunchShap
     return hipGetLastError();
 }
 
+template <int NT>
+static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
+                                hipStream_t s, int *grid_out) {
+    static const int occ = occupancy(gram_mfma_wave_kernel<NT>);
+    const int64_t nchunks = (d + 63) / 64;
+    const int waves = kBlock / kWave;
+    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, NT >= 4 ? 1 : 2);
+    *grid_out = grid;
+    hipLaunchKernelGGL((gram_mfma_wave_kernel<NT>), dim3(grid), dim3(kBlock), 0, s, static_cast<const float *>(G), N,
+                       d, nchunks, tail.partials);
+    return hipGetLastError();
+}
+
 template <int NT, typename T, int VEC4>
 static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                            hipStream_t s, int *grid_out) {
+    if constexpr (VEC4 != 0 && sizeof(T) == 4) {
+        if (tail.mode == kGramPartialsOnly && shape.mfma_direct == 2)
+            return run_mfma_wave<NT>(G, N, d, shape, tail, s, grid_out);
+    }
     // the LDS-staged kernel needs the 128-bit path and leaves the reduction to a later launch
     if (VEC4 != 0 && tail.mode == kGramPartialsOnly && shape.mfma_direct == 0)
         return run_mfma_lds<NT, T>(G, N, d, shape, tail, s, grid_out);

@@ -94,11 +94,13 @@ def test_gram_matches_oracle(pkg, N, d, dtype):
 
 @pytest.mark.parametrize("N,d", [(12, 1024), (16, 4096 + 16), (24, 100_000), (40, 20_000), (64, 65_536 + 256)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-def test_gram_lds_staged_variant_matches_oracle(pkg, N, d, dtype):
-    """The matrix-core kernel that stages coalesced tiles through LDS (tuning option)."""
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_gram_matrix_core_variants_match_oracle(pkg, N, d, dtype, variant):
+    """The three ways the matrix-core Gram kernel gets its operands (tuning option): workgroup tiles
+    staged through LDS (0), straight from memory (1), per-wavefront transpose through LDS (2)."""
     G = randG(N, d, dtype, sigma=2.0, seed=N + d % 991)
     agg = pkg.AdaCons(N, d)
-    agg.tune(pkg.ADACONS_TUNE_MFMA_DIRECT_LOADS, 0)
+    agg.tune(pkg.ADACONS_TUNE_MFMA_DIRECT_LOADS, variant)
     K = agg.gram(G)
     Kref = o.gram(workloads.to_oracle_input(G))
     scale = np.sqrt(np.outer(np.diag(Kref), np.diag(Kref)))
