@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # WRITE_SIZE runs of this script, scaled by the readings of a plain device copy of known size
 # (profiles/c2_n8_d25557032_f32_hbm_traffic_pmc.txt).  Fetched + written.
 PMC_TRAFFIC_BYTES = {
-    ("C2", "gram_kernel (A1)"): 827_360_000 + 70_000,
-    ("C2", "wsum_kernel (A3)"): 857_660_000 + 102_230_000,
+    ("C2", "gram_kernel (A1)"): 826_750_000 + 70_000,
+    ("C2", "wsum_kernel (A3)"): 856_950_000 + 102_230_000,
 }
 
 

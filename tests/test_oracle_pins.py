@@ -353,3 +353,17 @@ def test_threads_do_not_change_the_result(monkeypatch):
         env = dict(os.environ, OMP_NUM_THREADS=nt)
         outs.append(json.loads(subprocess.check_output([sys.executable, "-c", code], env=env)))
     assert outs[0] == outs[1]
+
+
+def test_stored_trace_of_the_oracle_itself():
+    """Regression guard: the six-step trace written by tests/golden/make_oracle_trace.py (which
+    calls only the oracle, on an explicitly specified integer sequence) is reproduced."""
+    import importlib.util, os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_trace", os.path.join(here, "golden", "make_oracle_trace.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = np.loadtxt(os.path.join(here, "golden", "oracle_trace_n5_d97.txt"))
+    assert stored.shape == (6, 23)
+    assert np.allclose(mod.trace(), stored, rtol=1e-13, atol=1e-15)
+    assert np.allclose(stored[:, 10:15].sum(axis=1), 1.0, atol=1e-14)

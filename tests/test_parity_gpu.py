@@ -392,3 +392,37 @@ def test_aggregate_apply_rejects_bad_arguments(pkg):
     with pytest.raises(pkg.AdaConsError):
         agg.aggregate_apply(G, torch.zeros(d, device=DEV), float("nan"))
     agg.close()
+
+
+# ------------------------------------------------------------------------- graph capture ----
+def test_aggregate_can_be_captured_in_a_hip_graph(pkg):
+    """adacons_aggregate enqueues kernels only (no allocation, no synchronisation, no memset
+    node), so a caller may capture it; every replay advances the momentum state like an eager
+    call.  Replays are interleaved with eager work and checked one by one against the oracle."""
+    N, d = 8, 1_000_004
+    agg = pkg.AdaCons(N, d, beta=0.9)
+    ost = o.OracleState(N, beta=0.9)
+    G = randG(N, d, sigma=2.0, seed=77)
+    out = torch.empty(d, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        agg.aggregate(G, out=out, stream=side)          # warm-up call outside the capture
+    side.synchronize()
+    o.aggregate(workloads.to_oracle_input(G), ost, want_out=False)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        agg.aggregate(G, out=out, stream=torch.cuda.current_stream())
+    for rep in range(4):
+        G.copy_(randG(N, d, sigma=2.0, seed=80 + rep))   # eager work between replays: new input in place
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        info = agg.coeffs()
+        ref_out, ref = o.aggregate(workloads.to_oracle_input(G), ost)
+        assert_gamma_close(info["gamma"], ref["gamma"])
+        assert rel_l2(out.cpu().numpy(), ref_out) <= 1e-5
+    _, step = agg.export_state()
+    assert step == 5
+    agg.close()
