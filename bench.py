@@ -46,7 +46,8 @@ def main() -> int:
                     help="time the layer-wise entry point instead (C2 only): one coefficient set per "
                          "parameter tensor of a ResNet-50; not the headline metric")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
-                    help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass / cached_head_mb")
+                    help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass / cached_head_mb / "
+                         "mfma_direct_loads / stats_only")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 "
@@ -77,7 +78,8 @@ def main() -> int:
             "fuse_coeffs": ada.ADACONS_TUNE_FUSE_COEFFS,
             "reverse_second_pass": ada.ADACONS_TUNE_REVERSE_SECOND_PASS,
             "cached_head_mb": ada.ADACONS_TUNE_CACHED_HEAD_MB,
-            "mfma_direct_loads": ada.ADACONS_TUNE_MFMA_DIRECT_LOADS}
+            "mfma_direct_loads": ada.ADACONS_TUNE_MFMA_DIRECT_LOADS,
+            "stats_only": ada.ADACONS_TUNE_STATS_ONLY}
     tuned = {}
     for kv in args.tune:
         k, v = kv.split("=")

@@ -142,7 +142,8 @@ adacons_status adacons_coeffs(const adacons_state *st, double *gamma_host, doubl
 adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype,
                             adacons_state *st, void *hip_stream);
 
-/* Copy the state's K (N x N doubles, row-major, symmetric) to the host; synchronises the stream. */
+/* Copy the state's K (N x N doubles, row-major, symmetric) to the host; synchronises the stream.
+ * ADACONS_EINVAL when the last call on this state did not produce K (ADACONS_TUNE_STATS_ONLY). */
 adacons_status adacons_read_gram(const adacons_state *st, double *K_host, void *hip_stream);
 
 /*
@@ -173,14 +174,23 @@ typedef enum {
     ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1,  /* persistent workgroups per CU in stage A3 */
     ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2; 0 (default): A2 is its own launch */
     ADACONS_TUNE_REVERSE_SECOND_PASS = 3, /* 1: A3 walks its column tiles backwards; 0 (default): forwards */
-    ADACONS_TUNE_CACHED_HEAD_MB = 4,      /* A1 (N <= 8) reads the first `value` MiB of G with cache-allocating
-                                             loads and streams the rest past the caches (non-temporal), so
-                                             that A3 finds the head in the 256 MB memory-side cache.
-                                             Default 320; >= 2^20 means all of G */
+    ADACONS_TUNE_CACHED_HEAD_MB = 4,      /* A1 reads the first `value` MiB of G with cache-allocating loads and
+                                             streams the rest past the caches (non-temporal), so that A3 finds
+                                             the head in the 256 MB memory-side cache.  Default 320; >= 2^20
+                                             means all of G.  For N > 8 the streamed part is used only when
+                                             every row of G starts on a 128-byte line (fp32 on the 128-bit
+                                             path); otherwise those kernels use ordinary loads throughout */
     ADACONS_TUNE_MFMA_DIRECT_LOADS = 5,   /* A1, N > 8: 1 = matrix-core operands loaded straight from memory;
                                              0 = workgroup tiles staged through LDS with coalesced loads;
                                              2 (default) = coalesced loads, per-wavefront transpose through
                                              LDS (fp32 on the 128-bit path; other inputs take variant 1) */
+    ADACONS_TUNE_STATS_ONLY = 6,          /* 1: for N > 8 stage A1 computes only what Eq. 7 consumes, the diagonal
+                                             of K and its row sums (||g_i||^2 and <g_i, sum_j g_j>: Alg. 1
+                                             steps 1-2), in O(N) operations per column; K itself is then not
+                                             produced and adacons_read_gram() reports ADACONS_EINVAL.  Honoured
+                                             by adacons_aggregate / adacons_aggregate_apply when G is 16-byte
+                                             aligned and d * sizeof(element) is a multiple of 16; otherwise,
+                                             and for N <= 8, the Gram kernels run.  0 (default): full K */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);

@@ -9,7 +9,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 LIB_PATH = os.path.join(_PKG, "libadacons.so")
-SOURCES = ["api.hip", "gram.hip", "wsum.hip", "layers.hip", "worker.hip"]
+SOURCES = ["api.hip", "gram.hip", "stats.hip", "wsum.hip", "layers.hip", "worker.hip"]
 HEADERS = ["adacons_internal.h", "device_util.h", "coeff_device.h"]
 
 HIPCC_FLAGS = [

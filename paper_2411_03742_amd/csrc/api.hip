@@ -22,6 +22,7 @@ struct adacons_state {
     double *partials;  // device, [max_rows][N(N+1)/2]
     double *K;         // device, [N][N]
     int max_rows;
+    bool k_valid;      // K holds the Gram matrix of the last call (false after a statistics-only A1)
     int tune[ADACONS_TUNE_COUNT_];
     // per-kernel timing (adacons_profile_begin/end)
     std::vector<hipEvent_t> events;  // 4 per call: before A1, after the Gram kernel, after A2, after A3
@@ -51,7 +52,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 2};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 2, 0};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 
@@ -101,6 +102,20 @@ GramTail tail_of(adacons_state *st, int mode) {
     t.cp.flags = st->flags;
     t.mode = mode;
     return t;
+}
+
+// Stages A1 + A2 of an aggregation: the Gram kernels, or the statistics-only pass when selected.
+hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
+                             hipStream_t s, hipEvent_t between) {
+    const LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
+    if (st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8 && vec_ok) {
+        st->k_valid = false;
+        const GramTail t = tail_of(st, kGramFinishCoeffs);
+        return launch_stats(G, N, d, dtype, shape, st->partials, st->ds, t.cp, s, between);
+    }
+    st->k_valid = true;
+    return launch_gram(G, N, d, dtype, vec_ok, shape, tail_of(st, kGramFinishCoeffs),
+                       st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s, between);
 }
 
 }  // namespace
@@ -160,6 +175,7 @@ adacons_status adacons_init_state(adacons_state **out_st, int N, int64_t d_max, 
     st->max_rows = gram_rows_needed(N, st->num_cu);
     for (int k = 0; k < ADACONS_TUNE_COUNT_; ++k) st->tune[k] = kTuneDefault[k];
     st->prof_capacity = 0;
+    st->k_valid = true;   // zeroed at creation
     st->prof_calls = 0;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -204,9 +220,7 @@ adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype 
     hipEvent_t *ev = prof ? &st->events[(size_t)st->prof_calls * 4] : nullptr;
 
     if (prof) HIP_TRY(hipEventRecord(ev[0], s));
-    HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
-                        tail_of(st, kGramFinishCoeffs), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s,
-                        prof ? ev[1] : nullptr));
+    HIP_TRY(launch_first_pass(st, G, N, d, dtype, vec_ok, s, prof ? ev[1] : nullptr));
     if (prof) HIP_TRY(hipEventRecord(ev[2], s));
     HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out,
                         st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s));
@@ -224,8 +238,7 @@ adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_
     if (rc != ADACONS_OK) return rc;
     if (!std::isfinite(lr)) return fail(ADACONS_EINVAL, "lr is not finite");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
-                        tail_of(st, kGramFinishCoeffs), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s));
+    HIP_TRY(launch_first_pass(st, G, N, d, dtype, vec_ok, s, nullptr));
     HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, w,
                         st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s, true, lr));
     return ADACONS_OK;
@@ -294,6 +307,7 @@ adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype
     bool vec_ok = false;
     adacons_status rc = check_call(G, N, d, dtype, st, nullptr, false, &vec_ok);
     if (rc != ADACONS_OK) return rc;
+    st->k_valid = true;
     HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
                         tail_of(st, kGramFinishK), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0,
                         static_cast<hipStream_t>(hip_stream)));
@@ -303,6 +317,7 @@ adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype
 adacons_status adacons_read_gram(const adacons_state *st, double *K_host, void *hip_stream) {
     if (!st) return fail(ADACONS_EINVAL, "state is NULL");
     if (!K_host) return fail(ADACONS_EINVAL, "K_host is NULL");
+    if (!st->k_valid) return fail(ADACONS_EINVAL, "the last call computed the statistics only (ADACONS_TUNE_STATS_ONLY): no K");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     HIP_TRY(hipMemcpyAsync(K_host, st->K, (size_t)st->N * st->N * sizeof(double), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));

@@ -108,4 +108,33 @@ __device__ __forceinline__ double wave_reduce_scatter(const double (&v)[NP], int
     return wave_reduce_scatter_step<NP, 32>(v, lane);
 }
 
+// sum over rows b = first, first + step, ... (< nrows) of partials[b][p], b ascending; the loads
+// of up to sixteen rows are issued together (rows past the end read as +0.0, which leaves a sum
+// unchanged), the additions keep the row order
+__device__ __forceinline__ double sum_rows(const double *partials, int np, int p, int first, int step, int nrows) {
+    double acc = 0.0;
+    for (int b = first; b < nrows; b += 16 * step) {
+        double t[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int row = b + k * step;
+            t[k] = (row < nrows) ? partials[(size_t)row * np + p] : 0.0;
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc += t[k];
+    }
+    return acc;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8) and every XCD
+// has its own L2.  Rows of G are in general not aligned to a 128-byte line relative to each
+// other, so the line at the boundary of two neighbouring column segments is needed by two
+// workgroups; giving each XCD a contiguous run of segments makes those two share an L2.
+// Returns the segment (0 .. grid-1) workgroup b takes inside one sweep of the grid.
+__device__ __forceinline__ int xcd_contiguous_slot(int b, int grid) {
+    constexpr int kXcds = 8;
+    if (grid % kXcds) return b;
+    return (b % kXcds) * (grid / kXcds) + b / kXcds;
+}
+
 }  // namespace adacons

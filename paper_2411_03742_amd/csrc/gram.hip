@@ -17,6 +17,8 @@
 #include "coeff_device.h"
 #include "device_util.h"
 
+#include <type_traits>
+
 namespace adacons {
 
 // ------------------------------------------------------------------------------------------
@@ -32,24 +34,6 @@ __device__ __forceinline__ void unpack_pair(int p, int N, int &i, int &j) {
     }
     i = row;
     j = row + left;
-}
-
-// sum over rows b = first, first + step, ... (< nrows) of partials[b][p], b ascending; the loads
-// of up to sixteen rows are issued together (rows past the end read as +0.0, which leaves a sum
-// unchanged), the additions keep the row order
-__device__ __forceinline__ double sum_rows(const double *partials, int np, int p, int first, int step, int nrows) {
-    double acc = 0.0;
-    for (int b = first; b < nrows; b += 16 * step) {
-        double t[16];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const int row = b + k * step;
-            t[k] = (row < nrows) ? partials[(size_t)row * np + p] : 0.0;
-        }
-#pragma unroll
-        for (int k = 0; k < 16; ++k) acc += t[k];
-    }
-    return acc;
 }
 
 // K[i][j] = K[j][i] = sum over rows of partials[.][p]: blockDim.x / np interleaved sub-sums per
@@ -131,17 +115,6 @@ __global__ void __launch_bounds__(kBlock) coeff_kernel(const double *K, DevState
     __shared__ double lds[kBlock];
     const double m_old = ((int)threadIdx.x < cp.N) ? ds->m[threadIdx.x] : 0.0;
     update_coefficients(K, ds, cp, lds, m_old);
-}
-
-// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8) and every XCD
-// has its own L2.  Rows of G are in general not aligned to a 128-byte line relative to each
-// other, so the line at the boundary of two neighbouring column segments is needed by two
-// workgroups; giving each XCD a contiguous run of segments makes those two share an L2.
-// Returns the segment (0 .. grid-1) workgroup b takes inside one sweep of the grid.
-__device__ __forceinline__ int xcd_contiguous_slot(int b, int grid) {
-    constexpr int kXcds = 8;
-    if (grid % kXcds) return b;
-    return (b % kXcds) * (grid / kXcds) + b / kXcds;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -522,7 +495,8 @@ gram_mfma_lds_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ntiles, 
 // current chunk is multiplied.
 template <int NT>
 __global__ void __launch_bounds__(kBlock, (NT >= 4) ? 1 : 2)
-gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nchunks, double *__restrict__ partials) {
+gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nchunks, int64_t cached_chunks,
+                      double *__restrict__ partials) {
     constexpr int NPT = NT * (NT + 1) / 2;
     constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
     constexpr int kSliceBytes = kRows * 256;                  // one wavefront's chunk: kRows x 64 floats
@@ -543,7 +517,7 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
 
     // load j of a chunk: row 4 j + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
     f32x4 stage[kLoads];
-    auto load_chunk = [&](int64_t ch) {
+    auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int row = 4 * j + (lane >> 4);
@@ -551,7 +525,10 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
             const bool live = row < N && col < d;   // d is a multiple of 4 on this path
             const int rowc = row < N ? row : N - 1;
             const int64_t colc = col < d ? col : d - 4;
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+            f32x4 x;
+            if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
+            else x = *src;
             stage[j] = live ? x : f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
@@ -560,8 +537,8 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
     const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
     int64_t ch = (int64_t)slot * (kBlock / kWave) + wave;
     int since_flush = 0;
-    if (ch < nchunks) load_chunk(ch);
-    while (ch < nchunks) {
+    // one chunk: park the staged registers in the slice, start the next chunk's loads, multiply
+    auto step = [&](auto stream) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int row = 4 * j + (lane >> 4);
@@ -569,7 +546,7 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
             *reinterpret_cast<f32x4 *>(slice + row * 256 + piece * 16) = stage[j];
         }
         const int64_t chn = ch + wstride;
-        load_chunk(chn < nchunks ? chn : nchunks - 1);   // past the end: the last chunk again, never used
+        load_chunk(chn < nchunks ? chn : nchunks - 1, stream);   // past the end: the last chunk again, never used
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             f32x4 v[NT];
@@ -602,7 +579,13 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
             }
         }
         ch = chn;
-    }
+    };
+    // Chunks below cached_chunks are fetched with ordinary loads (the head of G stays in the
+    // memory-side cache for the second pass), the rest with non-temporal ones.  Two loops, not a
+    // branch per chunk: loads that differ only in that hint would be merged into one kind.
+    if (ch < nchunks) load_chunk(ch, std::false_type{});
+    while (ch < nchunks && ch + wstride < cached_chunks) step(std::false_type{});
+    while (ch < nchunks) step(std::true_type{});
 #pragma unroll
     for (int p = 0; p < NPT; ++p)
 #pragma unroll
@@ -705,8 +688,16 @@ static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchSha
     const int waves = kBlock / kWave;
     const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, NT >= 4 ? 1 : 2);
     *grid_out = grid;
+    // Non-temporal loads past the cached head pay off only when every row starts on a 128-byte line
+    // (measured at N = 16: 6.8 against 6.3 TB/s); with rows shifted against the lines a 256-byte
+    // piece shares its first and last line with its neighbours, and lines that are not kept in L2
+    // are then fetched twice (6.1 against 6.3 TB/s).  shape.cached_head_mb < 0: ordinary loads only.
+    const bool rows_on_lines = reinterpret_cast<uintptr_t>(G) % 128 == 0 && (d * (int64_t)sizeof(float)) % 128 == 0;
+    int64_t cached_chunks = nchunks + (int64_t)grid * waves;   // beyond every prefetch
+    if (shape.cached_head_mb >= 0 && rows_on_lines)
+        cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
     hipLaunchKernelGGL((gram_mfma_wave_kernel<NT>), dim3(grid), dim3(kBlock), 0, s, static_cast<const float *>(G), N,
-                       d, nchunks, tail.partials);
+                       d, nchunks, cached_chunks, tail.partials);
     return hipGetLastError();
 }
 

@@ -33,11 +33,13 @@ def sample_columns(d, seed):
     return np.unique(idx)
 
 
-@pytest.mark.parametrize("name,steps", [("C2", 20), ("C3", 1), ("C4", 2), ("C5", 3)])
-def test_full_size_configuration(pkg, name, steps):
+@pytest.mark.parametrize("name,steps,stats_only", [("C2", 20, 0), ("C3", 1, 0), ("C4", 2, 0), ("C5", 3, 0),
+                                                   ("C4", 2, 1), ("C5", 2, 1)])
+def test_full_size_configuration(pkg, name, steps, stats_only):
     w = workloads.CONFIGS[name]
     w = w.scaled(w.d, steps)
     agg = pkg.AdaCons(w.N, w.d, beta=0.99)
+    agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)   # 1: stage A1 computes diag K and row sums only
     ost = o.OracleState(w.N, beta=0.99)
     out = torch.empty(w.d, dtype=torch.float32, device=DEV)
     for t, G in enumerate(workloads.stream(w, DEV)):

@@ -394,6 +394,60 @@ def test_aggregate_apply_rejects_bad_arguments(pkg):
     agg.close()
 
 
+# --------------------------------------------------------- statistics-only first pass ----
+@pytest.mark.parametrize("N,d", [(9, 70_000), (16, 200_000), (16, 16), (17, 50_008), (32, 65_536 + 24), (33, 10_000),
+                                 (48, 30_000), (63, 10_008), (64, 131_072 + 24), (64, 8)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_statistics_only_first_pass_matches_oracle(pkg, N, d, dtype):
+    """ADACONS_TUNE_STATS_ONLY: A1 delivers only diag K and the row sums of K (what Eq. 7 consumes);
+    coefficients, momentum state and output must match the oracle over several steps, and K is
+    reported as not available."""
+    agg = pkg.AdaCons(N, d, beta=0.9)
+    agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, 1)
+    ost = o.OracleState(N, beta=0.9)
+    for t in range(3):
+        G = randG(N, d, dtype=dtype, sigma=2.0, seed=1000 * N + t)
+        both(pkg, G, agg, ost)
+    with pytest.raises(pkg.AdaConsError) as e:
+        pkg.adacons_read_gram(agg._st, N, None)
+    assert e.value.status == 1        # ADACONS_EINVAL
+    m, step = agg.export_state()
+    assert step == 3 and np.allclose(m, ost.m, rtol=1e-6, atol=0)
+    agg.gram(G)                       # a Gram call makes K available again
+    agg.close()
+
+
+def test_statistics_only_is_ignored_where_it_does_not_apply(pkg):
+    """N <= 8 and inputs off the 128-bit path keep the Gram kernels (K stays available)."""
+    for N, d, shift in [(8, 100_000, 0), (16, 100_001, 1)]:
+        flat = torch.randn(N * d + shift, device=DEV)
+        G = flat[shift:].view(N, d)
+        agg = pkg.AdaCons(N, d)
+        agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, 1)
+        both(pkg, G, agg, o.OracleState(N))
+        K = pkg.adacons_read_gram(agg._st, N, None)
+        assert rel_l2(K, o.gram(workloads.to_oracle_input(G))) <= 3e-7
+        agg.close()
+
+
+def test_statistics_only_degenerate_rows(pkg):
+    """Zero rows and identical rows through the statistics-only pass: same flags and weights."""
+    N, d = 16, 40_000
+    G = randG(N, d, sigma=1.0, seed=5)
+    G[3].zero_()
+    G[7] = G[6]
+    agg = pkg.AdaCons(N, d)
+    agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, 1)
+    ost = o.OracleState(N)
+    out = agg.aggregate(G)
+    info = agg.coeffs()
+    oout, oinfo = o.aggregate(workloads.to_oracle_input(G), ost)
+    assert info["numeric_flags"] == oinfo["numeric_flags"] != 0
+    assert_gamma_close(info["gamma"], oinfo["gamma"])
+    assert rel_l2(out.cpu().numpy(), oout) <= 1e-5
+    agg.close()
+
+
 # ------------------------------------------------------------------------- graph capture ----
 def test_aggregate_can_be_captured_in_a_hip_graph(pkg):
     """adacons_aggregate enqueues kernels only (no allocation, no synchronisation, no memset
