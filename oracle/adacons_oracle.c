@@ -32,6 +32,13 @@
  *       out[k] = sum_i gamma_i G[i,k]               Eq. 12
  * Flags (the ablation columns of Table 2): momentum off skips O4-O5 (a~ = a);
  * normalise off stops at gamma_i = c_i (lambda = 1, Eq. 8).
+ * Two documented variants, off by default:
+ *   INDEX_EMA    O4-O5 without the sort: m_i <- beta m_i + (1-beta) a_i, a~_i = m_i -- the
+ *                momentum of Eq. 10, which Sec. 3.3 then replaces by Eq. 11 because it ties a
+ *                coefficient to the worker's index.
+ *   LAMBDA_EQ13  O7 with lambda as Eq. 13 prints it, 1 / sum_k (a~_k): the coefficients on the
+ *                column-normalised subspace matrix, gamma_i ||g_i||, then sum to one, not the
+ *                weights on the raw gradients (see the first reading below).
  *
  * Readings where the paper is silent or at odds with itself:
  *   - Eq. 13 prints ||g_i|| where the weight gamma_i it normalises has
@@ -64,7 +71,12 @@
 #define ORACLE_CHUNK 65536
 
 enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
-enum { ORACLE_FLAG_MOMENTUM = 1u, ORACLE_FLAG_NORMALIZE = 2u };
+enum {
+    ORACLE_FLAG_MOMENTUM = 1u,
+    ORACLE_FLAG_NORMALIZE = 2u,
+    ORACLE_FLAG_INDEX_EMA = 4u,   /* with MOMENTUM: the EMA of Eq. 10, coupled to the worker index */
+    ORACLE_FLAG_LAMBDA_EQ13 = 8u  /* with NORMALIZE: lambda exactly as Eq. 13 prints it */
+};
 enum {
     ORACLE_NUM_ZERO_NORM = 1u,        /* some q_i == 0 */
     ORACLE_NUM_NONFINITE = 2u,        /* NaN/Inf reached the statistics */
@@ -199,7 +211,13 @@ int oracle_coefficients_from_stats(const double *q, const double *r, int N, doub
     }
 
     /* O4-O5 */
-    if (flags & ORACLE_FLAG_MOMENTUM) {
+    if ((flags & ORACLE_FLAG_MOMENTUM) && (flags & ORACLE_FLAG_INDEX_EMA)) {
+        /* Eq. 10: state entry i belongs to worker i */
+        for (int i = 0; i < N; ++i) {
+            m[i] = beta * m[i] + (1.0 - beta) * a[i];
+            as[i] = m[i];
+        }
+    } else if (flags & ORACLE_FLAG_MOMENTUM) {
         for (int i = 0; i < N; ++i) {
             int rank = 0; /* position of worker i in the stable ascending order */
             for (int j = 0; j < N; ++j)
@@ -219,10 +237,12 @@ int oracle_coefficients_from_stats(const double *q, const double *r, int N, doub
 
     /* O7 (weights) */
     if (flags & ORACLE_FLAG_NORMALIZE) {
+        /* what is made to sum to one: the weights c, or (Eq. 13 as printed) the coefficients a~ */
+        const double *w = (flags & ORACLE_FLAG_LAMBDA_EQ13) ? as : c;
         double s = 0.0, sabs = 0.0;
         for (int i = 0; i < N; ++i) {
-            s += c[i];
-            sabs += fabs(c[i]);
+            s += w[i];
+            sabs += fabs(w[i]);
         }
         if (!isfinite(s) || sabs == 0.0 || fabs(s) <= 1e-12 * sabs) {
             nf |= ORACLE_NUM_UNIFORM_FALLBACK;

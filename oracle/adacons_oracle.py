@@ -27,6 +27,8 @@ F32 = 0
 BF16 = 1
 FLAG_MOMENTUM = 1
 FLAG_NORMALIZE = 2
+FLAG_INDEX_EMA = 4      # with FLAG_MOMENTUM: index-coupled EMA of Eq. 10 instead of the sorted one of Eq. 11
+FLAG_LAMBDA_EQ13 = 8    # with FLAG_NORMALIZE: lambda as Eq. 13 prints it (sum of a~, not of the weights)
 FLAG_DEFAULT = FLAG_MOMENTUM | FLAG_NORMALIZE
 NUM_ZERO_NORM = 1
 NUM_NONFINITE = 2

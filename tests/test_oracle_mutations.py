@@ -38,6 +38,11 @@ MUTATIONS = [
      "acc += gamma[i] * elem(G, dtype, (size_t)k * N + i);\n        out[k] = acc;"),
     ("weighted_sum_drops_first_worker", "for (int i = 0; i < N; ++i)\n            acc += gamma[i] * elem(G, dtype, (size_t)i * d + k);\n        out[k] = acc;",
      "for (int i = 1; i < N; ++i)\n            acc += gamma[i] * elem(G, dtype, (size_t)i * d + k);\n        out[k] = acc;"),
+    ("index_ema_weights_swapped", "m[i] = beta * m[i] + (1.0 - beta) * a[i];", "m[i] = (1.0 - beta) * m[i] + beta * a[i];"),
+    ("index_ema_still_sorted", "if ((flags & ORACLE_FLAG_MOMENTUM) && (flags & ORACLE_FLAG_INDEX_EMA)) {",
+     "if (0) {"),
+    ("lambda_eq13_switch_ignored", "(flags & ORACLE_FLAG_LAMBDA_EQ13) ? as : c;", "(flags & ORACLE_FLAG_LAMBDA_EQ13) ? c : c;"),
+    ("lambda_eq13_always_on", "(flags & ORACLE_FLAG_LAMBDA_EQ13) ? as : c;", "(flags & ORACLE_FLAG_LAMBDA_EQ13) ? as : as;"),
     ("state_updated_on_non_finite", "nf |= ORACLE_NUM_NONFINITE | ORACLE_NUM_UNIFORM_FALLBACK;",
      "nf |= ORACLE_NUM_NONFINITE | ORACLE_NUM_UNIFORM_FALLBACK; m[0] += 1.0;"),
 ]

@@ -195,6 +195,66 @@ def test_permutation_of_workers_with_persisting_state():
         assert np.allclose(st_a.m, st_b.m, rtol=1e-13)
 
 
+def test_index_coupled_ema_is_the_plain_recurrence_and_depends_on_worker_order():
+    """Variant INDEX_EMA (Eq. 10): m_T[i] = (1-beta) sum_tau beta^(T-tau) a_tau[i] per worker index.
+    Unlike the sorted EMA of Eq. 11 it is not invariant to re-ordering the workers between steps
+    (the reason Sec. 3.3 gives for sorting), and it coincides with Eq. 11 while the coefficients
+    keep their ascending order."""
+    N, d, T, beta = 6, 300, 8, 0.8
+    flags = o.FLAG_DEFAULT | o.FLAG_INDEX_EMA
+    st = o.OracleState(N, beta=beta, flags=flags)
+    st_perm = o.OracleState(N, beta=beta, flags=flags)
+    raws, moved = [], 0.0
+    for t in range(T):
+        G = _randG(N, d, sigma=2.0)
+        out, info = o.aggregate(G, st)
+        raws.append(info["raw"].copy())
+        m_closed = sum((1 - beta) * beta ** (t - tau) * raws[tau] for tau in range(t + 1))
+        assert np.allclose(st.m, m_closed, rtol=1e-12, atol=1e-15)
+        assert np.allclose(info["smoothed"], m_closed, rtol=1e-12, atol=1e-15)
+        assert abs(info["gamma"].sum() - 1.0) < 1e-12
+        perm = np.roll(np.arange(N), t + 1)
+        out_p, _ = o.aggregate(G[perm], st_perm)
+        if t > 0:
+            moved = max(moved, np.linalg.norm(out_p - out) / np.linalg.norm(out))
+    assert moved > 1e-3
+    # orthogonal rows with norms growing with the index (a_i = ||g_i|| / N ascending at every
+    # step): the sorted and the index-coupled EMA then agree
+    st_i = o.OracleState(N, beta=beta, flags=flags)
+    st_s = o.OracleState(N, beta=beta, flags=o.FLAG_DEFAULT)
+    for t in range(4):
+        K = np.diag(np.sort(RNG.uniform(0.5, 9.0, N)))
+        a = o.coefficients(K, st_i)
+        b = o.coefficients(K, st_s)
+        assert (np.diff(a["raw"]) > 0).all()
+        assert np.allclose(a["gamma"], b["gamma"], rtol=1e-13)
+        assert np.allclose(st_i.m, st_s.m, rtol=1e-13)
+
+
+def test_lambda_as_printed_in_eq13_normalises_the_subspace_coefficients():
+    """Variant LAMBDA_EQ13: lambda = 1 / sum_k a~_k.  Then the coefficients on the column-normalised
+    subspace matrix, gamma_i ||g_i||, sum to one; the weights are the default ones times
+    sum(c) / sum(a~); identical gradients give the unit vector g / ||g|| (not the mean: why the
+    default reading normalises the weights instead)."""
+    N, d = 7, 500
+    G = _randG(N, d, sigma=1.5)
+    flags = o.FLAG_DEFAULT | o.FLAG_LAMBDA_EQ13
+    out_l, lit = o.aggregate(G, o.OracleState(N, beta=0.9, flags=flags))
+    out_d, dflt = o.aggregate(G, o.OracleState(N, beta=0.9, flags=o.FLAG_DEFAULT))
+    norms = np.linalg.norm(G.astype(np.float64), axis=1)
+    assert abs((lit["gamma"] * norms).sum() - 1.0) < 1e-12
+    c = dflt["smoothed"] / norms
+    assert np.allclose(lit["gamma"], dflt["gamma"] * c.sum() / dflt["smoothed"].sum(), rtol=1e-12)
+    assert np.allclose(lit["raw"], dflt["raw"], rtol=1e-15)
+    g = RNG.standard_normal(d).astype(np.float32)
+    out, info = o.aggregate(np.tile(g, (4, 1)), o.OracleState(4, flags=flags))
+    assert np.allclose(out, g.astype(np.float64) / np.linalg.norm(g.astype(np.float64)), rtol=1e-12)
+    # without NORMALIZE the switch has nothing to act on
+    _, a = o.aggregate(G, o.OracleState(N, flags=o.FLAG_MOMENTUM | o.FLAG_LAMBDA_EQ13))
+    _, b = o.aggregate(G, o.OracleState(N, flags=o.FLAG_MOMENTUM))
+    assert np.array_equal(a["gamma"], b["gamma"])
+
+
 def test_constant_input_gives_constant_weights_over_time():
     N, d = 6, 256
     G = _randG(N, d, sigma=1.0)
