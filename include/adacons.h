@@ -62,7 +62,14 @@ typedef enum {
 enum {
     ADACONS_FLAG_MOMENTUM = 1u,  /* sorted EMA of Eq. 11; off: a~ = a */
     ADACONS_FLAG_NORMALIZE = 2u, /* sum-to-one weights of Eq. 12-13; off: gamma_i = c_i (lambda = 1, Eq. 8) */
-    ADACONS_FLAG_DEFAULT = 3u
+    ADACONS_FLAG_DEFAULT = 3u,
+    /* Two variants the paper discusses, off by default: */
+    ADACONS_FLAG_INDEX_EMA = 4u,   /* with MOMENTUM: m_i <- beta m_i + (1-beta) a_i per worker index (Eq. 10),
+                                      the momentum Sec. 3.3 replaces by the sorted one of Eq. 11 */
+    ADACONS_FLAG_LAMBDA_EQ13 = 8u, /* with NORMALIZE: lambda = 1 / sum_k a~_k exactly as Eq. 13 prints it: the
+                                      coefficients on the column-normalised subspace matrix, gamma_i ||g_i||,
+                                      sum to one instead of the weights on the raw gradients */
+    ADACONS_FLAG_ALL_ = 15u
 };
 
 /* Bits of the numeric status word returned by adacons_coeffs(). */

@@ -19,6 +19,7 @@ ADACONS_N_MAX = 64
 ADACONS_F32, ADACONS_BF16 = 0, 1
 ADACONS_OK = 0
 ADACONS_FLAG_MOMENTUM, ADACONS_FLAG_NORMALIZE, ADACONS_FLAG_DEFAULT = 1, 2, 3
+ADACONS_FLAG_INDEX_EMA, ADACONS_FLAG_LAMBDA_EQ13 = 4, 8
 ADACONS_NUM_ZERO_NORM, ADACONS_NUM_NONFINITE, ADACONS_NUM_UNIFORM_FALLBACK = 1, 2, 4
 ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0
 ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1

@@ -152,7 +152,7 @@ adacons_status adacons_init_state(adacons_state **out_st, int N, int64_t d_max, 
     if (N > ADACONS_N_MAX) return fail(ADACONS_EUNSUPPORTED, "N=%d > ADACONS_N_MAX=%d", N, ADACONS_N_MAX);
     if (d_max < 1) return fail(ADACONS_EINVAL, "d_max < 1");
     if (!(beta >= 0.0 && beta < 1.0)) return fail(ADACONS_EINVAL, "beta=%g outside [0, 1)", beta);
-    if (flags & ~ADACONS_FLAG_DEFAULT) return fail(ADACONS_EINVAL, "unknown flag bits 0x%x", flags);
+    if (flags & ~ADACONS_FLAG_ALL_) return fail(ADACONS_EINVAL, "unknown flag bits 0x%x", flags);
 
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));

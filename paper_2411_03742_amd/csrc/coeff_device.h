@@ -14,6 +14,8 @@ namespace adacons {
 //   m[rank_i] <- beta m[rank_i] + (1 - beta) a_i ; a~_i = m[rank_i]      Eq. 11
 //   c_i = a~_i / sqrt(q_i)                             column normalisation, Eq. 8
 //   gamma_i = c_i / sum_k c_k                          Eq. 12-13 (weights sum to one)
+// Variants: ADACONS_FLAG_INDEX_EMA uses rank_i = i (Eq. 10); ADACONS_FLAG_LAMBDA_EQ13 divides by
+// sum_k a~_k instead (lambda as Eq. 13 prints it).
 // Degenerate inputs: q_i = 0 gives a_i = c_i = 0; NaN/Inf in q or r, or |sum c| <= 1e-12 sum|c|,
 // gives gamma_i = 1/N; the EMA state is not touched when a statistic is non-finite.
 // m_old: the state entry m[tid] loaded by the caller ahead of time (thread tid < N), so that the
@@ -66,10 +68,13 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
         if (s_zero) nf |= ADACONS_NUM_ZERO_NORM;
         double as = a;
         if ((cp.flags & ADACONS_FLAG_MOMENTUM) && tid < N) {
-            int rank = 0;
-            for (int j = 0; j < N; ++j) {
-                const double aj = a_sh[j];
-                rank += (aj < a || (aj == a && j < tid)) ? 1 : 0;
+            int rank = tid;   // ADACONS_FLAG_INDEX_EMA: state entry i belongs to worker i (Eq. 10)
+            if (!(cp.flags & ADACONS_FLAG_INDEX_EMA)) {
+                rank = 0;
+                for (int j = 0; j < N; ++j) {
+                    const double aj = a_sh[j];
+                    rank += (aj < a || (aj == a && j < tid)) ? 1 : 0;
+                }
             }
             // ranks are a permutation of 0..N-1: every state entry has exactly one writer
             const double mk = cp.beta * m_sh[rank] + (1.0 - cp.beta) * a;
@@ -79,7 +84,8 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
         double c = 0.0;
         if (tid < N) {
             c = (q > 0.0) ? as / sqrt(q) : 0.0;
-            c_sh[tid] = c;
+            // what is made to sum to one: the weights c, or (ADACONS_FLAG_LAMBDA_EQ13) the coefficients a~
+            c_sh[tid] = (cp.flags & ADACONS_FLAG_LAMBDA_EQ13) ? as : c;
         }
         __syncthreads();
         if (tid == 0) {

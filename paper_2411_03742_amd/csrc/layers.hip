@@ -277,7 +277,7 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     if (N > kLayersMaxN) return lfail(ADACONS_EUNSUPPORTED, "layer-wise aggregation supports N <= 8");
     if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return lfail(ADACONS_EUNSUPPORTED, "unknown dtype");
     if (!(beta >= 0.0 && beta < 1.0)) return lfail(ADACONS_EINVAL, "beta outside [0, 1)");
-    if (flags & ~ADACONS_FLAG_DEFAULT) return lfail(ADACONS_EINVAL, "unknown flag bits");
+    if (flags & ~ADACONS_FLAG_ALL_) return lfail(ADACONS_EINVAL, "unknown flag bits");
     if (offsets_host[0] != 0) return lfail(ADACONS_EINVAL, "offsets[0] must be 0");
     for (int l = 0; l < L; ++l)
         if (offsets_host[l + 1] <= offsets_host[l]) return lfail(ADACONS_EINVAL, "offsets must ascend strictly");

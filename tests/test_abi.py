@@ -58,7 +58,7 @@ def test_argument_validation_needs_no_gpu(lib):
     assert cdll.adacons_init_state(ctypes.byref(st), 4, 0, 0.9, 3, None) == EINVAL
     assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, 1.0, 3, None) == EINVAL
     assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, float("nan"), 3, None) == EINVAL
-    assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, 0.9, 8, None) == EINVAL
+    assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, 0.9, 16, None) == EINVAL
     assert st.value is None
     # NULL state handles are rejected by every call that takes one
     cdll.adacons_aggregate.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int,

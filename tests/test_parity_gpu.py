@@ -161,15 +161,21 @@ def test_config_streams_at_test_size(pkg, name, d, steps):
     agg.close()
 
 
-@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("flags", [0, 1, 2, 3, 5, 7, 10, 11, 15])
 @pytest.mark.parametrize("N", [5, 8, 16])
 def test_ablation_variants(pkg, flags, N):
-    """The four columns of Table 2: momentum and normalisation on/off."""
+    """The four columns of Table 2 (momentum and normalisation on/off), and the two variants:
+    +4 the index-coupled EMA of Eq. 10, +8 lambda as Eq. 13 prints it."""
     d = 150_000
     agg = pkg.AdaCons(N, d, beta=0.9, flags=flags)
     ost = o.OracleState(N, beta=0.9, flags=flags)
     for t in range(4):
-        both(pkg, randG(N, d, sigma=2.0, seed=100 + t), agg, ost)
+        G = randG(N, d, sigma=2.0, seed=100 + t)
+        if flags & 4:
+            G = G[torch.roll(torch.arange(N), t).to(DEV)].contiguous()   # worker order matters for Eq. 10
+        both(pkg, G, agg, ost)
+    m, _ = agg.export_state()
+    assert np.allclose(m, ost.m, rtol=1e-6, atol=1e-12)
     agg.close()
 
 
