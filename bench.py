@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the read-only and copy rates measured on this box for context")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="REPS",
                     help="after the timed region, run REPS plain device copies of G (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled to bytes")
@@ -129,6 +131,21 @@ def main() -> int:
         "stages_GBps": {k: round(v[0] / (v[1] * 1e-3) / 1e9, 1) for k, v in stages.items()},
     }
 
+    # ---- per-call spread: each call bracketed by its own event pair (separate from the timed region:
+    # an event record costs a few microseconds on the stream) -------------------------------------
+    ncall = min(args.steps, 200)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(ncall)]
+    for i, (a, b) in enumerate(pairs):
+        a.record(stream)
+        agg.aggregate(bufs[i % 2], out=out, stream=stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    per_call = sorted(a.elapsed_time(b) for a, b in pairs)
+    pct = lambda q: round(per_call[min(ncall - 1, int(q * ncall))], 5)
+    per_call_ms = {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "calls": ncall}
+
+    ceilings = measured_ceilings(w, bufs, out, stream) if not args.no_ceilings else None
+
     if args.copy_calibration > 0:
         scratch = torch.empty_like(bufs[0])
         for _ in range(args.copy_calibration):
@@ -153,6 +170,8 @@ def main() -> int:
         "aggregations_per_s": round(1e3 / ms_per_step, 1),
         "gradients_per_s": round(w.N * 1e3 / ms_per_step, 1),
         "algorithmic_bytes_per_step": floor,
+        "per_call_ms": per_call_ms,
+        "measured_ceilings": ceilings,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
@@ -197,6 +216,46 @@ def bench_layers(args, w, bufs, out) -> int:
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2), "roofline": None, "cpu_baseline": None}))
     agg.close()
     return 0
+
+
+def measured_ceilings(w, bufs, out, stream) -> dict:
+    """Context for the roofline fraction: what this machine delivers for a read-only stream and for a
+    plain copy of the same buffers.  Read-only: the library's two-vector statistics kernel
+    (adacons_worker_stats: reads two vectors once, writes three doubles) over the two halves of G;
+    copy: a device-to-device copy of G (reads and writes N*d elements)."""
+    import torch
+    import paper_2411_03742_amd as ada
+
+    G = bufs[0]
+    half = (w.N // 2) * w.d
+    if half < 1:
+        return None
+    flat = G.reshape(-1)
+    x, y = flat[:half], flat[half:2 * half]
+    probe = ada.AdaCons(2, half)
+    reps = 20
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        probe.worker_stats(x, y, stream=stream)
+    e0.record(stream)
+    for _ in range(reps):
+        probe.worker_stats(x, y, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    read_gbps = 2 * half * G.element_size() / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
+    probe.close()
+    dst = bufs[1]
+    for _ in range(3):
+        dst.copy_(G)
+    e0.record(stream)
+    for _ in range(reps):
+        dst.copy_(G)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbps = 2 * G.numel() * G.element_size() / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
+    return {"read_only_GBps": round(read_gbps, 1), "copy_GBps": round(copy_gbps, 1), "unit": "GB/s",
+            "note": "read-only: two-vector statistics kernel over G's halves; copy: device-to-device copy of G "
+                    "(bytes read + written)"}
 
 
 def cpu_baseline(w, G) -> dict:
