@@ -23,12 +23,23 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
-# Bytes per launch that crossed the L2 <-> memory fabric, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script, scaled by the readings of a plain device copy of known size
-# (profiles/c2_n8_d25557032_f32_hbm_traffic_pmc.txt).  Fetched + written.
+# Bytes per launch that crossed the L2 <-> memory fabric (fetched + written), from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE runs of this script, scaled by the readings of a plain device copy of
+# known size in the same run (profiles/*_hbm_traffic_pmc.txt).  Default launch configuration,
+# except the entry with a tuning tuple.
 PMC_TRAFFIC_BYTES = {
-    ("C2", "gram_kernel (A1)"): 826_750_000 + 70_000,
-    ("C2", "wsum_kernel (A3)"): 856_950_000 + 102_230_000,
+    ("C1", "gram_kernel (A1)", ()): 16_802_265 + 24_576,
+    ("C1", "wsum_kernel (A3)", ()): 16_791_019 + 4_194_304,
+    ("C2", "gram_kernel (A1)", ()): 826_843_043 + 73_728,
+    ("C2", "wsum_kernel (A3)", ()): 857_044_343 + 102_228_128,
+    ("C3", "gram_kernel (A1)", ()): 5_362_251_980 + 147_456,
+    ("C3", "wsum_kernel (A3)", ()): 5_362_184_750 + 1_340_567_605,
+    ("C4", "gram_kernel (A1)", ()): 6_619_333_022 + 4_259_840,
+    ("C4", "wsum_kernel (A3)", ()): 7_018_929_123 + 102_228_128,
+    ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_823_823_468 + 262_144,
+    ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 7_019_207_350 + 102_228_128,
+    ("C5", "gram_kernel (A1)", ()): 7_964_256_303 + 557_057,
+    ("C5", "wsum_kernel (A3)", ()): 7_964_089_907 + 497_759_232,
 }
 
 
@@ -125,7 +136,7 @@ def main() -> int:
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": PMC_TRAFFIC_BYTES.get((args.workload, dom)),
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": PMC_TRAFFIC_BYTES.get((args.workload, dom, tuple(sorted(tuned.items())))),
         "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 5),
         "stages_ms": dict({k: round(v[1], 5) for k, v in stages.items()}, **{"finish_kernel (A2)": round(prof["coeff_ms"], 5)}),
         "stages_GBps": {k: round(v[0] / (v[1] * 1e-3) / 1e9, 1) for k, v in stages.items()},

@@ -39,6 +39,28 @@ __device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, 
     }
 }
 
+// Eight columns per lane (bf16 inputs): a lane's two 16-byte stores would each fill every other
+// 16 bytes of the wavefront's 2 KB of output, i.e. half of every 32-byte sector per instruction.
+// Exchanged across the wavefront first, each store instruction writes 1 KB without gaps: lane l
+// takes columns 4 l .. 4 l + 3 of the first half from lane l / 2 and of the second half from
+// lane 32 + l / 2.  All 64 lanes must be active.  `wave_col` is the first column of the wavefront.
+__device__ __forceinline__ void store_out_wave8(float *__restrict__ out, int64_t wave_col, const float (&acc)[8]) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int odd = lane & 1;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int src = h * 32 + (lane >> 1);
+        float v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float lo = __shfl(acc[c], src, kWave), hi = __shfl(acc[4 + c], src, kWave);
+            v[c] = odd ? hi : lo;
+        }
+        const f32x4 x = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + wave_col + h * 256 + lane * 4));
+    }
+}
+
 // One tile = kBlock * UNR column groups: thread t owns groups base + u * kBlock, u < UNR.
 // FULL: every group of the tile exists, so the loads carry no predicate and are all issued
 // before the first use.
@@ -72,9 +94,15 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
                     for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w, v[u][ii][c], acc[u][c]);
                 }
     }
+    if constexpr (FULL && !APPLY && VEC == 8) {
+        const int64_t wave_base = base - (threadIdx.x & (kWave - 1));   // group of lane 0
 #pragma unroll
-    for (int u = 0; u < UNR; ++u)
-        if (live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * kBlock) * VEC, acc[u], lr);
+        for (int u = 0; u < UNR; ++u) store_out_wave8(out, (wave_base + (int64_t)u * kBlock) * VEC, acc[u]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+            if (live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * kBlock) * VEC, acc[u], lr);
+    }
 }
 
 // NCT > 0: N known at compile time (rows fully unrolled, weights in registers, N <= 16);
@@ -126,7 +154,11 @@ static hipError_t run_as(const void *G, int N, int64_t d, const LaunchShape &sha
     static const int occ = occupancy(wsum_kernel<NCT, T, VEC, UNR, APPLY>);
     const int64_t ngroups = (d + VEC - 1) / VEC;
     const int64_t work = (ngroups + (int64_t)kBlock * UNR - 1) / ((int64_t)kBlock * UNR);
-    int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 8;
+    // Measured: eight workgroups per CU while G is small enough for the memory-side cache to matter
+    // (N = 8, 0.8 GB: 138 us against 150 us at one per CU); one per CU for long streams of few rows
+    // (N <= 8, 1.6 GB and up: 2-7 % faster); N >= 16 shows no preference beyond noise.
+    const bool long_stream = N <= 8 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 28;   // 1.25 GiB
+    int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : (long_stream ? 1 : 8);
     if (per_cu > occ) per_cu = occ;
     int64_t grid = (int64_t)shape.num_cu * per_cu;
     if (grid > work) grid = work;
