@@ -56,7 +56,7 @@ def main() -> int:
                     help="after the timed region, run REPS plain device copies of G (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled to bytes")
     ap.add_argument("--layers", choices=["resnet50"], default=None,
-                    help="time the layer-wise entry point instead (C2 only): one coefficient set per "
+                    help="time the layer-wise entry point instead (C2 or C4): one coefficient set per "
                          "parameter tensor of a ResNet-50; not the headline metric")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass / cached_head_mb / "
@@ -198,8 +198,8 @@ def bench_layers(args, w, bufs, out) -> int:
     import workloads
     import paper_2411_03742_amd as ada
 
-    if args.workload != "C2":
-        print("bench.py: --layers resnet50 goes with --workload C2", file=sys.stderr)
+    if w.d != sum(workloads.resnet50_layer_sizes()):
+        print("bench.py: --layers resnet50 goes with a workload of d = 25,557,032 (C2 or C4)", file=sys.stderr)
         return 2
     off = np.concatenate([[0], np.cumsum(workloads.resnet50_layer_sizes())]).astype(np.int64)
     agg = ada.AdaConsLayers(w.N, off, beta=0.99)

@@ -258,7 +258,9 @@ adacons_status adacons_worker_scale(void *g, int64_t d, adacons_dtype dtype, con
  * performs similarly.  Here the d columns are split into L contiguous segments ("layers"); every
  * layer gets its own Gram matrix, its own coefficients and its own Eq. 11 momentum state, i.e. the
  * steps A1-A3 above run independently on G[:, offsets[l] : offsets[l+1]) for every l, in three
- * launches for all layers together.  Supported for N <= 8 on the 128-bit path.
+ * launches for all layers together.  128-bit path only.  For N <= 8 stage A1 forms every layer's
+ * Gram matrix; for N > 8 it forms what Eq. 7 consumes of it, ||g_i||^2 and <g_i, sum_j g_j> over the
+ * layer's columns (Alg. 1 steps 1-2 per layer).
  */
 typedef struct adacons_layers adacons_layers; /* opaque, library-owned */
 
@@ -266,13 +268,13 @@ typedef struct adacons_layers adacons_layers; /* opaque, library-owned */
  * Build the per-layer state (L zero-initialised momentum vectors, tile tables, workspaces) on the
  * current device.  Allocates; synchronises `hip_stream` once.
  *   ls            out: receives the handle
- *   N             workers, 1 <= N <= 8
+ *   N             workers, 1 <= N <= ADACONS_N_MAX
  *   L             number of layers, >= 1
  *   offsets_host  host pointer, L + 1 ascending column offsets, offsets[0] = 0, offsets[L] = d;
  *                 empty layers (equal consecutive offsets) are not allowed
  *   dtype         element type later calls will pass (fixes the tile geometry)
  *   beta, flags   as in adacons_init_state
- * Errors: EINVAL, EUNSUPPORTED (N > 8), ENOMEM, EHIP.
+ * Errors: EINVAL, EUNSUPPORTED (N > ADACONS_N_MAX, unknown dtype), ENOMEM, EHIP.
  */
 adacons_status adacons_init_layers(adacons_layers **ls, int N, int L, const int64_t *offsets_host,
                                    adacons_dtype dtype, double beta, unsigned flags, void *hip_stream);

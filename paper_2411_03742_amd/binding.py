@@ -284,7 +284,7 @@ def adacons_layer_coeffs(ls, N: int, L: int, stream=None) -> dict:
 
 # ---- small convenience wrappers that own a state ------------------------------------------
 class AdaConsLayers:
-    """Layer-wise aggregation: one coefficient stream per contiguous column segment (N <= 8)."""
+    """Layer-wise aggregation: one coefficient stream per contiguous column segment."""
 
     def __init__(self, N: int, offsets, dtype: torch.dtype = torch.float32, beta: float = 0.99,
                  flags: int = ADACONS_FLAG_DEFAULT, stream=None):

@@ -15,6 +15,10 @@
 //   A2  one workgroup per layer adds that layer's partial rows in a fixed order and runs the
 //       coefficient update on the layer's own state.
 //   A3  grid-stride over the runs; the run's layer selects the weights.
+// N <= 8 keeps the whole Gram matrix of a column group in one thread's registers.  For N > 8 stage
+// A1 computes per layer what Eq. 7 consumes -- q_i = ||g_i||^2 and r_i = <g_i, sum_j g_j> over the
+// layer's columns -- with the wavefront-cooperative scheme of the statistics-only pass: a chunk
+// of 16 column groups of all N rows lives in the registers of one wavefront.
 #include <algorithm>
 #include <cstring>
 #include <new>
@@ -33,7 +37,7 @@ struct LayerRun {
     int layer;
 };
 
-constexpr int kLayersMaxN = 8;
+constexpr int kLayersMaxN = 8;           // largest N with the Gram matrix per thread; above: statistics
 constexpr int kRunGroups = 16 * kBlock;   // column groups per run: 16 sweeps of a workgroup
 
 // ------------------------------------------------------------------------------------------
@@ -107,6 +111,111 @@ gram_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
     }
 }
 
+// A1 for N > 8.  Same run bookkeeping as above; inside a run wavefront w takes the chunks
+// w, w + 4, ... of 16 column groups.  Load j of a chunk: row 4 j + lane / 16, group lane % 16
+// (four rows by 256 contiguous bytes per instruction).  Column sums s over the rows (in-lane, then
+// across the four lane groups), then q_i += <v_i, v_i>, r_i += <v_i, s> in fp64.  Groups past the
+// end of the run and columns of a straddling group that belong to the neighbouring layer are
+// zeroed.  One partial row [q_0 .. q_{N-1}, r_0 .. r_{N-1}] per run.
+template <typename T> __device__ __forceinline__ void widen_bits(const u32x4 x, float (&v)[VecWidth<T>::value]);
+template <> __device__ __forceinline__ void widen_bits<float>(const u32x4 x, float (&v)[4]) {
+    v[0] = __uint_as_float(x.x); v[1] = __uint_as_float(x.y); v[2] = __uint_as_float(x.z); v[3] = __uint_as_float(x.w);
+}
+template <> __device__ __forceinline__ void widen_bits<bf16_bits>(const u32x4 x, float (&v)[8]) { unpack_bf16x8(x, v); }
+
+template <int NT, typename T>
+__global__ void __launch_bounds__(kBlock, (NT * VecWidth<T>::value >= 16) ? 1 : 2)
+stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *__restrict__ runs, int nruns,
+                    const int *__restrict__ order, unsigned *__restrict__ ticket, double *__restrict__ partials) {
+    constexpr int VECW = VecWidth<T>::value;
+    constexpr int kLoads = 4 * NT;
+    __shared__ double lds[kBlock / kWave][2 * kNMax];
+    __shared__ unsigned s_next;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int grp = lane >> 4, cl = lane & 15;
+    if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);
+    __syncthreads();
+    unsigned tk = s_next;
+    while (tk < (unsigned)nruns) {   // tk is workgroup-uniform
+        __syncthreads();             // everyone has read s_next and the previous run's LDS sums
+        if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);   // next ticket: in flight during this run
+        const int r = order[tk];
+        const LayerRun run = runs[r];
+        double qacc[kLoads], racc[kLoads];
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) qacc[j] = racc[j] = 0.0;
+        const int64_t g_end = run.g0 + run.n;
+        const int nchunks = (run.n + 15) / 16;
+        for (int c = wave; c < nchunks; c += kBlock / kWave) {
+            const int64_t g = run.g0 + 16 * (int64_t)c + cl;
+            const bool in_run = g < g_end;
+            const int64_t gc = in_run ? g : g_end - 1;          // clamped: always a group of this run
+            const int64_t c0 = gc * VECW;
+            u32x4 x[kLoads];
+#pragma unroll
+            for (int j = 0; j < kLoads; ++j) {
+                const int row = 4 * j + grp;
+                const int rowc = row < N ? row : N - 1;
+                x[j] = *reinterpret_cast<const u32x4 *>(G + (int64_t)rowc * d + c0);
+            }
+            // per-column mask: inside the run, inside the layer (only the first and last group of a
+            // run can straddle a boundary), and a row that exists
+            bool live[VECW];
+#pragma unroll
+            for (int k = 0; k < VECW; ++k) live[k] = in_run && c0 + k >= run.cb && c0 + k < run.ce;
+            double ssum[VECW];
+#pragma unroll
+            for (int k = 0; k < VECW; ++k) ssum[k] = 0.0;
+#pragma unroll
+            for (int j = 0; j < kLoads; ++j) {
+                float v[VECW];
+                widen_bits<T>(x[j], v);
+                const bool row_ok = 4 * j + grp < N;
+#pragma unroll
+                for (int k = 0; k < VECW; ++k) ssum[k] += (row_ok && live[k]) ? (double)v[k] : 0.0;
+            }
+#pragma unroll
+            for (int k = 0; k < VECW; ++k) {
+                ssum[k] += __shfl_xor(ssum[k], 16, kWave);
+                ssum[k] += __shfl_xor(ssum[k], 32, kWave);
+            }
+#pragma unroll
+            for (int j = 0; j < kLoads; ++j) {
+                float v[VECW];
+                widen_bits<T>(x[j], v);
+                const bool row_ok = 4 * j + grp < N;
+#pragma unroll
+                for (int k = 0; k < VECW; ++k) {
+                    const double y = (row_ok && live[k]) ? (double)v[k] : 0.0;
+                    qacc[j] = fma(y, y, qacc[j]);
+                    racc[j] = fma(y, ssum[k], racc[j]);
+                }
+            }
+        }
+        // the sixteen lanes of a group in a fixed butterfly order, then the wavefronts in index order
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            double q = qacc[j], rr = racc[j];
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) {
+                q += __shfl_xor(q, off, kWave);
+                rr += __shfl_xor(rr, off, kWave);
+            }
+            if (cl == 0) {
+                lds[wave][4 * j + grp] = q;
+                lds[wave][kNMax + 4 * j + grp] = rr;
+            }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < 2 * N) {
+            const int t = threadIdx.x;
+            const int e = t < N ? t : kNMax + (t - N);
+            partials[(size_t)r * (2 * N) + t] = ((lds[0][e] + lds[1][e]) + lds[2][e]) + lds[3][e];
+        }
+        tk = s_next;   // written by thread 0 before the barrier above
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // A2: one workgroup per layer
 // ------------------------------------------------------------------------------------------
@@ -117,7 +226,8 @@ finish_layers_kernel(const double *__restrict__ partials, const int *__restrict_
     if (blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;   // A1 is over: ready for the next call
     __shared__ double lds[4 * kNMax];
     __shared__ double K_lds[kLayersMaxN * kLayersMaxN];
-    const int l = blockIdx.x, N = cp.N, np = num_pairs(N);
+    const bool stats = cp.N > kLayersMaxN;                   // rows hold [q, r] instead of the packed K
+    const int l = blockIdx.x, N = cp.N, np = stats ? 2 * N : num_pairs(N);
     DevState *ds = ds_all + l;
     const double m_old = ((int)threadIdx.x < N) ? ds->m[threadIdx.x] : 0.0;
     const int e0 = layer_entry0[l], e1 = layer_entry0[l + 1];
@@ -130,6 +240,17 @@ finish_layers_kernel(const double *__restrict__ partials, const int *__restrict_
         slice_sum[sl * np + pp] = acc;
     }
     __syncthreads();
+    if (stats) {
+        double q = 0.0, r = 0.0;
+        if ((int)threadIdx.x < N) {
+            for (int k = 0; k < slices; ++k) {
+                q += slice_sum[k * np + threadIdx.x];
+                r += slice_sum[k * np + N + threadIdx.x];
+            }
+        }
+        update_coefficients_from_stats(q, r, ds, cp, lds, m_old);
+        return;
+    }
     if ((int)threadIdx.x < np) {
         const int p = threadIdx.x;
         double tot = 0.0;
@@ -197,6 +318,84 @@ wsum_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
                     if (c0 + c >= cb && c0 + c < ce) out[c0 + c] = acc[c];
             }
         }
+    }
+}
+
+// A3 for N > 8: the number of rows is a run-time value, rows are walked eight at a time, the
+// weights are read through uniform (scalar) loads of the run's layer.
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kBlock)
+wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *__restrict__ runs, int nruns,
+                      const DevState *__restrict__ ds_all, float *__restrict__ out) {
+    constexpr int kWsumSplit = 8, kPiece = kRunGroups / kWsumSplit;
+    const int grid = (int)gridDim.x, b = (int)blockIdx.x;
+    const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;   // XCD-contiguous pieces
+    const int64_t npieces = (int64_t)nruns * kWsumSplit;
+    for (int64_t pc = slot; pc < npieces; pc += grid) {
+        const LayerRun run = runs[pc / kWsumSplit];
+        const int first = (int)(pc % kWsumSplit) * kPiece;
+        if (first >= run.n) continue;
+        const int last = (first + kPiece < run.n) ? first + kPiece : run.n;
+        const float *gam = ds_all[run.layer].gamma32;
+        const int64_t cb = run.cb, ce = run.ce;
+        for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
+            const int64_t c0 = (run.g0 + k) * VEC;
+            float acc[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+            for (int i0 = 0; i0 < N; i0 += 8) {
+                float v[8][VEC];
+#pragma unroll
+                for (int ii = 0; ii < 8; ++ii)
+                    if (i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + c0, v[ii]);
+#pragma unroll
+                for (int ii = 0; ii < 8; ++ii)
+                    if (i0 + ii < N) {
+                        const float w = gam[i0 + ii];
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w, v[ii][c], acc[c]);
+                    }
+            }
+            if (c0 >= cb && c0 + VEC <= ce) {
+#pragma unroll
+                for (int c = 0; c < VEC; c += 4) {
+                    const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+                    __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + c0 + c));
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c)
+                    if (c0 + c >= cb && c0 + c < ce) out[c0 + c] = acc[c];
+            }
+        }
+    }
+}
+
+template <int NT, typename T, int VEC>
+static hipError_t run_layers_stats(const void *G, int N, int64_t d, const LayerRun *runs, int nruns, const int *order,
+                                   int gram_grid, int wsum_grid, const int *layer_entry0, int L, double *partials,
+                                   double *K_all, DevState *ds_all, unsigned *ticket, CoeffParams cp, float *out,
+                                   hipStream_t s) {
+    hipLaunchKernelGGL((stats_layers_kernel<NT, T>), dim3(gram_grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N,
+                       d, runs, nruns, order, ticket, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(finish_layers_kernel, dim3(L), dim3(kLayerFinishBlock), 0, s, partials, layer_entry0, K_all,
+                       ds_all, cp, ticket);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((wsum_layers_rt_kernel<T, VEC>), dim3(wsum_grid), dim3(kBlock), 0, s, static_cast<const T *>(G),
+                       N, d, runs, nruns, ds_all, out);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC, typename... A>
+static hipError_t dispatch_layers_stats(int N, const void *G, A... a) {
+    switch ((N + 15) / 16) {
+        case 1: return run_layers_stats<1, T, VEC>(G, N, a...);
+        case 2: return run_layers_stats<2, T, VEC>(G, N, a...);
+        case 3: return run_layers_stats<3, T, VEC>(G, N, a...);
+        case 4: return run_layers_stats<4, T, VEC>(G, N, a...);
+        default: return hipErrorInvalidValue;
     }
 }
 
@@ -274,7 +473,7 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     *out_ls = nullptr;
     if (!offsets_host) return lfail(ADACONS_EINVAL, "offsets_host is NULL");
     if (N < 1 || L < 1) return lfail(ADACONS_EINVAL, "N < 1 or L < 1");
-    if (N > kLayersMaxN) return lfail(ADACONS_EUNSUPPORTED, "layer-wise aggregation supports N <= 8");
+    if (N > kNMax) return lfail(ADACONS_EUNSUPPORTED, "N > ADACONS_N_MAX");
     if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return lfail(ADACONS_EUNSUPPORTED, "unknown dtype");
     if (!(beta >= 0.0 && beta < 1.0)) return lfail(ADACONS_EINVAL, "beta outside [0, 1)");
     if (flags & ~ADACONS_FLAG_ALL_) return lfail(ADACONS_EINVAL, "unknown flag bits");
@@ -331,7 +530,7 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     ls->wsum_grid = prop.multiProcessorCount * 8;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int np = num_pairs(N);
+    const int np = N > kLayersMaxN ? 2 * N : num_pairs(N);   // doubles per partial row
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&ls->runs), sizeof(LayerRun) * (size_t)nruns);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->offsets), sizeof(int64_t) * (size_t)(L + 1));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->layer_entry0), sizeof(int) * (size_t)(L + 1));
@@ -369,7 +568,16 @@ adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons
     cp.N = N; cp.beta = ls->beta; cp.flags = ls->flags;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
-    if (dtype == ADACONS_F32)
+    if (N > kLayersMaxN) {
+        if (dtype == ADACONS_F32)
+            e = dispatch_layers_stats<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order,
+                                                ls->gram_grid, ls->wsum_grid, (const int *)ls->layer_entry0, ls->L,
+                                                ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
+        else
+            e = dispatch_layers_stats<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order,
+                                                    ls->gram_grid, ls->wsum_grid, (const int *)ls->layer_entry0, ls->L,
+                                                    ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
+    } else if (dtype == ADACONS_F32)
         e = dispatch_layers<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
                                       (const int64_t *)ls->offsets, (const int *)ls->layer_entry0, ls->L, ls->partials,
                                       ls->K, ls->ds, ls->ticket, cp, out, s);
