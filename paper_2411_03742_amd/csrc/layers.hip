@@ -45,13 +45,13 @@ constexpr int kRunGroups = 16 * kBlock;   // column groups per run: 16 sweeps of
 // ------------------------------------------------------------------------------------------
 // N 128-bit loads of column group g and the N(N+1)/2 fp64 FMAs per column; columns outside
 // [cb, ce) (the other layer's part of a straddling group) count as zero.
-template <int N, typename T, int VEC, bool EDGE>
+template <int N, typename T, int VEC, bool EDGE, bool STREAM>
 __device__ __forceinline__ void gram_layers_step(const T *__restrict__ G, int64_t d, int64_t g, int64_t cb, int64_t ce,
                                                  double (&acc)[N * (N + 1) / 2]) {
     const int64_t c0 = g * VEC;
     float v[N][VEC];
 #pragma unroll
-    for (int i = 0; i < N; ++i) load_vec<T, VEC, false>(G + (int64_t)i * d + c0, v[i]);
+    for (int i = 0; i < N; ++i) load_vec<T, VEC, STREAM>(G + (int64_t)i * d + c0, v[i]);
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
         const bool live = !EDGE || (c0 + c >= cb && c0 + c < ce);
@@ -72,7 +72,8 @@ __device__ __forceinline__ void gram_layers_step(const T *__restrict__ G, int64_
 template <int N, typename T, int VEC>
 __global__ void __launch_bounds__(kBlock, 2)
 gram_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restrict__ runs, int nruns,
-                   const int *__restrict__ order, unsigned *__restrict__ ticket, double *__restrict__ partials) {
+                   const int *__restrict__ order, unsigned *__restrict__ ticket, double *__restrict__ partials,
+                   int64_t cached_groups) {
     constexpr int NP = N * (N + 1) / 2;
     __shared__ double lds[4 * NP];
     __shared__ unsigned s_next;
@@ -89,12 +90,24 @@ gram_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
 #pragma unroll
         for (int p = 0; p < NP; ++p) acc[p] = 0.0;
         const int64_t g_end = run.g0 + run.n;
-        // only the first and the last group of a run can straddle a layer boundary
-        for (int64_t g = run.g0 + threadIdx.x; g < g_end; g += kBlock) {
-            if (g == run.g0 || g == g_end - 1)
-                gram_layers_step<N, T, VEC, true>(G, d, g, run.cb, run.ce, acc);
-            else
-                gram_layers_step<N, T, VEC, false>(G, d, g, run.cb, run.ce, acc);
+        // Only the first and the last group of a run can straddle a layer boundary.  Runs in the
+        // head of G (below cached_groups) use ordinary loads, so that the head stays in the
+        // memory-side cache for stage A3; the others stream past the caches.  Two loops: loads
+        // that differ only in that hint would otherwise be merged into one kind.
+        if (run.g0 < cached_groups) {
+            for (int64_t g = run.g0 + threadIdx.x; g < g_end; g += kBlock) {
+                if (g == run.g0 || g == g_end - 1)
+                    gram_layers_step<N, T, VEC, true, false>(G, d, g, run.cb, run.ce, acc);
+                else
+                    gram_layers_step<N, T, VEC, false, false>(G, d, g, run.cb, run.ce, acc);
+            }
+        } else {
+            for (int64_t g = run.g0 + threadIdx.x; g < g_end; g += kBlock) {
+                if (g == run.g0 || g == g_end - 1)
+                    gram_layers_step<N, T, VEC, true, true>(G, d, g, run.cb, run.ce, acc);
+                else
+                    gram_layers_step<N, T, VEC, false, true>(G, d, g, run.cb, run.ce, acc);
+            }
         }
         // workgroup sum in a fixed order into this run's partial row
         {
@@ -403,8 +416,10 @@ template <int N, typename T, int VEC>
 static hipError_t run_layers(const void *G, int64_t d, const LayerRun *runs, int nruns, const int *order, int gram_grid, int wsum_grid,
                              const int64_t *offsets, const int *layer_entry0, int L, double *partials, double *K_all,
                              DevState *ds_all, unsigned *ticket, CoeffParams cp, float *out, hipStream_t s) {
+    // the first 320 MiB of G with cache-allocating loads (same policy as the model-wise stage A1)
+    const int64_t cached_groups = ((int64_t)320 << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
     hipLaunchKernelGGL((gram_layers_kernel<N, T, VEC>), dim3(gram_grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), d, runs, nruns, order, ticket, partials);
+                       static_cast<const T *>(G), d, runs, nruns, order, ticket, partials, cached_groups);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(finish_layers_kernel, dim3(L), dim3(kLayerFinishBlock), 0, s, partials, layer_entry0, K_all,
