@@ -36,14 +36,15 @@ __device__ __forceinline__ void unpack_pair(int p, int N, int &i, int &j) {
     j = row + left;
 }
 
-// K[i][j] = K[j][i] = sum over rows of partials[.][p]: blockDim.x / np interleaved sub-sums per
+// K[i][j] = K[j][i] = sum over rows of partials[.][p]: min(blockDim.x / np, 32) interleaved sub-sums per
 // pair, added in slice order.  One workgroup, N(N+1)/2 <= blockDim.x; lds >= blockDim.x doubles.
 // When K_lds is given, K is also left there (N x N) for the coefficient update that follows.
 __device__ void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds,
                                     double *K_lds = nullptr) {
     const int np = num_pairs(N);
     const int tid = threadIdx.x;
-    const int slices = (int)blockDim.x / np;
+    // at most 32 slices: the slice sums are added one after the other by a single thread per pair
+    const int slices = ((int)blockDim.x / np < 32) ? (int)blockDim.x / np : 32;
     const int s = tid / np, p = tid - s * np;
     if (s < slices) lds[s * np + p] = sum_rows(partials, np, p, s, slices, nrows);
     __syncthreads();
