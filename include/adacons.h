@@ -189,8 +189,12 @@ typedef enum {
                                              path); otherwise those kernels use ordinary loads throughout */
     ADACONS_TUNE_MFMA_DIRECT_LOADS = 5,   /* A1, N > 8: 1 = matrix-core operands loaded straight from memory;
                                              0 = workgroup tiles staged through LDS with coalesced loads;
-                                             2 (default) = coalesced loads, per-wavefront transpose through
-                                             LDS (fp32 on the 128-bit path; other inputs take variant 1) */
+                                             2 = coalesced loads, per-wavefront transpose through
+                                             LDS; 3 = as 2, with every fp32 product formed from six exact bf16
+                                             products on the sixteen times faster bf16 matrix-core path (fp32
+                                             = sum of three bf16; dropped terms < 2^-24 of the product).
+                                             4 (default) = 3 for N > 48, else 2.
+                                             2 and 3: fp32 on the 128-bit path; other inputs take variant 1 */
     ADACONS_TUNE_STATS_ONLY = 6,          /* 1: for N > 8 stage A1 computes only what Eq. 7 consumes, the diagonal
                                              of K and its row sums (||g_i||^2 and <g_i, sum_j g_j>: Alg. 1
                                              steps 1-2), in O(N) operations per column; K itself is then not

@@ -56,7 +56,7 @@ struct LaunchShape {
     int blocks_per_cu;  // <= 0: let the launcher decide
     int max_rows;       // capacity of the partials workspace in rows
     int cached_head_mb; // stage A1: MiB at the head of G read with cache-allocating loads; < 0: all
-    int mfma_direct;    // stage A1, N > 8: 1 = operand-layout loads straight from memory, 0 = LDS-staged tiles
+    int mfma_direct;    // stage A1, N > 8: value of ADACONS_TUNE_MFMA_DIRECT_LOADS (which matrix-core kernel)
 };
 
 // gram.hip

@@ -52,7 +52,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 2, 0};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 4, 0};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 

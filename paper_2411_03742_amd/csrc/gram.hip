@@ -597,6 +597,145 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
 }
 
 // ------------------------------------------------------------------------------------------
+// A1, 8 < N <= 64, fp32, 128-bit path: products on the bf16 matrix-core path, fp32-exact by splitting
+// ------------------------------------------------------------------------------------------
+// The fp32 matrix-core instruction multiplies 32 element pairs per cycle and SIMD; the bf16 one
+// sixteen times as many.  An fp32 value is the exact sum of three bf16 values, x = h + m + l
+// (8 significant bits each, by truncation: h = top half of x's bits, m = top half of x - h,
+// l = x - h - m), so x y = hh + (hm + mh) + (hl + lh + mm) + terms below 2^-24 |x y|: six bf16
+// products, each exact, replace one fp32 product at 2.7 times the rate.  The wavefront loads its
+// 64-column chunk as in gram_mfma_wave_kernel, splits it in registers and parks the three planes
+// in its own LDS slice (rows of 64 bf16 = 128 B, 16-byte pieces XOR-swizzled with the row number);
+// operands for v_mfma_f32_16x16x32_bf16 (lane l: row l % 16, columns 8 (l / 16) .. + 7 of a 32-column
+// half) are read back with one 128-bit LDS load each.  Sums stay in fp32 inside the instruction;
+// the tile sums are flushed into fp64 registers every two chunks, as in the fp32 kernels.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+template <int NT>
+__global__ void __launch_bounds__(kBlock, (NT >= 3) ? 1 : 2)
+gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nchunks, int64_t cached_chunks,
+                       double *__restrict__ partials) {
+    constexpr int NPT = NT * (NT + 1) / 2;
+    constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
+    constexpr int kPlaneBytes = kRows * 128;                  // kRows x 64 bf16
+    constexpr int kSliceBytes = 3 * kPlaneBytes;              // h, m, l of one wavefront's chunk
+    static_assert(NPT * 256 * 8 <= 4 * kSliceBytes, "the final reduction reuses the slices");
+    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * kSliceBytes];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int r16 = lane & 15, kq = lane >> 4;
+    unsigned char *slice = lds_raw + wave * kSliceBytes;
+
+    f32x4 acc32[NPT];
+    double acc64[NPT][4];
+#pragma unroll
+    for (int p = 0; p < NPT; ++p) {
+        acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
+    }
+
+    // load j of a chunk: row 4 j + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
+    f32x4 stage[kLoads];
+    auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int row = 4 * j + (lane >> 4);
+            const int64_t col = ch * 64 + (lane & 15) * 4;
+            const bool live = row < N && col < d;   // d is a multiple of 4 on this path
+            const int rowc = row < N ? row : N - 1;
+            const int64_t colc = col < d ? col : d - 4;
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+            f32x4 x;
+            if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
+            else x = *src;
+            stage[j] = live ? x : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+
+    const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
+    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
+    int64_t ch = (int64_t)slot * (kBlock / kWave) + wave;
+    int since_flush = 0;
+    auto step = [&](auto stream) __attribute__((always_inline)) {
+        // split into three bf16 planes and park them
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+            const int row = 4 * j + (lane >> 4), cl = lane & 15;
+            unsigned hb[4], mb[4], lb[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float x = stage[j][c];
+                hb[c] = __float_as_uint(x) & 0xffff0000u;
+                const float r1 = x - __uint_as_float(hb[c]);          // exact
+                mb[c] = __float_as_uint(r1) & 0xffff0000u;
+                const float r2 = r1 - __uint_as_float(mb[c]);         // exact, at most 8 significant bits
+                lb[c] = __float_as_uint(r2);
+            }
+            // two bf16 (the upper halves) per dword: the lower column in the lower half
+            const int off = row * 128 + ((((cl >> 1) ^ (row & 7))) << 4) + ((cl & 1) << 3);
+            const u32x2 ph = {__builtin_amdgcn_perm(hb[1], hb[0], 0x07060302u), __builtin_amdgcn_perm(hb[3], hb[2], 0x07060302u)};
+            const u32x2 pm = {__builtin_amdgcn_perm(mb[1], mb[0], 0x07060302u), __builtin_amdgcn_perm(mb[3], mb[2], 0x07060302u)};
+            const u32x2 pl = {__builtin_amdgcn_perm(lb[1], lb[0], 0x07060302u), __builtin_amdgcn_perm(lb[3], lb[2], 0x07060302u)};
+            *reinterpret_cast<u32x2 *>(slice + off) = ph;
+            *reinterpret_cast<u32x2 *>(slice + kPlaneBytes + off) = pm;
+            *reinterpret_cast<u32x2 *>(slice + 2 * kPlaneBytes + off) = pl;
+        }
+        const int64_t chn = ch + wstride;
+        load_chunk(chn < nchunks ? chn : nchunks - 1, stream);   // past the end: the last chunk again, never used
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            bf16x8 op[3][NT];
+#pragma unroll
+            for (int P = 0; P < 3; ++P)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int row = t * 16 + r16;
+                    const int piece = (u * 4 + kq) ^ (row & 7);
+                    op[P][t] = *reinterpret_cast<const bf16x8 *>(slice + P * kPlaneBytes + row * 128 + piece * 16);
+                }
+            int p = 0;
+#pragma unroll
+            for (int I = 0; I < NT; ++I)
+#pragma unroll
+                for (int J = I; J < NT; ++J) {
+                    f32x4 a = acc32[p];
+                    // smallest terms first
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[1][I], op[1][J], a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[0][I], op[2][J], a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[2][I], op[0][J], a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[0][I], op[1][J], a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[1][I], op[0][J], a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[0][I], op[0][J], a, 0, 0, 0);
+                    acc32[p] = a;
+                    ++p;
+                }
+        }
+        since_flush += 4;
+        if (since_flush >= kFlush) {
+            since_flush = 0;
+#pragma unroll
+            for (int p = 0; p < NPT; ++p) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+                acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        ch = chn;
+    };
+    if (ch < nchunks) load_chunk(ch, std::false_type{});
+    while (ch < nchunks && ch + wstride < cached_chunks) step(std::false_type{});
+    while (ch < nchunks) step(std::true_type{});
+#pragma unroll
+    for (int p = 0; p < NPT; ++p)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
+    __syncthreads();   // every wavefront is done with its slice before the buffer is reused
+    mfma_store_partial_row<NT>(acc64, reinterpret_cast<double *>(lds_raw), N,
+                               partials + (size_t)blockIdx.x * num_pairs(N));
+}
+
+// ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
 template <typename Kern>
@@ -681,13 +820,16 @@ static hipError_t run_mfma_lds(const void *G, int N, int64_t d, const LaunchShap
     return hipGetLastError();
 }
 
-template <int NT>
+// SPLIT: products on the bf16 matrix-core path (gram_mfma_split_kernel) instead of the fp32 one.
+template <int NT, bool SPLIT>
 static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                                 hipStream_t s, int *grid_out) {
-    static const int occ = occupancy(gram_mfma_wave_kernel<NT>);
+    auto kern = SPLIT ? gram_mfma_split_kernel<NT> : gram_mfma_wave_kernel<NT>;
+    static const int occ = occupancy(kern);
     const int64_t nchunks = (d + 63) / 64;
     const int waves = kBlock / kWave;
-    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, NT >= 4 ? 1 : 2);
+    const int dflt = SPLIT ? (NT >= 3 ? 1 : 2) : (NT >= 4 ? 1 : 2);
+    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, dflt);
     *grid_out = grid;
     // Non-temporal loads past the cached head pay off only when every row starts on a 128-byte line
     // (measured at N = 16: 6.8 against 6.3 TB/s); with rows shifted against the lines a 256-byte
@@ -697,8 +839,8 @@ static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchSha
     int64_t cached_chunks = nchunks + (int64_t)grid * waves;   // beyond every prefetch
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
-    hipLaunchKernelGGL((gram_mfma_wave_kernel<NT>), dim3(grid), dim3(kBlock), 0, s, static_cast<const float *>(G), N,
-                       d, nchunks, cached_chunks, tail.partials);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, static_cast<const float *>(G), N, d, nchunks,
+                       cached_chunks, tail.partials);
     return hipGetLastError();
 }
 
@@ -706,8 +848,13 @@ template <int NT, typename T, int VEC4>
 static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                            hipStream_t s, int *grid_out) {
     if constexpr (VEC4 != 0 && sizeof(T) == 4) {
-        if (tail.mode == kGramPartialsOnly && shape.mfma_direct == 2)
-            return run_mfma_wave<NT>(G, N, d, shape, tail, s, grid_out);
+        // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.27 against
+        // 1.33 ms) and N = 32 (2 %), lose at N = 48 (0.96 against 0.87 ms) and N = 16
+        const int variant = shape.mfma_direct == 4 ? (NT == 4 ? 3 : 2) : shape.mfma_direct;
+        if (tail.mode == kGramPartialsOnly && variant == 2)
+            return run_mfma_wave<NT, false>(G, N, d, shape, tail, s, grid_out);
+        if (tail.mode == kGramPartialsOnly && variant == 3)
+            return run_mfma_wave<NT, true>(G, N, d, shape, tail, s, grid_out);
     }
     // the LDS-staged kernel needs the 128-bit path and leaves the reduction to a later launch
     if (VEC4 != 0 && tail.mode == kGramPartialsOnly && shape.mfma_direct == 0)

@@ -94,10 +94,11 @@ def test_gram_matches_oracle(pkg, N, d, dtype):
 
 @pytest.mark.parametrize("N,d", [(12, 1024), (16, 4096 + 16), (24, 100_000), (40, 20_000), (64, 65_536 + 256)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 def test_gram_matrix_core_variants_match_oracle(pkg, N, d, dtype, variant):
-    """The three ways the matrix-core Gram kernel gets its operands (tuning option): workgroup tiles
-    staged through LDS (0), straight from memory (1), per-wavefront transpose through LDS (2)."""
+    """The matrix-core Gram kernels (tuning option): workgroup tiles staged through LDS (0), operands
+    straight from memory (1), per-wavefront transpose through LDS (2), the same with every fp32
+    product formed from six exact bf16 products (3)."""
     G = randG(N, d, dtype, sigma=2.0, seed=N + d % 991)
     agg = pkg.AdaCons(N, d)
     agg.tune(pkg.ADACONS_TUNE_MFMA_DIRECT_LOADS, variant)
