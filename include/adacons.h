@@ -83,7 +83,8 @@ enum {
  * Create the carried state of one coefficient stream: the EMA vector m of
  * Eq. 11 (N doubles kept in sorted order, zero-initialised), the call counter,
  * the coefficient buffers and the partial-sum workspace of stage A1, all on the
- * current HIP device.  This is the only call that allocates device memory.
+ * current HIP device.  This is the only call that allocates device memory.  Later calls
+ * with this state must be made with the same device current (else ADACONS_EINVAL).
  *   st       out: receives the handle (host pointer to a host pointer)
  *   N        number of workers, 1 <= N <= ADACONS_N_MAX
  *   d_max    largest gradient length later calls may pass, >= 1

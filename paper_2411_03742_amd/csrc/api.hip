@@ -64,6 +64,9 @@ adacons_status check_call(const void *G, int N, int64_t d, adacons_dtype dtype, 
     if (need_out && !out) return fail(ADACONS_EINVAL, "out is NULL");
     if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return fail(ADACONS_EUNSUPPORTED, "unknown dtype %d", (int)dtype);
     if (N != st->N) return fail(ADACONS_EINVAL, "N=%d does not match the state's N=%d", N, st->N);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != st->device)
+        return fail(ADACONS_EINVAL, "the state lives on device %d, the current device is %d", st->device, dev);
     if (d < 1 || d > st->d_max)
         return fail(ADACONS_EINVAL, "d=%lld outside [1, d_max=%lld]", (long long)d, (long long)st->d_max);
     const size_t es = elem_size(dtype);

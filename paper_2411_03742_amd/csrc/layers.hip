@@ -450,7 +450,7 @@ static hipError_t dispatch_layers(int N, A... a) {
 using namespace adacons;
 
 struct adacons_layers {
-    int N, L;
+    int N, L, device;
     int64_t d;
     adacons_dtype dtype;
     double beta;
@@ -540,7 +540,7 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     adacons_layers *ls = new (std::nothrow) adacons_layers();
     if (!ls) return lfail(ADACONS_ENOMEM, "host allocation failed");
     memset(ls, 0, sizeof *ls);
-    ls->N = N; ls->L = L; ls->d = offsets_host[L]; ls->dtype = dtype; ls->beta = beta; ls->flags = flags;
+    ls->N = N; ls->L = L; ls->device = dev; ls->d = offsets_host[L]; ls->dtype = dtype; ls->beta = beta; ls->flags = flags;
     ls->nruns = nruns; ls->gram_grid = gram_grid;
     ls->wsum_grid = prop.multiProcessorCount * 8;
 
@@ -574,6 +574,8 @@ adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons
                                         float *out, void *hip_stream) {
     if (!ls || !G || !out) return lfail(ADACONS_EINVAL, "NULL argument");
     if (N != ls->N || d != ls->d || dtype != ls->dtype) return lfail(ADACONS_EINVAL, "N, d or dtype differ from init");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ls->device) return lfail(ADACONS_EINVAL, "the layer state lives on another device");
     const size_t es = dtype == ADACONS_BF16 ? 2 : 4;
     const uintptr_t g0 = reinterpret_cast<uintptr_t>(G), o0 = reinterpret_cast<uintptr_t>(out);
     if (g0 % 16 || o0 % 16 || ((uint64_t)d * es) % 16) return lfail(ADACONS_EALIGN, "layer-wise path needs 16-byte alignment");
