@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", type=int, default=0, metavar="CALLS",
+                    help="time the aggregation replayed from a HIP graph that holds CALLS consecutive calls "
+                         "(launch-bound small workloads); steps is rounded to a multiple of CALLS")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the read-only and copy rates measured on this box for context")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="REPS",
@@ -106,10 +109,28 @@ def main() -> int:
 
     # ---- timed region: exactly `steps` aggregations, nothing else on the stream ----------
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    graph = None
+    if args.graph > 0:
+        # the library enqueues kernels only, so the calls can be captured once and replayed
+        args.steps = max(args.graph, args.steps // args.graph * args.graph)
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(args.graph):
+                agg.aggregate(bufs[i % 2], out=out, stream=torch.cuda.current_stream())
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        tuned["graph_calls"] = args.graph
     t0 = time.perf_counter()
     e0.record(stream)
-    for i in range(args.steps):
-        agg.aggregate(bufs[i % 2], out=out, stream=stream)
+    if graph is not None:
+        for _ in range(args.steps // args.graph):
+            graph.replay()
+    else:
+        for i in range(args.steps):
+            agg.aggregate(bufs[i % 2], out=out, stream=stream)
     e1.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
