@@ -83,6 +83,17 @@ enum {
     ORACLE_NUM_UNIFORM_FALLBACK = 4u  /* gamma replaced by 1/N */
 };
 
+/* Number of OpenMP threads later calls use (results do not depend on it); n < 1 is ignored. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1)
+        omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP
