@@ -518,20 +518,33 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
 
     // load j of a chunk: row 4 j + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
     f32x4 stage[kLoads];
-    auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
+    // interior: every row exists (N = 16 NT) and the chunk lies inside d, so no clamp and no zero-fill
+    // (the address selects and zero masks cost more vector instructions than the loads themselves)
+    auto load_chunk_as = [&](int64_t ch, auto stream, auto interior) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int row = 4 * j + (lane >> 4);
             const int64_t col = ch * 64 + (lane & 15) * 4;
-            const bool live = row < N && col < d;   // d is a multiple of 4 on this path
-            const int rowc = row < N ? row : N - 1;
-            const int64_t colc = col < d ? col : d - 4;
-            const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
-            f32x4 x;
-            if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
-            else x = *src;
-            stage[j] = live ? x : f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (decltype(interior)::value) {
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)row * d + col);
+                if constexpr (decltype(stream)::value) stage[j] = __builtin_nontemporal_load(src);
+                else stage[j] = *src;
+            } else {
+                const bool live = row < N && col < d;   // d is a multiple of 4 on this path
+                const int rowc = row < N ? row : N - 1;
+                const int64_t colc = col < d ? col : d - 4;
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+                f32x4 x;
+                if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
+                else x = *src;
+                stage[j] = live ? x : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
         }
+    };
+    const int64_t full_chunks = (N == kRows) ? d / 64 : 0;   // chunks below this index are interior
+    auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
+        if (ch < full_chunks) load_chunk_as(ch, stream, std::true_type{});
+        else load_chunk_as(ch, stream, std::false_type{});
     };
 
     const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
@@ -637,20 +650,32 @@ gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nc
 
     // load j of a chunk: row 4 j + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
     f32x4 stage[kLoads];
-    auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
+    // interior: every row exists (N = 16 NT) and the chunk lies inside d, so no clamp and no zero-fill
+    auto load_chunk_as = [&](int64_t ch, auto stream, auto interior) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int row = 4 * j + (lane >> 4);
             const int64_t col = ch * 64 + (lane & 15) * 4;
-            const bool live = row < N && col < d;   // d is a multiple of 4 on this path
-            const int rowc = row < N ? row : N - 1;
-            const int64_t colc = col < d ? col : d - 4;
-            const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
-            f32x4 x;
-            if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
-            else x = *src;
-            stage[j] = live ? x : f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (decltype(interior)::value) {
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)row * d + col);
+                if constexpr (decltype(stream)::value) stage[j] = __builtin_nontemporal_load(src);
+                else stage[j] = *src;
+            } else {
+                const bool live = row < N && col < d;   // d is a multiple of 4 on this path
+                const int rowc = row < N ? row : N - 1;
+                const int64_t colc = col < d ? col : d - 4;
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+                f32x4 x;
+                if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
+                else x = *src;
+                stage[j] = live ? x : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
         }
+    };
+    const int64_t full_chunks = (N == kRows) ? d / 64 : 0;   // chunks below this index are interior
+    auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
+        if (ch < full_chunks) load_chunk_as(ch, stream, std::true_type{});
+        else load_chunk_as(ch, stream, std::false_type{});
     };
 
     const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
