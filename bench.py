@@ -34,8 +34,8 @@ PMC_TRAFFIC_BYTES = {
     ("C2", "wsum_kernel (A3)", ()): 857_044_343 + 102_228_128,
     ("C3", "gram_kernel (A1)", ()): 5_362_251_980 + 147_456,
     ("C3", "wsum_kernel (A3)", ()): 5_362_184_750 + 1_340_567_605,
-    ("C4", "gram_kernel (A1)", ()): 6_619_333_022 + 4_259_840,
-    ("C4", "wsum_kernel (A3)", ()): 7_018_929_123 + 102_228_128,
+    ("C4", "gram_kernel (A1)", ()): 6_644_466_645 + 4_259_840,
+    ("C4", "wsum_kernel (A3)", ()): 7_019_504_076 + 102_228_128,
     ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_823_823_468 + 262_144,
     ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 7_019_207_350 + 102_228_128,
     ("C5", "gram_kernel (A1)", ()): 7_964_256_303 + 557_057,
