@@ -494,13 +494,21 @@ gram_mfma_lds_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ntiles, 
 // both directions) and reads it back in operand layout.  Nothing is shared between wavefronts,
 // so there is no workgroup barrier in the loop; the next chunk's loads are in flight while the
 // current chunk is multiplied.
-template <int NT>
+// bf16 inputs take the same kernel: a 16-byte piece then holds eight columns (chunks of 128 columns),
+// and the operands go to v_mfma_f32_16x16x32_bf16 as they are -- bf16 products are exact in the fp32
+// accumulator, at sixteen times the rate of the fp32 instruction.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+template <int NT, typename T>
 __global__ void __launch_bounds__(kBlock, (NT >= 4) ? 1 : 2)
-gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nchunks, int64_t cached_chunks,
+gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, int64_t cached_chunks,
                       double *__restrict__ partials) {
     constexpr int NPT = NT * (NT + 1) / 2;
     constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
-    constexpr int kSliceBytes = kRows * 256;                  // one wavefront's chunk: kRows x 64 floats
+    constexpr int VECW = VecWidth<T>::value;                  // columns per 16-byte piece
+    constexpr int kCols = 16 * VECW;                          // columns per chunk: 256 bytes of every row
+    constexpr int kSliceBytes = kRows * 256;                  // one wavefront's chunk
     static_assert(NPT * 256 * 8 <= 4 * kSliceBytes, "the final reduction reuses the slices");
     __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * kSliceBytes];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -516,7 +524,7 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
         for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
     }
 
-    // load j of a chunk: row 4 j + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
+    // load j of a chunk: row 4 j + lane / 16, columns chunk * kCols + VECW (lane % 16) .. + VECW - 1
     f32x4 stage[kLoads];
     // interior: every row exists (N = 16 NT) and the chunk lies inside d, so no clamp and no zero-fill
     // (the address selects and zero masks cost more vector instructions than the loads themselves)
@@ -524,15 +532,15 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int row = 4 * j + (lane >> 4);
-            const int64_t col = ch * 64 + (lane & 15) * 4;
+            const int64_t col = ch * kCols + (lane & 15) * VECW;
             if constexpr (decltype(interior)::value) {
                 const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)row * d + col);
                 if constexpr (decltype(stream)::value) stage[j] = __builtin_nontemporal_load(src);
                 else stage[j] = *src;
             } else {
-                const bool live = row < N && col < d;   // d is a multiple of 4 on this path
+                const bool live = row < N && col < d;   // d is a multiple of VECW on this path
                 const int rowc = row < N ? row : N - 1;
-                const int64_t colc = col < d ? col : d - 4;
+                const int64_t colc = col < d ? col : d - VECW;
                 const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
                 f32x4 x;
                 if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
@@ -541,7 +549,7 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
             }
         }
     };
-    const int64_t full_chunks = (N == kRows) ? d / 64 : 0;   // chunks below this index are interior
+    const int64_t full_chunks = (N == kRows) ? d / kCols : 0;   // chunks below this index are interior
     auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
         if (ch < full_chunks) load_chunk_as(ch, stream, std::true_type{});
         else load_chunk_as(ch, stream, std::false_type{});
@@ -570,19 +578,32 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
                 const int piece = (u * 4 + kq) ^ (row & 15);
                 v[t] = *reinterpret_cast<const f32x4 *>(slice + row * 256 + piece * 16);
             }
+            if constexpr (sizeof(T) == 4) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
+                for (int c = 0; c < 4; ++c) {
+                    int p = 0;
+#pragma unroll
+                    for (int I = 0; I < NT; ++I)
+#pragma unroll
+                        for (int J = I; J < NT; ++J) {
+                            acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[I][c], v[J][c], acc32[p], 0, 0, 0);
+                            ++p;
+                        }
+                }
+            } else {
+                // lane l: row l % 16, columns 32 u + 8 (l / 16) .. + 7 of the chunk
                 int p = 0;
 #pragma unroll
                 for (int I = 0; I < NT; ++I)
 #pragma unroll
                     for (int J = I; J < NT; ++J) {
-                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[I][c], v[J][c], acc32[p], 0, 0, 0);
+                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v[I]),
+                                                                           __builtin_bit_cast(bf16x8, v[J]), acc32[p], 0, 0, 0);
                         ++p;
                     }
             }
         }
-        since_flush += 4;
+        since_flush += kCols / 16;
         if (since_flush >= kFlush) {
             since_flush = 0;
 #pragma unroll
@@ -622,8 +643,6 @@ gram_mfma_wave_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nch
 // operands for v_mfma_f32_16x16x32_bf16 (lane l: row l % 16, columns 8 (l / 16) .. + 7 of a 32-column
 // half) are read back with one 128-bit LDS load each.  Sums stay in fp32 inside the instruction;
 // the tile sums are flushed into fp64 registers every two chunks, as in the fp32 kernels.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 template <int NT>
 __global__ void __launch_bounds__(kBlock, (NT >= 3) ? 1 : 2)
@@ -845,13 +864,17 @@ static hipError_t run_mfma_lds(const void *G, int N, int64_t d, const LaunchShap
     return hipGetLastError();
 }
 
-// SPLIT: products on the bf16 matrix-core path (gram_mfma_split_kernel) instead of the fp32 one.
-template <int NT, bool SPLIT>
+// SPLIT (fp32 only): products on the bf16 matrix-core path (gram_mfma_split_kernel) instead of the fp32 one.
+template <int NT, typename T, bool SPLIT>
 static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                                 hipStream_t s, int *grid_out) {
-    auto kern = SPLIT ? gram_mfma_split_kernel<NT> : gram_mfma_wave_kernel<NT>;
+    auto kern = [] {
+        if constexpr (SPLIT && sizeof(T) == 4) return gram_mfma_split_kernel<NT>;
+        else return gram_mfma_wave_kernel<NT, T>;
+    }();
     static const int occ = occupancy(kern);
-    const int64_t nchunks = (d + 63) / 64;
+    const int64_t cols = 16 * VecWidth<T>::value;   // columns per chunk
+    const int64_t nchunks = (d + cols - 1) / cols;
     const int waves = kBlock / kWave;
     const int dflt = SPLIT ? (NT >= 3 ? 1 : 2) : (NT >= 4 ? 1 : 2);
     const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, dflt);
@@ -860,11 +883,11 @@ static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchSha
     // (measured at N = 16: 6.8 against 6.3 TB/s); with rows shifted against the lines a 256-byte
     // piece shares its first and last line with its neighbours, and lines that are not kept in L2
     // are then fetched twice (6.1 against 6.3 TB/s).  shape.cached_head_mb < 0: ordinary loads only.
-    const bool rows_on_lines = reinterpret_cast<uintptr_t>(G) % 128 == 0 && (d * (int64_t)sizeof(float)) % 128 == 0;
+    const bool rows_on_lines = reinterpret_cast<uintptr_t>(G) % 128 == 0 && (d * (int64_t)sizeof(T)) % 128 == 0;
     int64_t cached_chunks = nchunks + (int64_t)grid * waves;   // beyond every prefetch
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, static_cast<const float *>(G), N, d, nchunks,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N, d, nchunks,
                        cached_chunks, tail.partials);
     return hipGetLastError();
 }
@@ -872,14 +895,14 @@ static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchSha
 template <int NT, typename T, int VEC4>
 static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                            hipStream_t s, int *grid_out) {
-    if constexpr (VEC4 != 0 && sizeof(T) == 4) {
-        // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.27 against
-        // 1.33 ms) and N = 32 (2 %), lose at N = 48 (0.96 against 0.87 ms) and N = 16
-        const int variant = shape.mfma_direct == 4 ? (NT == 4 ? 3 : 2) : shape.mfma_direct;
+    if constexpr (VEC4 != 0) {
+        // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.12 against
+        // 1.29 ms), lose at N = 48, and are even at N <= 32.  bf16 inputs need no split (3 = 2).
+        const int variant = shape.mfma_direct == 4 ? ((NT == 4 && sizeof(T) == 4) ? 3 : 2) : shape.mfma_direct;
         if (tail.mode == kGramPartialsOnly && variant == 2)
-            return run_mfma_wave<NT, false>(G, N, d, shape, tail, s, grid_out);
+            return run_mfma_wave<NT, T, false>(G, N, d, shape, tail, s, grid_out);
         if (tail.mode == kGramPartialsOnly && variant == 3)
-            return run_mfma_wave<NT, true>(G, N, d, shape, tail, s, grid_out);
+            return run_mfma_wave<NT, T, true>(G, N, d, shape, tail, s, grid_out);
     }
     // the LDS-staged kernel needs the 128-bit path and leaves the reduction to a later launch
     if (VEC4 != 0 && tail.mode == kGramPartialsOnly && shape.mfma_direct == 0)
