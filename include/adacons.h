@@ -194,7 +194,7 @@ typedef enum {
                                              LDS; 3 = as 2, with every fp32 product formed from six exact bf16
                                              products on the sixteen times faster bf16 matrix-core path (fp32
                                              = sum of three bf16; dropped terms < 2^-24 of the product).
-                                             4 (default) = 3 for N > 48, else 2.  bf16 inputs go to the bf16
+                                             4 (default) = 3 for N > 32, else 2.  bf16 inputs go to the bf16
                                              matrix-core instruction as they are (exact products; 3 = 2).
                                              2 and 3 need the 128-bit path; other inputs take variant 1 */
     ADACONS_TUNE_STATS_ONLY = 6,          /* 1: for N > 8 stage A1 computes only what Eq. 7 consumes, the diagonal

@@ -896,9 +896,10 @@ template <int NT, typename T, int VEC4>
 static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                            hipStream_t s, int *grid_out) {
     if constexpr (VEC4 != 0) {
-        // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.12 against
-        // 1.29 ms), lose at N = 48, and are even at N <= 32.  bf16 inputs need no split (3 = 2).
-        const int variant = shape.mfma_direct == 4 ? ((NT == 4 && sizeof(T) == 4) ? 3 : 2) : shape.mfma_direct;
+        // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.10 against
+        // 1.29 ms) and N = 48 (0.80 against 0.88 ms) and are even at N <= 32 (where the whole step
+        // measured 2 % slower with them).  bf16 inputs need no split (3 = 2).
+        const int variant = shape.mfma_direct == 4 ? ((NT >= 3 && sizeof(T) == 4) ? 3 : 2) : shape.mfma_direct;
         if (tail.mode == kGramPartialsOnly && variant == 2)
             return run_mfma_wave<NT, T, false>(G, N, d, shape, tail, s, grid_out);
         if (tail.mode == kGramPartialsOnly && variant == 3)
