@@ -22,6 +22,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "adacons_internal.h"
@@ -137,7 +138,7 @@ template <> __device__ __forceinline__ void widen_bits<float>(const u32x4 x, flo
 template <> __device__ __forceinline__ void widen_bits<bf16_bits>(const u32x4 x, float (&v)[8]) { unpack_bf16x8(x, v); }
 
 template <int NT, typename T>
-__global__ void __launch_bounds__(kBlock, (NT * VecWidth<T>::value >= 16) ? 1 : 2)
+__global__ void __launch_bounds__(kBlock, (NT * VecWidth<T>::value >= 12) ? 1 : 2)
 stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *__restrict__ runs, int nruns,
                     const int *__restrict__ order, unsigned *__restrict__ ticket, double *__restrict__ partials) {
     constexpr int VECW = VecWidth<T>::value;
@@ -159,23 +160,24 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
         for (int j = 0; j < kLoads; ++j) qacc[j] = racc[j] = 0.0;
         const int64_t g_end = run.g0 + run.n;
         const int nchunks = (run.n + 15) / 16;
-        for (int c = wave; c < nchunks; c += kBlock / kWave) {
+        // interior chunk: all sixteen groups belong to the run, none of their columns to a neighbouring
+        // layer, and every row exists -- no clamps, no masks (they cost more than the arithmetic)
+        auto chunk = [&](int c, auto interior) __attribute__((always_inline)) {
+            constexpr bool kInterior = decltype(interior)::value;
             const int64_t g = run.g0 + 16 * (int64_t)c + cl;
-            const bool in_run = g < g_end;
+            const bool in_run = kInterior || g < g_end;
             const int64_t gc = in_run ? g : g_end - 1;          // clamped: always a group of this run
             const int64_t c0 = gc * VECW;
             u32x4 x[kLoads];
 #pragma unroll
             for (int j = 0; j < kLoads; ++j) {
                 const int row = 4 * j + grp;
-                const int rowc = row < N ? row : N - 1;
+                const int rowc = (kInterior || row < N) ? row : N - 1;
                 x[j] = *reinterpret_cast<const u32x4 *>(G + (int64_t)rowc * d + c0);
             }
-            // per-column mask: inside the run, inside the layer (only the first and last group of a
-            // run can straddle a boundary), and a row that exists
             bool live[VECW];
 #pragma unroll
-            for (int k = 0; k < VECW; ++k) live[k] = in_run && c0 + k >= run.cb && c0 + k < run.ce;
+            for (int k = 0; k < VECW; ++k) live[k] = kInterior || (in_run && c0 + k >= run.cb && c0 + k < run.ce);
             double ssum[VECW];
 #pragma unroll
             for (int k = 0; k < VECW; ++k) ssum[k] = 0.0;
@@ -183,7 +185,7 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
             for (int j = 0; j < kLoads; ++j) {
                 float v[VECW];
                 widen_bits<T>(x[j], v);
-                const bool row_ok = 4 * j + grp < N;
+                const bool row_ok = kInterior || 4 * j + grp < N;
 #pragma unroll
                 for (int k = 0; k < VECW; ++k) ssum[k] += (row_ok && live[k]) ? (double)v[k] : 0.0;
             }
@@ -196,7 +198,7 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
             for (int j = 0; j < kLoads; ++j) {
                 float v[VECW];
                 widen_bits<T>(x[j], v);
-                const bool row_ok = 4 * j + grp < N;
+                const bool row_ok = kInterior || 4 * j + grp < N;
 #pragma unroll
                 for (int k = 0; k < VECW; ++k) {
                     const double y = (row_ok && live[k]) ? (double)v[k] : 0.0;
@@ -204,6 +206,12 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
                     racc[j] = fma(y, ssum[k], racc[j]);
                 }
             }
+        };
+        for (int c = wave; c < nchunks; c += kBlock / kWave) {
+            const int64_t first = (run.g0 + 16 * (int64_t)c) * VECW;      // the chunk's columns [first, first + 16 VECW)
+            const bool interior = N == 16 * NT && 16 * c + 16 <= run.n && first >= run.cb && first + 16 * VECW <= run.ce;
+            if (interior) chunk(c, std::true_type{});
+            else chunk(c, std::false_type{});
         }
         // the sixteen lanes of a group in a fixed butterfly order, then the wavefronts in index order
 #pragma unroll
