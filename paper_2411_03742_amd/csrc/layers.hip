@@ -2,7 +2,7 @@
 // performance"): steps A1-A3 run independently on every contiguous column segment of G, with one
 // coefficient set and one Eq. 11 momentum state per layer -- in three launches for all layers.
 //
-// Every layer is cut into runs of at most kRunGroups column groups (one group = one 128-bit load per
+// Every layer is cut into runs of at most run_groups column groups (one group = one 128-bit load per
 // row); a run never crosses a layer boundary.  Layer boundaries need not be multiples of the group
 // width: the group that straddles two layers belongs to a run of each, and the columns that
 // belong to the other layer are masked (zeroed in A1, not stored in A3).
@@ -34,12 +34,25 @@ namespace adacons {
 struct LayerRun {
     int64_t g0;      // first column group (group = VEC columns)
     int64_t cb, ce;  // the layer's column range [cb, ce)
-    int n;           // groups in this run, 1..kRunGroups
+    int n;           // groups in this run, 1..run_groups
     int layer;
 };
 
 constexpr int kLayersMaxN = 8;           // largest N with the Gram matrix per thread; above: statistics
-constexpr int kRunGroups = 16 * kBlock;   // column groups per run: 16 sweeps of a workgroup
+// Column groups per run: chosen per layout so that the full-length runs come to a whole number per
+// workgroup of stage A1 (a fixed length of 16 sweeps left 24 of 512 workgroups with a fourth
+// full-length run on the ResNet-50 layout while the others had three).  A multiple of 512, so that an
+// eighth of it (the piece of stage A3) is a whole number of wavefront segments.
+static int choose_run_groups(int64_t total_groups, int gram_grid) {
+    const int64_t nominal = 16 * kBlock;
+    int64_t per_block = (total_groups + (int64_t)gram_grid * nominal / 2) / ((int64_t)gram_grid * nominal);   // runs per workgroup
+    if (per_block < 1) per_block = 1;
+    int64_t len = (total_groups + gram_grid * per_block - 1) / (gram_grid * per_block);
+    len = (len + 511) / 512 * 512;
+    if (len < 4 * kBlock) len = 4 * kBlock;
+    if (len > 64 * kBlock) len = 64 * kBlock;
+    return (int)len;
+}
 
 // ------------------------------------------------------------------------------------------
 // A1
@@ -295,25 +308,57 @@ finish_layers_kernel(const double *__restrict__ partials, const int *__restrict_
 // ------------------------------------------------------------------------------------------
 // A3
 // ------------------------------------------------------------------------------------------
+// A run is cut into pieces of kWsumPiece column groups (run_groups is a multiple of it); a workgroup
+// sweeps the pieces grid-stride.  A piece that lies inside its run and its layer is a full tile: two
+// groups per thread, all 2 N loads issued before the first use, no predicates (as in the model-wise
+// stage A3); the pieces at the end of a run or on a layer boundary go group by group with masks.
+constexpr int kWsumPiece = 2 * kBlock;
+
 template <int N, typename T, int VEC>
 __global__ void __launch_bounds__(kBlock)
 wsum_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restrict__ runs, int nruns,
-                   const int64_t *__restrict__ offsets, const DevState *__restrict__ ds_all, float *__restrict__ out) {
-    // a run is split into kWsumSplit pieces, each taken by one workgroup sweep
-    constexpr int kWsumSplit = 8, kPiece = kRunGroups / kWsumSplit;
+                   const int64_t *__restrict__ offsets, const DevState *__restrict__ ds_all, float *__restrict__ out,
+                   int run_groups) {
+    const int split = run_groups / kWsumPiece;
     const int grid = (int)gridDim.x, b = (int)blockIdx.x;
     const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;   // XCD-contiguous pieces
-    const int64_t npieces = (int64_t)nruns * kWsumSplit;
+    const int64_t npieces = (int64_t)nruns * split;
     for (int64_t pc = slot; pc < npieces; pc += grid) {
-        const LayerRun run = runs[pc / kWsumSplit];
-        const int first = (int)(pc % kWsumSplit) * kPiece;
+        const LayerRun run = runs[pc / split];
+        const int first = (int)(pc % split) * kWsumPiece;
         if (first >= run.n) continue;
-        const int last = (first + kPiece < run.n) ? first + kPiece : run.n;
+        const int last = (first + kWsumPiece < run.n) ? first + kWsumPiece : run.n;
         const float *gam = ds_all[run.layer].gamma32;
         float w[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) w[i] = gam[i];
         const int64_t cb = run.cb, ce = run.ce;
+        const int64_t p0 = (run.g0 + first) * VEC;                     // first column of the piece
+        if (first + kWsumPiece <= run.n && p0 >= cb && p0 + (int64_t)kWsumPiece * VEC <= ce) {
+            float v[2][N][VEC];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int i = 0; i < N; ++i)
+                    load_vec<T, VEC, true>(G + (int64_t)i * d + p0 + ((int64_t)u * kBlock + threadIdx.x) * VEC, v[u][i]);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                float acc[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+#pragma unroll
+                for (int i = 0; i < N; ++i)
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w[i], v[u][i][c], acc[c]);
+                float *dst = out + p0 + ((int64_t)u * kBlock + threadIdx.x) * VEC;
+#pragma unroll
+                for (int c = 0; c < VEC; c += 4) {
+                    const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+                    __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(dst + c));
+                }
+            }
+            continue;
+        }
         for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
             const int64_t c0 = (run.g0 + k) * VEC;
             float v[N][VEC];
@@ -347,8 +392,9 @@ wsum_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
 template <typename T, int VEC>
 __global__ void __launch_bounds__(kBlock)
 wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *__restrict__ runs, int nruns,
-                      const DevState *__restrict__ ds_all, float *__restrict__ out) {
-    constexpr int kWsumSplit = 8, kPiece = kRunGroups / kWsumSplit;
+                      const DevState *__restrict__ ds_all, float *__restrict__ out, int run_groups) {
+    const int kWsumSplit = run_groups / kWsumPiece;
+    constexpr int kPiece = kWsumPiece;
     const int grid = (int)gridDim.x, b = (int)blockIdx.x;
     const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;   // XCD-contiguous pieces
     const int64_t npieces = (int64_t)nruns * kWsumSplit;
@@ -393,7 +439,7 @@ wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun 
 }
 
 template <int NT, typename T, int VEC>
-static hipError_t run_layers_stats(const void *G, int N, int64_t d, const LayerRun *runs, int nruns, const int *order,
+static hipError_t run_layers_stats(const void *G, int N, int64_t d, const LayerRun *runs, int nruns, int run_groups, const int *order,
                                    int gram_grid, int wsum_grid, const int *layer_entry0, int L, double *partials,
                                    double *K_all, DevState *ds_all, unsigned *ticket, CoeffParams cp, float *out,
                                    hipStream_t s) {
@@ -405,7 +451,7 @@ static hipError_t run_layers_stats(const void *G, int N, int64_t d, const LayerR
                        ds_all, cp, ticket);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL((wsum_layers_rt_kernel<T, VEC>), dim3(wsum_grid), dim3(kBlock), 0, s, static_cast<const T *>(G),
-                       N, d, runs, nruns, ds_all, out);
+                       N, d, runs, nruns, ds_all, out, run_groups);
     return hipGetLastError();
 }
 
@@ -421,7 +467,7 @@ static hipError_t dispatch_layers_stats(int N, const void *G, A... a) {
 }
 
 template <int N, typename T, int VEC>
-static hipError_t run_layers(const void *G, int64_t d, const LayerRun *runs, int nruns, const int *order, int gram_grid, int wsum_grid,
+static hipError_t run_layers(const void *G, int64_t d, const LayerRun *runs, int nruns, int run_groups, const int *order, int gram_grid, int wsum_grid,
                              const int64_t *offsets, const int *layer_entry0, int L, double *partials, double *K_all,
                              DevState *ds_all, unsigned *ticket, CoeffParams cp, float *out, hipStream_t s) {
     // the first 320 MiB of G with cache-allocating loads (same policy as the model-wise stage A1)
@@ -434,7 +480,7 @@ static hipError_t run_layers(const void *G, int64_t d, const LayerRun *runs, int
                        ds_all, cp, ticket);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL((wsum_layers_kernel<N, T, VEC>), dim3(wsum_grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), d, runs, nruns, offsets, ds_all, out);
+                       static_cast<const T *>(G), d, runs, nruns, offsets, ds_all, out, run_groups);
     return hipGetLastError();
 }
 
@@ -463,7 +509,7 @@ struct adacons_layers {
     adacons_dtype dtype;
     double beta;
     unsigned flags;
-    int nruns, gram_grid, wsum_grid;
+    int nruns, run_groups, gram_grid, wsum_grid;
     LayerRun *runs;       // device, nruns
     int64_t *offsets;     // device, L + 1
     int *layer_entry0;    // device, L + 1
@@ -512,18 +558,22 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return lfail(ADACONS_EUNSUPPORTED, "built for gfx950 only");
 
     const int vec = dtype == ADACONS_BF16 ? 8 : 4;
-    // runs: per layer, the groups that contain any of its columns, cut into pieces of kRunGroups
+    int64_t total_groups = 0;
+    for (int l = 0; l < L; ++l) total_groups += (offsets_host[l + 1] + vec - 1) / vec - offsets_host[l] / vec;
+    const int grid_target = prop.multiProcessorCount * 2;   // measured (ResNet-50 layout): 144 us at two workgroups per CU, 152 at one, 155 at three
+    const int run_groups = choose_run_groups(total_groups, grid_target);
+    // runs: per layer, the groups that contain any of its columns, cut into pieces of run_groups
     std::vector<LayerRun> runs;
     std::vector<int> layer_entry0(L + 1);
     for (int l = 0; l < L; ++l) {
         layer_entry0[l] = (int)runs.size();
         const int64_t g_first = offsets_host[l] / vec, g_last = (offsets_host[l + 1] + vec - 1) / vec;
-        for (int64_t g = g_first; g < g_last; g += kRunGroups) {
+        for (int64_t g = g_first; g < g_last; g += run_groups) {
             LayerRun r;
             r.g0 = g;
             r.cb = offsets_host[l];
             r.ce = offsets_host[l + 1];
-            r.n = (int)((g_last - g < kRunGroups) ? g_last - g : kRunGroups);
+            r.n = (int)((g_last - g < run_groups) ? g_last - g : run_groups);
             r.layer = l;
             runs.push_back(r);
         }
@@ -534,22 +584,22 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     std::vector<int> order;
     order.reserve(nruns);
     for (int r = 0; r < nruns; ++r)
-        if (runs[r].n == kRunGroups) order.push_back(r);
+        if (runs[r].n == run_groups) order.push_back(r);
     {
         std::vector<int> rest;
         for (int r = 0; r < nruns; ++r)
-            if (runs[r].n != kRunGroups) rest.push_back(r);
+            if (runs[r].n != run_groups) rest.push_back(r);
         std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return runs[a].n > runs[b].n; });
         order.insert(order.end(), rest.begin(), rest.end());
     }
-    int gram_grid = prop.multiProcessorCount * 2;   // measured: 154 us at two workgroups per CU, 199 us at one
+    int gram_grid = grid_target;
     if (gram_grid > nruns) gram_grid = nruns;
 
     adacons_layers *ls = new (std::nothrow) adacons_layers();
     if (!ls) return lfail(ADACONS_ENOMEM, "host allocation failed");
     memset(ls, 0, sizeof *ls);
     ls->N = N; ls->L = L; ls->device = dev; ls->d = offsets_host[L]; ls->dtype = dtype; ls->beta = beta; ls->flags = flags;
-    ls->nruns = nruns; ls->gram_grid = gram_grid;
+    ls->nruns = nruns; ls->run_groups = run_groups; ls->gram_grid = gram_grid;
     ls->wsum_grid = prop.multiProcessorCount * 8;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -595,19 +645,19 @@ adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons
     hipError_t e;
     if (N > kLayersMaxN) {
         if (dtype == ADACONS_F32)
-            e = dispatch_layers_stats<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order,
+            e = dispatch_layers_stats<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order,
                                                 ls->gram_grid, ls->wsum_grid, (const int *)ls->layer_entry0, ls->L,
                                                 ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
         else
-            e = dispatch_layers_stats<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order,
+            e = dispatch_layers_stats<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order,
                                                     ls->gram_grid, ls->wsum_grid, (const int *)ls->layer_entry0, ls->L,
                                                     ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
     } else if (dtype == ADACONS_F32)
-        e = dispatch_layers<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
+        e = dispatch_layers<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
                                       (const int64_t *)ls->offsets, (const int *)ls->layer_entry0, ls->L, ls->partials,
                                       ls->K, ls->ds, ls->ticket, cp, out, s);
     else
-        e = dispatch_layers<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
+        e = dispatch_layers<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
                                           (const int64_t *)ls->offsets, (const int *)ls->layer_entry0, ls->L,
                                           ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
     if (e != hipSuccess) return lfail(ADACONS_EHIP, hipGetErrorString(e));
