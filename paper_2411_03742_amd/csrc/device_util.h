@@ -63,6 +63,13 @@ __device__ __forceinline__ void load_vec<bf16_bits, 1, true>(const bf16_bits *__
     v[0] = bf16_widen(__builtin_nontemporal_load(p));
 }
 
+// The 16 bytes of one 128-bit load as VecWidth<T> fp32 values (fp32: reinterpreted, bf16: widened).
+template <typename T> __device__ __forceinline__ void widen_bits(const u32x4 x, float (&v)[VecWidth<T>::value]);
+template <> __device__ __forceinline__ void widen_bits<float>(const u32x4 x, float (&v)[4]) {
+    v[0] = __uint_as_float(x.x); v[1] = __uint_as_float(x.y); v[2] = __uint_as_float(x.z); v[3] = __uint_as_float(x.w);
+}
+template <> __device__ __forceinline__ void widen_bits<bf16_bits>(const u32x4 x, float (&v)[8]) { unpack_bf16x8(x, v); }
+
 // Sum over the 64 lanes of a wavefront in a fixed butterfly order; every lane gets the total.
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll

@@ -144,12 +144,6 @@ gram_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
 // across the four lane groups), then q_i += <v_i, v_i>, r_i += <v_i, s> in fp64.  Groups past the
 // end of the run and columns of a straddling group that belong to the neighbouring layer are
 // zeroed.  One partial row [q_0 .. q_{N-1}, r_0 .. r_{N-1}] per run.
-template <typename T> __device__ __forceinline__ void widen_bits(const u32x4 x, float (&v)[VecWidth<T>::value]);
-template <> __device__ __forceinline__ void widen_bits<float>(const u32x4 x, float (&v)[4]) {
-    v[0] = __uint_as_float(x.x); v[1] = __uint_as_float(x.y); v[2] = __uint_as_float(x.z); v[3] = __uint_as_float(x.w);
-}
-template <> __device__ __forceinline__ void widen_bits<bf16_bits>(const u32x4 x, float (&v)[8]) { unpack_bf16x8(x, v); }
-
 template <int NT, typename T>
 __global__ void __launch_bounds__(kBlock, (NT * VecWidth<T>::value >= 12) ? 1 : 2)
 stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *__restrict__ runs, int nruns,

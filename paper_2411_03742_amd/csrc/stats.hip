@@ -23,12 +23,6 @@ namespace adacons {
 
 namespace {
 
-template <typename T> __device__ __forceinline__ void widen(const u32x4 x, float (&v)[VecWidth<T>::value]);
-template <> __device__ __forceinline__ void widen<float>(const u32x4 x, float (&v)[4]) {
-    v[0] = __uint_as_float(x.x); v[1] = __uint_as_float(x.y); v[2] = __uint_as_float(x.z); v[3] = __uint_as_float(x.w);
-}
-template <> __device__ __forceinline__ void widen<bf16_bits>(const u32x4 x, float (&v)[8]) { unpack_bf16x8(x, v); }
-
 // NT = ceil(N / 16): the kernel is compiled for 16, 32, 48 and 64 rows (4 NT loads per chunk).
 // A wavefront takes kSuper consecutive chunks at a time so that about sixteen loads are in flight
 // per buffer for every NT.
@@ -80,7 +74,7 @@ stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, in
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             float v[VECW];
-            widen<T>(src[j], v);
+            widen_bits<T>(src[j], v);
 #pragma unroll
             for (int c = 0; c < VECW; ++c) s[c] += (double)v[c];
         }
@@ -92,7 +86,7 @@ stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, in
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             float v[VECW];
-            widen<T>(src[j], v);
+            widen_bits<T>(src[j], v);
 #pragma unroll
             for (int c = 0; c < VECW; ++c) {
                 const double x = (double)v[c];
