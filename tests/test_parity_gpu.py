@@ -310,6 +310,37 @@ def test_degenerate_inputs_match_oracle_flags(pkg):
     agg.close(); agg2.close()
 
 
+@pytest.mark.parametrize("N,dtype,stats_only", [(16, torch.float32, 0), (48, torch.float32, 0), (64, torch.float32, 0),
+                                               (64, torch.bfloat16, 0), (32, torch.float32, 1), (64, torch.bfloat16, 1)])
+def test_degenerate_inputs_many_workers(pkg, N, dtype, stats_only):
+    """Zero rows, an infinity, a NaN and all-zero input through the matrix-core kernels (fp32
+    instruction, split-bf16 products, bf16 instruction) and the statistics-only pass: same flags,
+    same weights, momentum state untouched by a non-finite step."""
+    d = 40_000
+    agg = pkg.AdaCons(N, d, beta=0.5)
+    agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)
+    ost = o.OracleState(N, beta=0.5)
+    G = randG(N, d, dtype=dtype, sigma=2.0, seed=N)
+    both(pkg, G, agg, ost)
+    Gz = G.clone(); Gz[N - 1] = 0; Gz[3] = 0
+    _, info, _ = both(pkg, Gz, agg, ost)
+    assert info["numeric_flags"] & pkg.ADACONS_NUM_ZERO_NORM and info["gamma"][3] == 0.0 and info["gamma"][N - 1] == 0.0
+    m_before, _ = agg.export_state()
+    for bad in (float("inf"), float("-inf"), float("nan")):
+        Gn = G.clone(); Gn[N // 2, 12_345] = bad
+        agg.aggregate(Gn)
+        info = agg.coeffs()
+        _, oinfo = o.aggregate(workloads.to_oracle_input(Gn), ost, want_out=False)
+        assert info["numeric_flags"] == oinfo["numeric_flags"] == (pkg.ADACONS_NUM_NONFINITE | pkg.ADACONS_NUM_UNIFORM_FALLBACK)
+        assert np.allclose(info["gamma"], 1.0 / N)
+    m_after, step = agg.export_state()
+    assert np.array_equal(m_before, m_after) and step == 5 == ost.t
+    _, info, _ = both(pkg, torch.zeros(N, d, device=DEV, dtype=dtype), agg, ost)
+    assert info["numeric_flags"] & pkg.ADACONS_NUM_UNIFORM_FALLBACK
+    both(pkg, G, agg, ost)          # and a regular step afterwards
+    agg.close()
+
+
 def test_checkpoint_resume_and_reset(pkg):
     N, d = 8, 200_000
     a = pkg.AdaCons(N, d, beta=0.9)
