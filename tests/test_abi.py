@@ -65,6 +65,31 @@ def test_argument_validation_needs_no_gpu(lib):
                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     assert cdll.adacons_aggregate(None, 4, 10, 0, None, None, None) == EINVAL
     assert cdll.adacons_destroy_state(None) == 0
+    # the layer-wise and worker-share entry points check their arguments before touching the device too
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    cdll.adacons_init_layers.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_int, i64p,
+                                         ctypes.c_int, ctypes.c_double, ctypes.c_uint, ctypes.c_void_p]
+    ls = ctypes.c_void_p()
+    good = (ctypes.c_int64 * 3)(0, 40, 100)
+    for args in [(None, 4, 2, good, 0, 0.9, 3, None),
+                 (ctypes.byref(ls), 4, 2, None, 0, 0.9, 3, None),
+                 (ctypes.byref(ls), 0, 2, good, 0, 0.9, 3, None),
+                 (ctypes.byref(ls), 4, 0, good, 0, 0.9, 3, None),
+                 (ctypes.byref(ls), 4, 2, good, 0, 1.5, 3, None),
+                 (ctypes.byref(ls), 4, 2, good, 0, 0.9, 32, None),
+                 (ctypes.byref(ls), 4, 2, (ctypes.c_int64 * 3)(1, 40, 100), 0, 0.9, 3, None),
+                 (ctypes.byref(ls), 4, 2, (ctypes.c_int64 * 3)(0, 40, 40), 0, 0.9, 3, None)]:
+        assert cdll.adacons_init_layers(*args) == EINVAL, args
+    assert cdll.adacons_init_layers(ctypes.byref(ls), 65, 2, good, 0, 0.9, 3, None) == EUNSUPPORTED
+    assert cdll.adacons_init_layers(ctypes.byref(ls), 4, 2, good, 7, 0.9, 3, None) == EUNSUPPORTED
+    assert ls.value is None
+    assert cdll.adacons_destroy_layers(None) == 0
+    cdll.adacons_aggregate_layers.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert cdll.adacons_aggregate_layers(None, 4, 100, 0, None, None, None) == EINVAL
+    cdll.adacons_worker_stats.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert cdll.adacons_worker_stats(None, None, 10, 0, None, None, None) == EINVAL
 
 
 def test_product_path_never_touches_the_oracle():
