@@ -34,9 +34,13 @@ def sample_columns(d, seed):
 
 
 @pytest.mark.parametrize("name,steps,stats_only", [("C2", 20, 0), ("C3", 1, 0), ("C4", 2, 0), ("C5", 3, 0),
-                                                   ("C4", 2, 1), ("C5", 2, 1)])
+                                                   ("C4", 2, 1), ("C5", 2, 1), ("C4-bf16", 2, 0)])
 def test_full_size_configuration(pkg, name, steps, stats_only):
-    w = workloads.CONFIGS[name]
+    if name == "C4-bf16":     # C4's shape and recipe stored as bf16: the bf16 matrix-core Gram at full length
+        from dataclasses import replace
+        w = replace(workloads.C4, name="C4-bf16", dtype="bf16")
+    else:
+        w = workloads.CONFIGS[name]
     w = w.scaled(w.d, steps)
     agg = pkg.AdaCons(w.N, w.d, beta=0.99)
     agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)   # 1: stage A1 computes diag K and row sums only
