@@ -58,7 +58,10 @@
  * quadratic; O6 (lambda = 1) against the explicit d x d preconditioner of
  * Eq. 9; O4-O5 against the closed form of the recurrence, the step-1 identity
  * and permutation invariance with persisting state; O7 against sum-to-one, the
- * identical / orthogonal / N=1 / N=2 closed forms.  No function is unpinned.
+ * identical / orthogonal / N=1 / N=2 closed forms; the INDEX_EMA switch against the plain
+ * per-index recurrence and its dependence on the worker order; the LAMBDA_EQ13 switch against
+ * sum_i gamma_i ||g_i|| = 1 and the unit vector it yields for identical gradients.  No function
+ * is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
