@@ -107,8 +107,11 @@ adacons_status adacons_reset_state(adacons_state *st, void *hip_stream);
  *   G      device pointer, N x d row-major contiguous (row i = g_i, row stride d elements),
  *          element type `dtype`; read twice; must stay valid until the stream reaches the
  *          end of this call's work; must be aligned to its element size.  The 128-bit fast
- *          path is taken when G is 16-byte aligned and d*sizeof(elem) % 16 == 0, otherwise a
- *          slower element-wise path runs (same results).
+ *          path is taken when G is 16-byte aligned and d*sizeof(elem) % 16 == 0 (every row then
+ *          starts on a 16-byte boundary), otherwise an element-wise path runs: same results at
+ *          a little over half the speed (measured 3.6 against 6.3 TB/s at N = 8, d = 25.6 M).
+ *          A caller that flattens gradients itself should pad d to a multiple of 16 bytes; a
+ *          multiple of 128 bytes (rows on cache lines) is worth a further 2-5 %.
  *   N, d   must satisfy N == state's N, 1 <= d <= d_max
  *   out    device pointer to d floats (fp32 for both dtypes), caller-owned, written once,
  *          4-byte aligned, must not overlap G
