@@ -106,12 +106,13 @@ adacons_status adacons_reset_state(adacons_state *st, void *hip_stream);
  * `hip_stream`.  Asynchronous; allocates nothing; never synchronises.
  *   G      device pointer, N x d row-major contiguous (row i = g_i, row stride d elements),
  *          element type `dtype`; read twice; must stay valid until the stream reaches the
- *          end of this call's work; must be aligned to its element size.  The 128-bit fast
- *          path is taken when G is 16-byte aligned and d*sizeof(elem) % 16 == 0 (every row then
- *          starts on a 16-byte boundary), otherwise an element-wise path runs: same results at
- *          a little over half the speed (measured 3.6 against 6.3 TB/s at N = 8, d = 25.6 M).
- *          A caller that flattens gradients itself should pad d to a multiple of 16 bytes; a
- *          multiple of 128 bytes (rows on cache lines) is worth a further 2-5 %.
+ *          end of this call's work; must be aligned to its element size.  Every shape runs on
+ *          the same 128-bit kernels: when G or out is not 16-byte aligned, or d*sizeof(elem) is not
+ *          a multiple of 16 (rows then start off the 16-byte grid), the accesses are issued from
+ *          element-aligned addresses and the d mod 4 (fp32) or d mod 8 (bf16) columns that no whole
+ *          group covers are added by a small extra launch per stage; measured 6.1 against 6.25 TB/s
+ *          at N = 8, d = 25.6 M + 1.  A caller that flattens gradients itself gains 2-5 % by padding
+ *          d to a multiple of 128 bytes (rows on cache lines).
  *   N, d   must satisfy N == state's N, 1 <= d <= d_max
  *   out    device pointer to d floats (fp32 for both dtypes), caller-owned, written once,
  *          4-byte aligned, must not overlap G
@@ -183,7 +184,8 @@ adacons_status adacons_state_import(adacons_state *st, const double *m_host, int
 typedef enum {
     ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0,  /* persistent workgroups per CU in stage A1 */
     ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1,  /* persistent workgroups per CU in stage A3 */
-    ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2; 0 (default): A2 is its own launch */
+    ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2 (only with 16-byte aligned rows);
+                                             0 (default): A2 is its own launch */
     ADACONS_TUNE_REVERSE_SECOND_PASS = 3, /* 1: A3 walks its column tiles backwards; 0 (default): forwards */
     ADACONS_TUNE_CACHED_HEAD_MB = 4,      /* A1 reads the first `value` MiB of G with cache-allocating loads and
                                              streams the rest past the caches (non-temporal), so that A3 finds
@@ -199,14 +201,13 @@ typedef enum {
                                              = sum of three bf16; dropped terms < 2^-24 of the product).
                                              4 (default) = 3 for N > 32, else 2.  bf16 inputs go to the bf16
                                              matrix-core instruction as they are (exact products; 3 = 2).
-                                             2 and 3 need the 128-bit path; other inputs take variant 1 */
+                                             0 and 1 need 16-byte aligned rows; other inputs take 4 instead */
     ADACONS_TUNE_STATS_ONLY = 6,          /* 1: for N > 8 stage A1 computes only what Eq. 7 consumes, the diagonal
                                              of K and its row sums (||g_i||^2 and <g_i, sum_j g_j>: Alg. 1
                                              steps 1-2), in O(N) operations per column; K itself is then not
                                              produced and adacons_read_gram() reports ADACONS_EINVAL.  Honoured
-                                             by adacons_aggregate / adacons_aggregate_apply when G is 16-byte
-                                             aligned and d * sizeof(element) is a multiple of 16; otherwise,
-                                             and for N <= 8, the Gram kernels run.  0 (default): full K */
+                                             by adacons_aggregate / adacons_aggregate_apply; for N <= 8 the
+                                             Gram kernel runs.  0 (default): full K */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);

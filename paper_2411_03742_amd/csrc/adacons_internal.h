@@ -67,8 +67,8 @@ hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStre
 int gram_rows_needed(int N, int num_cu);
 hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t stream);  // K may be NULL
 
-// stats.hip: A1 reduced to diag K and its row sums, then A2 (N > 8, 128-bit path only)
-hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, const LaunchShape &shape,
+// stats.hip: A1 reduced to diag K and its row sums, then A2 (N > 8)
+hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok, const LaunchShape &shape,
                         double *partials, DevState *ds, const CoeffParams &cp, hipStream_t stream,
                         hipEvent_t between = nullptr);
 

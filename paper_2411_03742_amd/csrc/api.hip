@@ -111,10 +111,10 @@ GramTail tail_of(adacons_state *st, int mode) {
 hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                              hipStream_t s, hipEvent_t between) {
     const LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
-    if (st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8 && vec_ok) {
+    if (st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8) {
         st->k_valid = false;
         const GramTail t = tail_of(st, kGramFinishCoeffs);
-        return launch_stats(G, N, d, dtype, shape, st->partials, st->ds, t.cp, s, between);
+        return launch_stats(G, N, d, dtype, vec_ok, shape, st->partials, st->ds, t.cp, s, between);
     }
     st->k_valid = true;
     return launch_gram(G, N, d, dtype, vec_ok, shape, tail_of(st, kGramFinishCoeffs),

@@ -8,6 +8,11 @@ namespace adacons {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+// 128 bits of global memory that are only aligned to the element (fp32: 4 bytes, bf16: 2 bytes).
+// The device runs with unaligned access enabled, so these still compile to one 128-bit load or
+// store; rows of G that do not start on a 16-byte boundary cost extra cache-line visits, not a fault.
+typedef float gf32x4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef unsigned gu32x4 __attribute__((ext_vector_type(4), aligned(2)));
 
 typedef uint16_t bf16_bits;  // a bfloat16 as stored: the upper half of an IEEE binary32
 
@@ -25,12 +30,12 @@ __device__ __forceinline__ void load_vec(const T *__restrict__ p, float (&v)[VEC
 
 template <>
 __device__ __forceinline__ void load_vec<float, 4, false>(const float *__restrict__ p, float (&v)[4]) {
-    const f32x4 x = *reinterpret_cast<const f32x4 *>(p);
+    const f32x4 x = *reinterpret_cast<const gf32x4 *>(p);
     v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
 }
 template <>
 __device__ __forceinline__ void load_vec<float, 4, true>(const float *__restrict__ p, float (&v)[4]) {
-    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const gf32x4 *>(p));
     v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
 }
 template <>
@@ -48,11 +53,11 @@ __device__ __forceinline__ void unpack_bf16x8(const u32x4 x, float (&v)[8]) {
 }
 template <>
 __device__ __forceinline__ void load_vec<bf16_bits, 8, false>(const bf16_bits *__restrict__ p, float (&v)[8]) {
-    unpack_bf16x8(*reinterpret_cast<const u32x4 *>(p), v);
+    unpack_bf16x8(*reinterpret_cast<const gu32x4 *>(p), v);
 }
 template <>
 __device__ __forceinline__ void load_vec<bf16_bits, 8, true>(const bf16_bits *__restrict__ p, float (&v)[8]) {
-    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)), v);
+    unpack_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const gu32x4 *>(p)), v);
 }
 template <>
 __device__ __forceinline__ void load_vec<bf16_bits, 1, false>(const bf16_bits *__restrict__ p, float (&v)[1]) {

@@ -235,7 +235,7 @@ __device__ __forceinline__ void mfma_store_partial_row(const double (&acc64)[NT 
 // columns >= d count as zero: the load itself goes to a clamped (valid) address and the value is
 // replaced afterwards, so that the loads stay free of branches and the waits on them exact.
 // STREAM: non-temporal loads.
-template <int NT, typename T, int VEC4, bool STREAM>
+template <int NT, typename T, bool STREAM>
 __device__ __forceinline__ void mfma_load_chunk(const T *__restrict__ G, int N, int64_t d, int64_t ch, int r16,
                                                 int kq, float (&v)[kUnits][NT][4]) {
 #pragma unroll
@@ -245,37 +245,26 @@ __device__ __forceinline__ void mfma_load_chunk(const T *__restrict__ G, int N, 
         for (int t = 0; t < NT; ++t) {
             const int row = t * 16 + r16;
             const int rowc = row < N ? row : N - 1;
-            if constexpr (VEC4 != 0) {
-                // d is a multiple of the vector width here (>= 4 for fp32, >= 8 for bf16)
-                const bool live = row < N && col < d;
-                const int64_t colc = col < d ? col : d - 4;
-                const T *p = G + (int64_t)rowc * d + colc;
-                float w[4];
-                if constexpr (sizeof(T) == 4) {
-                    load_vec<float, 4, STREAM>(reinterpret_cast<const float *>(p), w);
-                } else {
-                    // 4 bf16 = one 64-bit load
-                    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-                    const u32x2 *q = reinterpret_cast<const u32x2 *>(p);
-                    u32x2 x;
-                    if constexpr (STREAM) x = __builtin_nontemporal_load(q); else x = *q;
-                    w[0] = __uint_as_float(x.x << 16);
-                    w[1] = __uint_as_float(x.x & 0xffff0000u);
-                    w[2] = __uint_as_float(x.y << 16);
-                    w[3] = __uint_as_float(x.y & 0xffff0000u);
-                }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) v[u][t][c] = live ? w[c] : 0.f;
+            // d is a multiple of the vector width here (>= 4 for fp32, >= 8 for bf16)
+            const bool live = row < N && col < d;
+            const int64_t colc = col < d ? col : d - 4;
+            const T *p = G + (int64_t)rowc * d + colc;
+            float w[4];
+            if constexpr (sizeof(T) == 4) {
+                load_vec<float, 4, STREAM>(reinterpret_cast<const float *>(p), w);
             } else {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const bool live = row < N && col + c < d;
-                    const int64_t colc = col + c < d ? col + c : d - 1;
-                    float one[1];
-                    load_vec<T, 1, STREAM>(G + (int64_t)rowc * d + colc, one);
-                    v[u][t][c] = live ? one[0] : 0.f;
-                }
+                // 4 bf16 = one 64-bit load
+                typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 *q = reinterpret_cast<const u32x2 *>(p);
+                u32x2 x;
+                if constexpr (STREAM) x = __builtin_nontemporal_load(q); else x = *q;
+                w[0] = __uint_as_float(x.x << 16);
+                w[1] = __uint_as_float(x.x & 0xffff0000u);
+                w[2] = __uint_as_float(x.y << 16);
+                w[3] = __uint_as_float(x.y & 0xffff0000u);
             }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[u][t][c] = live ? w[c] : 0.f;
         }
     }
 }
@@ -283,7 +272,7 @@ __device__ __forceinline__ void mfma_load_chunk(const T *__restrict__ G, int N, 
 // STREAM selects non-temporal loads (kept for measurement; the launcher uses ordinary loads).
 // The next chunk's loads are issued before the current chunk's MFMAs, so that the matrix
 // cores and the memory pipeline work at the same time even with one wavefront per SIMD.
-template <int NT, typename T, int VEC4, bool STREAM>
+template <int NT, typename T, bool STREAM>
 __global__ void __launch_bounds__(kBlock, (NT >= 3) ? 1 : 2)
 gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, GramTail tail) {
     constexpr int NPT = NT * (NT + 1) / 2;
@@ -306,11 +295,11 @@ gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, Gra
     const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
     int64_t ch = (int64_t)slot * (kBlock / kWave) + wave;
     float cur[kUnits][NT][4], nxt[kUnits][NT][4];
-    if (ch < nchunks) mfma_load_chunk<NT, T, VEC4, STREAM>(G, N, d, ch, r16, kq, cur);
+    if (ch < nchunks) mfma_load_chunk<NT, T, STREAM>(G, N, d, ch, r16, kq, cur);
     while (ch < nchunks) {
         const int64_t chn = ch + wstride;
         // past the end the last chunk is simply loaded again (in bounds, never used)
-        mfma_load_chunk<NT, T, VEC4, STREAM>(G, N, d, chn < nchunks ? chn : nchunks - 1, r16, kq, nxt);
+        mfma_load_chunk<NT, T, STREAM>(G, N, d, chn < nchunks ? chn : nchunks - 1, r16, kq, nxt);
 #pragma unroll
         for (int u = 0; u < kUnits; ++u) {
 #pragma unroll
@@ -502,8 +491,8 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 template <int NT, typename T>
 __global__ void __launch_bounds__(kBlock, (NT >= 4) ? 1 : 2)
-gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, int64_t cached_chunks,
-                      double *__restrict__ partials) {
+gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks,
+                      int64_t cached_chunks, double *__restrict__ partials) {
     constexpr int NPT = NT * (NT + 1) / 2;
     constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
     constexpr int VECW = VecWidth<T>::value;                  // columns per 16-byte piece
@@ -534,14 +523,14 @@ gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks
             const int row = 4 * j + (lane >> 4);
             const int64_t col = ch * kCols + (lane & 15) * VECW;
             if constexpr (decltype(interior)::value) {
-                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)row * d + col);
+                const gf32x4 *src = reinterpret_cast<const gf32x4 *>(G + (int64_t)row * d + col);
                 if constexpr (decltype(stream)::value) stage[j] = __builtin_nontemporal_load(src);
                 else stage[j] = *src;
             } else {
-                const bool live = row < N && col < d;   // d is a multiple of VECW on this path
+                const bool live = row < N && col < dcols;   // dcols is a multiple of VECW
                 const int rowc = row < N ? row : N - 1;
-                const int64_t colc = col < d ? col : d - VECW;
-                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+                const int64_t colc = col < dcols ? col : dcols - VECW;
+                const gf32x4 *src = reinterpret_cast<const gf32x4 *>(G + (int64_t)rowc * d + colc);
                 f32x4 x;
                 if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
                 else x = *src;
@@ -549,7 +538,7 @@ gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks
             }
         }
     };
-    const int64_t full_chunks = (N == kRows) ? d / kCols : 0;   // chunks below this index are interior
+    const int64_t full_chunks = (N == kRows) ? dcols / kCols : 0;   // chunks below this index are interior
     auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
         if (ch < full_chunks) load_chunk_as(ch, stream, std::true_type{});
         else load_chunk_as(ch, stream, std::false_type{});
@@ -646,8 +635,8 @@ gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks
 
 template <int NT>
 __global__ void __launch_bounds__(kBlock, (NT >= 3) ? 1 : 2)
-gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nchunks, int64_t cached_chunks,
-                       double *__restrict__ partials) {
+gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks,
+                       int64_t cached_chunks, double *__restrict__ partials) {
     constexpr int NPT = NT * (NT + 1) / 2;
     constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
     constexpr int kPlaneBytes = kRows * 128;                  // kRows x 64 bf16
@@ -676,14 +665,14 @@ gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nc
             const int row = 4 * j + (lane >> 4);
             const int64_t col = ch * 64 + (lane & 15) * 4;
             if constexpr (decltype(interior)::value) {
-                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)row * d + col);
+                const gf32x4 *src = reinterpret_cast<const gf32x4 *>(G + (int64_t)row * d + col);
                 if constexpr (decltype(stream)::value) stage[j] = __builtin_nontemporal_load(src);
                 else stage[j] = *src;
             } else {
-                const bool live = row < N && col < d;   // d is a multiple of 4 on this path
+                const bool live = row < N && col < dcols;   // dcols is a multiple of 4
                 const int rowc = row < N ? row : N - 1;
-                const int64_t colc = col < d ? col : d - 4;
-                const f32x4 *src = reinterpret_cast<const f32x4 *>(G + (int64_t)rowc * d + colc);
+                const int64_t colc = col < dcols ? col : dcols - 4;
+                const gf32x4 *src = reinterpret_cast<const gf32x4 *>(G + (int64_t)rowc * d + colc);
                 f32x4 x;
                 if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
                 else x = *src;
@@ -691,7 +680,7 @@ gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t nc
             }
         }
     };
-    const int64_t full_chunks = (N == kRows) ? d / 64 : 0;   // chunks below this index are interior
+    const int64_t full_chunks = (N == kRows) ? dcols / 64 : 0;   // chunks below this index are interior
     auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
         if (ch < full_chunks) load_chunk_as(ch, stream, std::true_type{});
         else load_chunk_as(ch, stream, std::false_type{});
@@ -805,11 +794,12 @@ int gram_rows_needed(int N, int num_cu) {
     return num_cu * 8;  // upper bound on workgroups per CU for any Gram kernel
 }
 
+// dcols: the columns this launch covers, a multiple of VEC (rows are d elements apart).
 template <int N, typename T, int VEC>
-static hipError_t run_vec(const void *G, int64_t d, const LaunchShape &shape, const GramTail &tail, hipStream_t s,
-                          int *grid_out) {
+static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchShape &shape, const GramTail &tail,
+                          hipStream_t s, int *grid_out) {
     static const int occ = occupancy(gram_vec_kernel<N, T, VEC>);
-    const int64_t ngroups = (d + VEC - 1) / VEC;
+    const int64_t ngroups = dcols / VEC;
     // measured best: one workgroup per CU for fp32, two for bf16 (twice the FMAs per byte)
     const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ, sizeof(T) == 2 ? 2 : 1);
     *grid_out = grid;
@@ -823,31 +813,31 @@ static hipError_t run_vec(const void *G, int64_t d, const LaunchShape &shape, co
 }
 
 template <typename T, int VEC>
-static hipError_t dispatch_vec(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
-                               hipStream_t s, int *grid_out) {
+static hipError_t dispatch_vec(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
+                               const GramTail &tail, hipStream_t s, int *grid_out) {
     switch (N) {
-        case 1: return run_vec<1, T, VEC>(G, d, shape, tail, s, grid_out);
-        case 2: return run_vec<2, T, VEC>(G, d, shape, tail, s, grid_out);
-        case 3: return run_vec<3, T, VEC>(G, d, shape, tail, s, grid_out);
-        case 4: return run_vec<4, T, VEC>(G, d, shape, tail, s, grid_out);
-        case 5: return run_vec<5, T, VEC>(G, d, shape, tail, s, grid_out);
-        case 6: return run_vec<6, T, VEC>(G, d, shape, tail, s, grid_out);
-        case 7: return run_vec<7, T, VEC>(G, d, shape, tail, s, grid_out);
-        case 8: return run_vec<8, T, VEC>(G, d, shape, tail, s, grid_out);
+        case 1: return run_vec<1, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 2: return run_vec<2, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 3: return run_vec<3, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 4: return run_vec<4, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 5: return run_vec<5, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 6: return run_vec<6, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 7: return run_vec<7, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 8: return run_vec<8, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
 
-template <int NT, typename T, int VEC4, bool STREAM>
+template <int NT, typename T, bool STREAM>
 static hipError_t run_mfma_as(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
                               hipStream_t s, int *grid_out) {
-    static const int occ = occupancy(gram_mfma_kernel<NT, T, VEC4, STREAM>);
+    static const int occ = occupancy(gram_mfma_kernel<NT, T, STREAM>);
     const int64_t cols_per_chunk = 16 * kUnits;
     const int64_t nchunks = (d + cols_per_chunk - 1) / cols_per_chunk;
     const int waves = kBlock / kWave;
     const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, NT >= 3 ? 1 : 2);
     *grid_out = grid;
-    hipLaunchKernelGGL((gram_mfma_kernel<NT, T, VEC4, STREAM>), dim3(grid), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL((gram_mfma_kernel<NT, T, STREAM>), dim3(grid), dim3(kBlock), 0, s,
                        static_cast<const T *>(G), N, d, nchunks, tail);
     return hipGetLastError();
 }
@@ -865,16 +855,17 @@ static hipError_t run_mfma_lds(const void *G, int N, int64_t d, const LaunchShap
 }
 
 // SPLIT (fp32 only): products on the bf16 matrix-core path (gram_mfma_split_kernel) instead of the fp32 one.
+// dcols: the columns this launch covers, a multiple of the 128-bit vector width (rows are d elements apart).
 template <int NT, typename T, bool SPLIT>
-static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
-                                hipStream_t s, int *grid_out) {
+static hipError_t run_mfma_wave(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
+                                const GramTail &tail, hipStream_t s, int *grid_out) {
     auto kern = [] {
         if constexpr (SPLIT && sizeof(T) == 4) return gram_mfma_split_kernel<NT>;
         else return gram_mfma_wave_kernel<NT, T>;
     }();
     static const int occ = occupancy(kern);
     const int64_t cols = 16 * VecWidth<T>::value;   // columns per chunk
-    const int64_t nchunks = (d + cols - 1) / cols;
+    const int64_t nchunks = (dcols + cols - 1) / cols;
     const int waves = kBlock / kWave;
     const int dflt = SPLIT ? (NT >= 3 ? 1 : 2) : (NT >= 4 ? 1 : 2);
     const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, dflt);
@@ -887,42 +878,65 @@ static hipError_t run_mfma_wave(const void *G, int N, int64_t d, const LaunchSha
     int64_t cached_chunks = nchunks + (int64_t)grid * waves;   // beyond every prefetch
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N, d, nchunks,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N, d, dcols, nchunks,
                        cached_chunks, tail.partials);
     return hipGetLastError();
 }
 
-template <int NT, typename T, int VEC4>
-static hipError_t run_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
-                           hipStream_t s, int *grid_out) {
-    if constexpr (VEC4 != 0) {
-        // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.10 against
-        // 1.29 ms) and N = 48 (0.80 against 0.88 ms) and are even at N <= 32 (where the whole step
-        // measured 2 % slower with them).  bf16 inputs need no split (3 = 2).
-        const int variant = shape.mfma_direct == 4 ? ((NT >= 3 && sizeof(T) == 4) ? 3 : 2) : shape.mfma_direct;
-        if (tail.mode == kGramPartialsOnly && variant == 2)
-            return run_mfma_wave<NT, T, false>(G, N, d, shape, tail, s, grid_out);
-        if (tail.mode == kGramPartialsOnly && variant == 3)
-            return run_mfma_wave<NT, T, true>(G, N, d, shape, tail, s, grid_out);
-    }
-    // the LDS-staged kernel needs the 128-bit path and leaves the reduction to a later launch
-    if (VEC4 != 0 && tail.mode == kGramPartialsOnly && shape.mfma_direct == 0)
+// The wavefront-transpose kernels (variants 2 and 3) take any element-aligned G and any dcols that is a
+// multiple of the vector width; the direct and LDS-tile kernels (variants 1 and 0) and the fused tail
+// need 16-byte aligned rows and dcols = d, which the caller guarantees before selecting them.
+template <int NT, typename T>
+static hipError_t run_mfma(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
+                           const GramTail &tail, hipStream_t s, int *grid_out) {
+    // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.10 against
+    // 1.29 ms) and N = 48 (0.80 against 0.88 ms) and are even at N <= 32 (where the whole step
+    // measured 2 % slower with them).  bf16 inputs need no split (3 = 2).
+    const int variant = shape.mfma_direct == 4 ? ((NT >= 3 && sizeof(T) == 4) ? 3 : 2) : shape.mfma_direct;
+    if (tail.mode == kGramPartialsOnly && variant == 2)
+        return run_mfma_wave<NT, T, false>(G, N, d, dcols, shape, tail, s, grid_out);
+    if (tail.mode == kGramPartialsOnly && variant == 3)
+        return run_mfma_wave<NT, T, true>(G, N, d, dcols, shape, tail, s, grid_out);
+    if (dcols != d) return hipErrorInvalidValue;
+    // the LDS-staged kernel leaves the reduction to a later launch
+    if (tail.mode == kGramPartialsOnly && shape.mfma_direct == 0)
         return run_mfma_lds<NT, T>(G, N, d, shape, tail, s, grid_out);
     // Ordinary loads only: one load instruction takes 64 contiguous bytes of each of 16 rows, so
     // the other half of every 128-byte line is needed by the next instruction; non-temporal loads
     // do not keep the line and measured 20 % slower here.
-    return run_mfma_as<NT, T, VEC4, false>(G, N, d, shape, tail, s, grid_out);
+    return run_mfma_as<NT, T, false>(G, N, d, shape, tail, s, grid_out);
 }
 
-template <typename T, int VEC4>
-static hipError_t dispatch_mfma(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
-                                hipStream_t s, int *grid_out) {
+template <typename T>
+static hipError_t dispatch_mfma(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
+                                const GramTail &tail, hipStream_t s, int *grid_out) {
     switch ((N + 15) / 16) {
-        case 1: return run_mfma<1, T, VEC4>(G, N, d, shape, tail, s, grid_out);
-        case 2: return run_mfma<2, T, VEC4>(G, N, d, shape, tail, s, grid_out);
-        case 3: return run_mfma<3, T, VEC4>(G, N, d, shape, tail, s, grid_out);
-        case 4: return run_mfma<4, T, VEC4>(G, N, d, shape, tail, s, grid_out);
+        case 1: return run_mfma<1, T>(G, N, d, dcols, shape, tail, s, grid_out);
+        case 2: return run_mfma<2, T>(G, N, d, dcols, shape, tail, s, grid_out);
+        case 3: return run_mfma<3, T>(G, N, d, dcols, shape, tail, s, grid_out);
+        case 4: return run_mfma<4, T>(G, N, d, dcols, shape, tail, s, grid_out);
         default: return hipErrorInvalidValue;
+    }
+}
+
+// The last d - col0 < 8 columns of every row, which no whole 128-bit group covers: their products go
+// into one more partial row (packed upper triangle), added with the others by the reduction.
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+gram_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, double *__restrict__ row_out) {
+    const int np = num_pairs(N);
+    const int ncols = (int)(d - col0);
+    for (int p = threadIdx.x; p < np; p += kBlock) {
+        int i, j;
+        unpack_pair(p, N, i, j);
+        double tot = 0.0;
+        for (int c = 0; c < ncols; ++c) {
+            float a[1], b[1];
+            load_vec<T, 1, false>(G + (int64_t)i * d + col0 + c, a);
+            load_vec<T, 1, false>(G + (int64_t)j * d + col0 + c, b);
+            tot = fma((double)a[0], (double)b[0], tot);
+        }
+        row_out[p] = tot;
     }
 }
 
@@ -930,27 +944,41 @@ static hipError_t dispatch_mfma(const void *G, int N, int64_t d, const LaunchSha
 // With `fuse` and N(N+1)/2 <= kBlock the Gram kernel's last workgroup does it; otherwise one
 // finish_kernel launch does (N <= 44), or a multi-workgroup reduction followed by coeff_kernel.
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
-                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream,
+                       const LaunchShape &shape_in, const GramTail &want, bool fuse, hipStream_t stream,
                        hipEvent_t between) {
+    // Without 16-byte aligned rows (vec_ok false) the same 128-bit kernels run from element-aligned
+    // addresses over the whole groups of every row, the columns left over (fewer than one group) go
+    // through gram_edge_kernel into one more partial row, and nothing is fused into the Gram kernel.
+    const int64_t vec = (dtype == ADACONS_F32) ? 4 : 8;
+    const int64_t dcols = vec_ok ? d : d / vec * vec;
+    LaunchShape shape = shape_in;
+    if (!vec_ok) {
+        if (shape.max_rows < 2) return hipErrorInvalidValue;
+        shape.max_rows -= 1;   // room for the edge row
+        if (shape.mfma_direct != 2 && shape.mfma_direct != 3) shape.mfma_direct = 4;
+    }
     GramTail tail = want;
-    const bool fused = fuse && num_pairs(N) <= kBlock;
+    const bool fused = fuse && vec_ok && num_pairs(N) <= kBlock;
     if (!fused) tail.mode = kGramPartialsOnly;
     int grid = 0;
     hipError_t e;
     if (N <= 8) {
-        if (dtype == ADACONS_F32)
-            e = vec_ok ? dispatch_vec<float, 4>(G, N, d, shape, tail, stream, &grid)
-                       : dispatch_vec<float, 1>(G, N, d, shape, tail, stream, &grid);
-        else
-            e = vec_ok ? dispatch_vec<bf16_bits, 8>(G, N, d, shape, tail, stream, &grid)
-                       : dispatch_vec<bf16_bits, 1>(G, N, d, shape, tail, stream, &grid);
+        e = (dtype == ADACONS_F32) ? dispatch_vec<float, 4>(G, N, d, dcols, shape, tail, stream, &grid)
+                                   : dispatch_vec<bf16_bits, 8>(G, N, d, dcols, shape, tail, stream, &grid);
     } else {
+        e = (dtype == ADACONS_F32) ? dispatch_mfma<float>(G, N, d, dcols, shape, tail, stream, &grid)
+                                   : dispatch_mfma<bf16_bits>(G, N, d, dcols, shape, tail, stream, &grid);
+    }
+    if (e == hipSuccess && dcols < d) {
+        double *row = want.partials + (size_t)grid * num_pairs(N);
         if (dtype == ADACONS_F32)
-            e = vec_ok ? dispatch_mfma<float, 1>(G, N, d, shape, tail, stream, &grid)
-                       : dispatch_mfma<float, 0>(G, N, d, shape, tail, stream, &grid);
+            hipLaunchKernelGGL(gram_edge_kernel<float>, dim3(1), dim3(kBlock), 0, stream,
+                               static_cast<const float *>(G), N, d, dcols, row);
         else
-            e = vec_ok ? dispatch_mfma<bf16_bits, 1>(G, N, d, shape, tail, stream, &grid)
-                       : dispatch_mfma<bf16_bits, 0>(G, N, d, shape, tail, stream, &grid);
+            hipLaunchKernelGGL(gram_edge_kernel<bf16_bits>, dim3(1), dim3(kBlock), 0, stream,
+                               static_cast<const bf16_bits *>(G), N, d, dcols, row);
+        e = hipGetLastError();
+        grid += 1;
     }
     if (e == hipSuccess && between) e = hipEventRecord(between, stream);
     if (e != hipSuccess || fused) return e;

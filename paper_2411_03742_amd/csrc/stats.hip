@@ -34,7 +34,7 @@ template <int NT, typename T> struct StatsShape {
 
 template <int NT, typename T>
 __global__ void __launch_bounds__(kBlock, (NT * VecWidth<T>::value >= 16) ? 1 : 2)
-stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, int64_t cached_chunks,
+stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks, int64_t cached_chunks,
                   double *__restrict__ partials) {
     constexpr int VECW = VecWidth<T>::value;
     constexpr int kLoads = 4 * NT;
@@ -47,7 +47,8 @@ stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, in
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) qacc[j] = racc[j] = 0.0;
 
-    // branch-free loads: rows >= N and columns >= d read a clamped address and are zeroed
+    // branch-free loads: rows >= N and columns >= dcols (a multiple of VECW; rows are d elements apart)
+    // read a clamped address and are zeroed
     auto load_chunk = [&](u32x4 (&dst)[kSuper][kLoads], int64_t ch, auto stream) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < kSuper; ++u)
@@ -55,10 +56,10 @@ stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, in
             for (int j = 0; j < kLoads; ++j) {
                 const int row = 4 * j + grp;
                 const int64_t col = (ch * kSuper + u) * kChunk + (int64_t)cl * VECW;
-                const bool live = row < N && col < d;   // d is a multiple of VECW on this path
+                const bool live = row < N && col < dcols;
                 const int rowc = row < N ? row : N - 1;
-                const int64_t colc = col < d ? col : d - VECW;
-                const u32x4 *src = reinterpret_cast<const u32x4 *>(G + (int64_t)rowc * d + colc);
+                const int64_t colc = col < dcols ? col : dcols - VECW;
+                const gu32x4 *src = reinterpret_cast<const gu32x4 *>(G + (int64_t)rowc * d + colc);
                 u32x4 x;
                 if constexpr (decltype(stream)::value) x = __builtin_nontemporal_load(src);
                 else x = *src;
@@ -174,9 +175,33 @@ stats_finish_kernel(const double *partials, int nrows, DevState *ds, CoeffParams
     update_coefficients_from_stats(q, r, ds, cp, lds, m_old);
 }
 
+// The last d - col0 < 8 columns, which no whole 128-bit group covers: one more partial row.
+template <typename T>
+__global__ void __launch_bounds__(kWave)
+stats_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, double *__restrict__ row_out) {
+    const int i = threadIdx.x;
+    if (i >= N) return;
+    const int ncols = (int)(d - col0);
+    double q = 0.0, r = 0.0;
+    for (int c = 0; c < ncols; ++c) {
+        double s = 0.0;
+        for (int j = 0; j < N; ++j) {
+            float v[1];
+            load_vec<T, 1, false>(G + (int64_t)j * d + col0 + c, v);
+            s += (double)v[0];
+        }
+        float x[1];
+        load_vec<T, 1, false>(G + (int64_t)i * d + col0 + c, x);
+        q = fma((double)x[0], (double)x[0], q);
+        r = fma((double)x[0], s, r);
+    }
+    row_out[i] = q;
+    row_out[N + i] = r;
+}
+
 template <int NT, typename T>
-hipError_t run_stats(const void *G, int N, int64_t d, const LaunchShape &shape, double *partials, hipStream_t s,
-                     int *grid_out) {
+hipError_t run_stats(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, double *partials,
+                     hipStream_t s, int *grid_out) {
     static const int occ = [] {
         int nb = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, stats_wave_kernel<NT, T>, kBlock, 0) != hipSuccess || nb < 1)
@@ -184,7 +209,7 @@ hipError_t run_stats(const void *G, int N, int64_t d, const LaunchShape &shape, 
         return nb;
     }();
     const int64_t chunk = 16 * VecWidth<T>::value * StatsShape<NT, T>::kSuper;   // columns a wavefront takes at a time
-    const int64_t nchunks = (d + chunk - 1) / chunk;
+    const int64_t nchunks = (dcols + chunk - 1) / chunk;
     const int waves = kBlock / kWave;
     int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 2;
     if (per_cu > occ) per_cu = occ;
@@ -203,31 +228,50 @@ hipError_t run_stats(const void *G, int N, int64_t d, const LaunchShape &shape, 
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * chunk * (int64_t)sizeof(T));
     hipLaunchKernelGGL((stats_wave_kernel<NT, T>), dim3((unsigned)grid), dim3(kBlock), 0, s, static_cast<const T *>(G),
-                       N, d, nchunks, cached_chunks, partials);
+                       N, d, dcols, nchunks, cached_chunks, partials);
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t dispatch_stats(const void *G, int N, int64_t d, const LaunchShape &shape, double *partials, hipStream_t s,
-                          int *grid_out) {
+hipError_t dispatch_stats(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, double *partials,
+                          hipStream_t s, int *grid_out) {
     switch ((N + 15) / 16) {
-        case 1: return run_stats<1, T>(G, N, d, shape, partials, s, grid_out);
-        case 2: return run_stats<2, T>(G, N, d, shape, partials, s, grid_out);
-        case 3: return run_stats<3, T>(G, N, d, shape, partials, s, grid_out);
-        case 4: return run_stats<4, T>(G, N, d, shape, partials, s, grid_out);
+        case 1: return run_stats<1, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 2: return run_stats<2, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 3: return run_stats<3, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 4: return run_stats<4, T>(G, N, d, dcols, shape, partials, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-// G 16-byte aligned with d * sizeof(element) a multiple of 16; the partial rows need 2 N doubles
-// per workgroup (never more than the N (N + 1) / 2 of a Gram row for N >= 3).
-hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, const LaunchShape &shape,
+// The partial rows need 2 N doubles per workgroup (never more than the N (N + 1) / 2 of a Gram row for
+// N >= 3).  Without 16-byte aligned rows (vec_ok false) the kernel covers the whole 128-bit groups of
+// every row from element-aligned addresses and stats_edge_kernel adds a row for the columns left over.
+hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok, const LaunchShape &shape_in,
                         double *partials, DevState *ds, const CoeffParams &cp, hipStream_t stream, hipEvent_t between) {
+    const int64_t vec = (dtype == ADACONS_F32) ? 4 : 8;
+    const int64_t dcols = vec_ok ? d : d / vec * vec;
+    LaunchShape shape = shape_in;
+    if (!vec_ok) {
+        if (shape.max_rows < 2) return hipErrorInvalidValue;
+        shape.max_rows -= 1;   // room for the edge row
+    }
     int grid = 0;
-    hipError_t e = (dtype == ADACONS_F32) ? dispatch_stats<float>(G, N, d, shape, partials, stream, &grid)
-                                          : dispatch_stats<bf16_bits>(G, N, d, shape, partials, stream, &grid);
+    hipError_t e = (dtype == ADACONS_F32) ? dispatch_stats<float>(G, N, d, dcols, shape, partials, stream, &grid)
+                                          : dispatch_stats<bf16_bits>(G, N, d, dcols, shape, partials, stream, &grid);
+    if (e == hipSuccess && dcols < d) {
+        double *row = partials + (size_t)grid * (2 * N);
+        if (dtype == ADACONS_F32)
+            hipLaunchKernelGGL(stats_edge_kernel<float>, dim3(1), dim3(kWave), 0, stream, static_cast<const float *>(G),
+                               N, d, dcols, row);
+        else
+            hipLaunchKernelGGL(stats_edge_kernel<bf16_bits>, dim3(1), dim3(kWave), 0, stream,
+                               static_cast<const bf16_bits *>(G), N, d, dcols, row);
+        e = hipGetLastError();
+        grid += 1;
+    }
     if (e == hipSuccess && between) e = hipEventRecord(between, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(stats_finish_kernel, dim3(1), dim3(kStatsFinishBlock), 0, stream, partials, grid, ds, cp);

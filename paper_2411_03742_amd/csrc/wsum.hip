@@ -19,22 +19,17 @@ constexpr int kRowsInFlight = 8;
 // with ordinary accesses, it is needed again next step).
 template <int VEC, bool APPLY>
 __device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, const float (&acc)[VEC], float lr) {
-    if constexpr (VEC == 1) {
-        if constexpr (APPLY) out[col] = fmaf(-lr, acc[0], out[col]);
-        else __builtin_nontemporal_store(acc[0], out + col);
-    } else {
 #pragma unroll
-        for (int c = 0; c < VEC; c += 4) {
-            f32x4 *dst = reinterpret_cast<f32x4 *>(out + col + c);
-            if constexpr (APPLY) {
-                const f32x4 w = *dst;
-                const f32x4 x = {fmaf(-lr, acc[c], w.x), fmaf(-lr, acc[c + 1], w.y), fmaf(-lr, acc[c + 2], w.z),
-                                 fmaf(-lr, acc[c + 3], w.w)};
-                *dst = x;
-            } else {
-                const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
-                __builtin_nontemporal_store(x, dst);
-            }
+    for (int c = 0; c < VEC; c += 4) {
+        gf32x4 *dst = reinterpret_cast<gf32x4 *>(out + col + c);
+        if constexpr (APPLY) {
+            const f32x4 w = *dst;
+            const f32x4 x = {fmaf(-lr, acc[c], w.x), fmaf(-lr, acc[c + 1], w.y), fmaf(-lr, acc[c + 2], w.z),
+                             fmaf(-lr, acc[c + 3], w.w)};
+            *dst = x;
+        } else {
+            const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+            __builtin_nontemporal_store(x, dst);
         }
     }
 }
@@ -57,7 +52,7 @@ __device__ __forceinline__ void store_out_wave8(float *__restrict__ out, int64_t
             v[c] = odd ? hi : lo;
         }
         const f32x4 x = {v[0], v[1], v[2], v[3]};
-        __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + wave_col + h * 256 + lane * 4));
+        __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(out + wave_col + h * 256 + lane * 4));
     }
 }
 
@@ -148,11 +143,12 @@ static int occupancy(Kern k) {
     return nb;
 }
 
+// dcols: the columns this launch covers, a multiple of VEC (rows are d elements apart).
 template <int NCT, typename T, int VEC, int UNR, bool APPLY>
-static hipError_t run_as(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
-                         bool reverse, float lr, hipStream_t s) {
+static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, const float *gamma,
+                         float *out, bool reverse, float lr, hipStream_t s) {
     static const int occ = occupancy(wsum_kernel<NCT, T, VEC, UNR, APPLY>);
-    const int64_t ngroups = (d + VEC - 1) / VEC;
+    const int64_t ngroups = dcols / VEC;
     const int64_t work = (ngroups + (int64_t)kBlock * UNR - 1) / ((int64_t)kBlock * UNR);
     // Measured: eight workgroups per CU while G is small enough for the memory-side cache to matter
     // (N = 8, 0.8 GB: 138 us against 150 us at one per CU); one per CU for long streams of few rows
@@ -175,32 +171,57 @@ struct WsumMode {
 };
 
 template <int NCT, typename T, int VEC, int UNR>
-static hipError_t run(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
-                      const WsumMode &m, hipStream_t s) {
-    return m.apply ? run_as<NCT, T, VEC, UNR, true>(G, N, d, shape, gamma, out, m.reverse, m.lr, s)
-                   : run_as<NCT, T, VEC, UNR, false>(G, N, d, shape, gamma, out, m.reverse, 0.f, s);
+static hipError_t run(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, const float *gamma,
+                      float *out, const WsumMode &m, hipStream_t s) {
+    return m.apply ? run_as<NCT, T, VEC, UNR, true>(G, N, d, dcols, shape, gamma, out, m.reverse, m.lr, s)
+                   : run_as<NCT, T, VEC, UNR, false>(G, N, d, dcols, shape, gamma, out, m.reverse, 0.f, s);
 }
 
 template <typename T, int VEC, int UNR>
-static hipError_t dispatch(const void *G, int N, int64_t d, const LaunchShape &shape, const float *gamma, float *out,
-                           const WsumMode &m, hipStream_t s) {
+static hipError_t dispatch(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
+                           const float *gamma, float *out, const WsumMode &m, hipStream_t s) {
     switch (N) {
-        case 4: return run<4, T, VEC, UNR>(G, N, d, shape, gamma, out, m, s);
-        case 8: return run<8, T, VEC, UNR>(G, N, d, shape, gamma, out, m, s);
-        case 16: return run<16, T, VEC, 1>(G, N, d, shape, gamma, out, m, s);  // 16 loads in flight already
-        default: return run<0, T, VEC, UNR>(G, N, d, shape, gamma, out, m, s);
+        case 4: return run<4, T, VEC, UNR>(G, N, d, dcols, shape, gamma, out, m, s);
+        case 8: return run<8, T, VEC, UNR>(G, N, d, dcols, shape, gamma, out, m, s);
+        case 16: return run<16, T, VEC, 1>(G, N, d, dcols, shape, gamma, out, m, s);  // 16 loads in flight already
+        default: return run<0, T, VEC, UNR>(G, N, d, dcols, shape, gamma, out, m, s);
     }
 }
 
+// The last d - col0 < 8 columns, which no whole 128-bit group covers: one thread per column.
+template <typename T>
+__global__ void __launch_bounds__(kWave)
+wsum_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, const float *__restrict__ gamma,
+                 float *__restrict__ out, int apply, float lr) {
+    const int64_t col = col0 + threadIdx.x;
+    if (col >= d) return;
+    float acc = 0.f;
+    for (int i = 0; i < N; ++i) {
+        float v[1];
+        load_vec<T, 1, false>(G + (int64_t)i * d + col, v);
+        acc = fmaf(gamma[i], v[0], acc);
+    }
+    out[col] = apply ? fmaf(-lr, acc, out[col]) : acc;
+}
+
+// Without 16-byte aligned rows and output (vec_ok false) the same kernels run from element-aligned
+// addresses over the whole 128-bit groups of every row; wsum_edge_kernel takes the columns left over.
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const float *gamma, float *out, bool reverse,
                        hipStream_t stream, bool apply, float lr) {
     const WsumMode m = {reverse, apply, lr};
+    const int64_t vec = (dtype == ADACONS_F32) ? 4 : 8;
+    const int64_t dcols = vec_ok ? d : d / vec * vec;
+    hipError_t e = (dtype == ADACONS_F32) ? dispatch<float, 4, 2>(G, N, d, dcols, shape, gamma, out, m, stream)
+                                          : dispatch<bf16_bits, 8, 2>(G, N, d, dcols, shape, gamma, out, m, stream);
+    if (e != hipSuccess || dcols == d) return e;
     if (dtype == ADACONS_F32)
-        return vec_ok ? dispatch<float, 4, 2>(G, N, d, shape, gamma, out, m, stream)
-                      : dispatch<float, 1, 2>(G, N, d, shape, gamma, out, m, stream);
-    return vec_ok ? dispatch<bf16_bits, 8, 2>(G, N, d, shape, gamma, out, m, stream)
-                  : dispatch<bf16_bits, 1, 2>(G, N, d, shape, gamma, out, m, stream);
+        hipLaunchKernelGGL(wsum_edge_kernel<float>, dim3(1), dim3(kWave), 0, stream, static_cast<const float *>(G), N, d,
+                           dcols, gamma, out, apply ? 1 : 0, lr);
+    else
+        hipLaunchKernelGGL(wsum_edge_kernel<bf16_bits>, dim3(1), dim3(kWave), 0, stream,
+                           static_cast<const bf16_bits *>(G), N, d, dcols, gamma, out, apply ? 1 : 0, lr);
+    return hipGetLastError();
 }
 
 }  // namespace adacons

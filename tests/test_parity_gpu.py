@@ -257,14 +257,23 @@ def test_tiny_and_ragged_shapes(pkg, N, d):
     agg.close()
 
 
+def shifted_rows(N, d, dtype, shift, seed=0):
+    """An N x d contiguous view that starts `shift` elements into a fresh allocation."""
+    flat = torch.empty(N * d + shift, device=DEV, dtype=dtype)
+    G = flat[shift:].view(N, d)
+    G.copy_(randG(N, d, dtype=dtype, seed=seed))   # a common signal plus noise: well-conditioned coefficients
+    assert G.is_contiguous() and G.data_ptr() == flat.data_ptr() + shift * flat.element_size()
+    return G
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("N", [4, 16])
 def test_unaligned_base_and_odd_length(pkg, N, dtype):
-    """G starting one element past a 16-byte boundary, odd d: the element-wise path."""
+    """G starting one element past a 16-byte boundary, odd d: 128-bit accesses from element-aligned
+    addresses plus the kernels for the columns that no whole group covers."""
     d = 100_001
-    flat = torch.randn(N * d + 1, device=DEV).to(dtype)
-    G = flat[1:].view(N, d)
-    assert G.data_ptr() % 16 != 0 and G.is_contiguous()
+    G = shifted_rows(N, d, dtype, 1)
+    assert G.data_ptr() % 16 != 0
     agg = pkg.AdaCons(N, d)
     both(pkg, G, agg, o.OracleState(N))
     outbuf = torch.empty(d + 1, device=DEV)
@@ -272,6 +281,38 @@ def test_unaligned_base_and_odd_length(pkg, N, dtype):
     out2 = agg2.aggregate(G, out=outbuf[1:])
     assert rel_l2(out2.cpu().numpy(), agg.aggregate(G).cpu().numpy()) <= 1e-6
     agg.close(); agg2.close()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("N,d,shift", [(1, 5, 1), (3, 2, 0), (5, 9, 3), (8, 70_003, 0), (8, 70_000, 2), (7, 262_150, 5),
+                                       (8, 1_048_577, 0), (9, 7, 1), (16, 33, 0), (16, 70_001, 3), (24, 65_543, 0),
+                                       (33, 20_002, 1), (48, 40_005, 0), (64, 131_079, 7), (64, 65_536, 1), (64, 6, 0)])
+@pytest.mark.parametrize("stats_only", [0, 1])
+def test_rows_off_16_byte_boundaries(pkg, N, d, shift, dtype, stats_only):
+    """Every leftover count (d mod 4 for fp32, d mod 8 for bf16), shifted bases, d smaller than one
+    group, all row-tile counts, with and without the statistics-only first pass, over two steps
+    (momentum carried); then the fused descent step on the same input."""
+    if stats_only and N <= 8:
+        pytest.skip("statistics-only applies to N > 8")
+    agg = pkg.AdaCons(N, d, beta=0.8)
+    agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)
+    ost = o.OracleState(N, beta=0.8)
+    for t in range(2):
+        G = shifted_rows(N, d, dtype, shift, seed=17 * N + t)
+        both(pkg, G, agg, ost)
+    if not stats_only:
+        K = pkg.adacons_read_gram(agg._st, N, None)
+        assert rel_l2(K, o.gram(workloads.to_oracle_input(G))) <= 3e-7
+    # w <- w - lr * aggregate with an output that is itself off the 16-byte grid
+    wbuf = torch.randn(d + 1, device=DEV)
+    w = wbuf[1:]
+    w0 = w.clone()
+    agg.aggregate_apply(G, w, lr=0.25)
+    oout, oinfo = o.aggregate(workloads.to_oracle_input(G), ost)
+    if rank_gap_is_safe(oinfo["raw"]):
+        ref = w0.cpu().numpy().astype(np.float64) - 0.25 * oout
+        assert rel_l2(w.cpu().numpy(), ref) <= 1e-5
+    agg.close()
 
 
 def test_d_smaller_than_d_max_and_state_reuse(pkg):
@@ -456,16 +497,15 @@ def test_statistics_only_first_pass_matches_oracle(pkg, N, d, dtype):
 
 
 def test_statistics_only_is_ignored_where_it_does_not_apply(pkg):
-    """N <= 8 and inputs off the 128-bit path keep the Gram kernels (K stays available)."""
-    for N, d, shift in [(8, 100_000, 0), (16, 100_001, 1)]:
-        flat = torch.randn(N * d + shift, device=DEV)
-        G = flat[shift:].view(N, d)
-        agg = pkg.AdaCons(N, d)
-        agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, 1)
-        both(pkg, G, agg, o.OracleState(N))
-        K = pkg.adacons_read_gram(agg._st, N, None)
-        assert rel_l2(K, o.gram(workloads.to_oracle_input(G))) <= 3e-7
-        agg.close()
+    """N <= 8 keeps the Gram kernel (K stays available)."""
+    N, d = 8, 100_000
+    G = randG(N, d, seed=2)
+    agg = pkg.AdaCons(N, d)
+    agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, 1)
+    both(pkg, G, agg, o.OracleState(N))
+    K = pkg.adacons_read_gram(agg._st, N, None)
+    assert rel_l2(K, o.gram(workloads.to_oracle_input(G))) <= 3e-7
+    agg.close()
 
 
 def test_statistics_only_degenerate_rows(pkg):
