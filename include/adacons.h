@@ -40,7 +40,10 @@
 extern "C" {
 #endif
 
-#define ADACONS_N_MAX 64 /* largest supported worker count */
+#define ADACONS_N_MAX 128     /* largest supported worker count (the largest N in the paper: Appendix A, linear regression) */
+#define ADACONS_GRAM_N_MAX 64 /* largest N for which stage A1 forms the whole matrix K; above it stage A1
+                                 computes what Eq. 7 consumes, diag K and the row sums of K (the norm and the
+                                 dot product with the summed gradient of Alg. 1), and K is not available */
 
 typedef struct adacons_state adacons_state; /* opaque, library-owned */
 
@@ -149,13 +152,14 @@ adacons_status adacons_coeffs(const adacons_state *st, double *gamma_host, doubl
 /*
  * Stage A1 alone: K = G G^T (Eq. 7 third line / the double sum of Eq. 8) into the state's
  * K buffer, without touching the coefficient state.  Same argument rules as
- * adacons_aggregate.  Asynchronous.
+ * adacons_aggregate.  Asynchronous.  ADACONS_EUNSUPPORTED for N > ADACONS_GRAM_N_MAX.
  */
 adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype,
                             adacons_state *st, void *hip_stream);
 
 /* Copy the state's K (N x N doubles, row-major, symmetric) to the host; synchronises the stream.
- * ADACONS_EINVAL when the last call on this state did not produce K (ADACONS_TUNE_STATS_ONLY). */
+ * ADACONS_EINVAL when the last call on this state did not produce K (ADACONS_TUNE_STATS_ONLY, or
+ * N > ADACONS_GRAM_N_MAX). */
 adacons_status adacons_read_gram(const adacons_state *st, double *K_host, void *hip_stream);
 
 /*
@@ -278,13 +282,13 @@ typedef struct adacons_layers adacons_layers; /* opaque, library-owned */
  * Build the per-layer state (L zero-initialised momentum vectors, tile tables, workspaces) on the
  * current device.  Allocates; synchronises `hip_stream` once.
  *   ls            out: receives the handle
- *   N             workers, 1 <= N <= ADACONS_N_MAX
+ *   N             workers, 1 <= N <= ADACONS_GRAM_N_MAX
  *   L             number of layers, >= 1
  *   offsets_host  host pointer, L + 1 ascending column offsets, offsets[0] = 0, offsets[L] = d;
  *                 empty layers (equal consecutive offsets) are not allowed
  *   dtype         element type later calls will pass (fixes the tile geometry)
  *   beta, flags   as in adacons_init_state
- * Errors: EINVAL, EUNSUPPORTED (N > ADACONS_N_MAX, unknown dtype), ENOMEM, EHIP.
+ * Errors: EINVAL, EUNSUPPORTED (N > ADACONS_GRAM_N_MAX, unknown dtype), ENOMEM, EHIP.
  */
 adacons_status adacons_init_layers(adacons_layers **ls, int N, int L, const int64_t *offsets_host,
                                    adacons_dtype dtype, double beta, unsigned flags, void *hip_stream);

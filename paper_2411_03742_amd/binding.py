@@ -15,7 +15,8 @@ import torch
 
 from . import build as _build
 
-ADACONS_N_MAX = 64
+ADACONS_N_MAX = 128
+ADACONS_GRAM_N_MAX = 64
 ADACONS_F32, ADACONS_BF16 = 0, 1
 ADACONS_OK = 0
 ADACONS_FLAG_MOMENTUM, ADACONS_FLAG_NORMALIZE, ADACONS_FLAG_DEFAULT = 1, 2, 3

@@ -111,7 +111,7 @@ GramTail tail_of(adacons_state *st, int mode) {
 hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                              hipStream_t s, hipEvent_t between) {
     const LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
-    if (st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8) {
+    if ((st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8) || N > ADACONS_GRAM_N_MAX) {
         st->k_valid = false;
         const GramTail t = tail_of(st, kGramFinishCoeffs);
         return launch_stats(G, N, d, dtype, vec_ok, shape, st->partials, st->ds, t.cp, s, between);
@@ -178,12 +178,15 @@ adacons_status adacons_init_state(adacons_state **out_st, int N, int64_t d_max, 
     st->max_rows = gram_rows_needed(N, st->num_cu);
     for (int k = 0; k < ADACONS_TUNE_COUNT_; ++k) st->tune[k] = kTuneDefault[k];
     st->prof_capacity = 0;
-    st->k_valid = true;   // zeroed at creation
+    st->k_valid = N <= ADACONS_GRAM_N_MAX;   // zeroed at creation; never produced for larger N
     st->prof_calls = 0;
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&st->ds), sizeof(DevState));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->partials), (size_t)st->max_rows * (num_pairs(N) < 3 ? 3 : num_pairs(N)) * sizeof(double));
+    // a partial row: N (N + 1) / 2 sums of products, or q and r per worker (2 N) where K is not formed;
+    // at least the 3 sums of the one-worker statistics
+    const size_t row_doubles = N > ADACONS_GRAM_N_MAX ? 2 * (size_t)N : (size_t)(num_pairs(N) < 3 ? 3 : num_pairs(N));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->partials), (size_t)st->max_rows * row_doubles * sizeof(double));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->K), ((size_t)N * N + 2 * (size_t)N) * sizeof(double));
     if (e == hipSuccess) e = launch_clear_state(st->ds, st->K, N * N, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
@@ -310,6 +313,8 @@ adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype
     bool vec_ok = false;
     adacons_status rc = check_call(G, N, d, dtype, st, nullptr, false, &vec_ok);
     if (rc != ADACONS_OK) return rc;
+    if (N > ADACONS_GRAM_N_MAX)
+        return fail(ADACONS_EUNSUPPORTED, "K is formed for N <= %d only (N=%d)", ADACONS_GRAM_N_MAX, N);
     st->k_valid = true;
     HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
                         tail_of(st, kGramFinishK), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0,
@@ -320,7 +325,7 @@ adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype
 adacons_status adacons_read_gram(const adacons_state *st, double *K_host, void *hip_stream) {
     if (!st) return fail(ADACONS_EINVAL, "state is NULL");
     if (!K_host) return fail(ADACONS_EINVAL, "K_host is NULL");
-    if (!st->k_valid) return fail(ADACONS_EINVAL, "the last call computed the statistics only (ADACONS_TUNE_STATS_ONLY): no K");
+    if (!st->k_valid) return fail(ADACONS_EINVAL, "the last call computed the statistics only (ADACONS_TUNE_STATS_ONLY or N > ADACONS_GRAM_N_MAX): no K");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     HIP_TRY(hipMemcpyAsync(K_host, st->K, (size_t)st->N * st->N * sizeof(double), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));

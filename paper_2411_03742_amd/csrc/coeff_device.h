@@ -7,7 +7,7 @@
 
 namespace adacons {
 
-// Stage A2.  One workgroup (at least kNMax threads); thread i < N is worker i.  fp64 throughout.
+// Stage A2.  One workgroup (at least N threads, lds of 3 N doubles); thread i < N is worker i.  fp64 throughout.
 //   q_i = K_ii, r_i = sum_j K_ij                      (||g_i||^2 and N <g_i, gbar>)
 //   a_i = r_i / (N sqrt(q_i))                          Eq. 7, positive for a descent direction
 //   rank_i = #{j : a_j < a_i or (a_j = a_i and j < i)} ascending, ties to the lower index
@@ -25,10 +25,10 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
                                                       double *lds, double m_old) {
     const int N = cp.N;
     const int tid = threadIdx.x;
-    double *m_sh = lds + 2 * kNMax;  // [kNMax]
+    double *m_sh = lds + 2 * N;  // [N]
     if (tid < N) m_sh[tid] = m_old;
-    double *a_sh = lds;          // [kNMax]
-    double *c_sh = lds + kNMax;  // [kNMax]
+    double *a_sh = lds;          // [N]
+    double *c_sh = lds + N;      // [N]
     __shared__ int s_bad, s_zero;
     __shared__ double s_sum, s_abs;
     if (tid == 0) {

@@ -113,7 +113,7 @@ finish_kernel(const double *partials, int nrows, double *K, DevState *ds, CoeffP
 }
 
 __global__ void __launch_bounds__(kBlock) coeff_kernel(const double *K, DevState *ds, CoeffParams cp) {
-    __shared__ double lds[kBlock];
+    __shared__ double lds[3 * kNMax];
     const double m_old = ((int)threadIdx.x < cp.N) ? ds->m[threadIdx.x] : 0.0;
     update_coefficients(K, ds, cp, lds, m_old);
 }

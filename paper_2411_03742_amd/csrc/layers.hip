@@ -536,7 +536,7 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     *out_ls = nullptr;
     if (!offsets_host) return lfail(ADACONS_EINVAL, "offsets_host is NULL");
     if (N < 1 || L < 1) return lfail(ADACONS_EINVAL, "N < 1 or L < 1");
-    if (N > kNMax) return lfail(ADACONS_EUNSUPPORTED, "N > ADACONS_N_MAX");
+    if (N > ADACONS_GRAM_N_MAX) return lfail(ADACONS_EUNSUPPORTED, "layer-wise aggregation takes N <= 64");
     if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return lfail(ADACONS_EUNSUPPORTED, "unknown dtype");
     if (!(beta >= 0.0 && beta < 1.0)) return lfail(ADACONS_EINVAL, "beta outside [0, 1)");
     if (flags & ~ADACONS_FLAG_ALL_) return lfail(ADACONS_EINVAL, "unknown flag bits");

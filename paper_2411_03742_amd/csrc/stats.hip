@@ -6,8 +6,9 @@
 //
 // A wavefront takes a chunk of 16 * VECW columns of all N rows with 128-bit loads that cover four
 // rows by 256 contiguous bytes each (lane l: row 4 j + l / 16 in load j, column group l % 16), so
-// the chunk lives in the registers of the wavefront and is read from memory once:
-//   s   = column sums over the rows: in-lane over the loads, then across the four lane groups;
+// the chunk lives in the registers of the wavefront and is read from memory once (N > 64: eight rows
+// by 128 bytes per load and chunks of 8 * VECW columns, which keeps the register count of N <= 64):
+//   s   = column sums over the rows: in-lane over the loads, then across the lane groups;
 //   q_i += <v_i, v_i>, r_i += <v_i, s> per lane for each of its rows, all in fp64.
 // The next chunk is in flight while the current one is summed.  At the end the sixteen lanes of a
 // group are added in a fixed butterfly order, the four wavefronts in index order: one partial row
@@ -23,25 +24,30 @@ namespace adacons {
 
 namespace {
 
-// NT = ceil(N / 16): the kernel is compiled for 16, 32, 48 and 64 rows (4 NT loads per chunk).
+// NT = ceil(N / 16): the kernel is compiled for 16, 32, ..., 128 rows.  One load instruction covers
+// kRowsPerLoad rows (4 up to 64 rows, 8 above), so a chunk takes kLoads = 16 NT / kRowsPerLoad loads.
 // A wavefront takes kSuper consecutive chunks at a time so that about sixteen loads are in flight
 // per buffer for every NT.
 // (bf16 needs twice the arithmetic per byte and is bound by the fp64 units: fewer chunks in flight
 // keep its register count at two wavefronts per SIMD).
 template <int NT, typename T> struct StatsShape {
-    static constexpr int kSuper = (sizeof(T) == 4) ? (NT == 1 ? 4 : (NT == 2 ? 2 : 1)) : (NT == 1 ? 2 : 1);
+    static constexpr int kRowsPerLoad = (NT > 4) ? 8 : 4;
+    static constexpr int kLanesPerRow = kWave / kRowsPerLoad;   // lanes (column groups) side by side in one row
+    static constexpr int kLoads = 16 * NT / kRowsPerLoad;
+    static constexpr int kSuper = (sizeof(T) == 4) ? (kLoads <= 4 ? 4 : (kLoads <= 8 ? 2 : 1)) : (kLoads <= 4 ? 2 : 1);
 };
 
 template <int NT, typename T>
-__global__ void __launch_bounds__(kBlock, (NT * VecWidth<T>::value >= 16) ? 1 : 2)
+__global__ void __launch_bounds__(kBlock, (StatsShape<NT, T>::kLoads * VecWidth<T>::value > 48) ? 1 : 2)
 stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks, int64_t cached_chunks,
                   double *__restrict__ partials) {
     constexpr int VECW = VecWidth<T>::value;
-    constexpr int kLoads = 4 * NT;
+    constexpr int kLoads = StatsShape<NT, T>::kLoads;
     constexpr int kSuper = StatsShape<NT, T>::kSuper;
-    constexpr int64_t kChunk = 16 * VECW;
+    constexpr int RPL = StatsShape<NT, T>::kRowsPerLoad, LPR = StatsShape<NT, T>::kLanesPerRow;
+    constexpr int64_t kChunk = LPR * VECW;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, cl = lane & 15;
+    const int grp = lane / LPR, cl = lane % LPR;   // load j: row RPL j + grp, column group cl of the chunk
 
     double qacc[kLoads], racc[kLoads];
 #pragma unroll
@@ -54,7 +60,7 @@ stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int6
         for (int u = 0; u < kSuper; ++u)
 #pragma unroll
             for (int j = 0; j < kLoads; ++j) {
-                const int row = 4 * j + grp;
+                const int row = RPL * j + grp;
                 const int64_t col = (ch * kSuper + u) * kChunk + (int64_t)cl * VECW;
                 const bool live = row < N && col < dcols;
                 const int rowc = row < N ? row : N - 1;
@@ -81,8 +87,8 @@ stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int6
         }
 #pragma unroll
         for (int c = 0; c < VECW; ++c) {
-            s[c] += __shfl_xor(s[c], 16, 64);
-            s[c] += __shfl_xor(s[c], 32, 64);
+#pragma unroll
+            for (int off = LPR; off < kWave; off <<= 1) s[c] += __shfl_xor(s[c], off, 64);
         }
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
@@ -132,13 +138,13 @@ stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int6
     for (int j = 0; j < kLoads; ++j) {
         double q = qacc[j], r = racc[j];
 #pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) {
+        for (int off = LPR / 2; off >= 1; off >>= 1) {
             q += __shfl_xor(q, off, 64);
             r += __shfl_xor(r, off, 64);
         }
         if (cl == 0) {
-            lds[wave][4 * j + grp] = q;
-            lds[wave][kNMax + 4 * j + grp] = r;
+            lds[wave][RPL * j + grp] = q;
+            lds[wave][kNMax + RPL * j + grp] = r;
         }
     }
     __syncthreads();
@@ -177,7 +183,7 @@ stats_finish_kernel(const double *partials, int nrows, DevState *ds, CoeffParams
 
 // The last d - col0 < 8 columns, which no whole 128-bit group covers: one more partial row.
 template <typename T>
-__global__ void __launch_bounds__(kWave)
+__global__ void __launch_bounds__(kNMax)
 stats_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, double *__restrict__ row_out) {
     const int i = threadIdx.x;
     if (i >= N) return;
@@ -208,7 +214,7 @@ hipError_t run_stats(const void *G, int N, int64_t d, int64_t dcols, const Launc
             nb = 1;
         return nb;
     }();
-    const int64_t chunk = 16 * VecWidth<T>::value * StatsShape<NT, T>::kSuper;   // columns a wavefront takes at a time
+    const int64_t chunk = StatsShape<NT, T>::kLanesPerRow * VecWidth<T>::value * StatsShape<NT, T>::kSuper;   // columns a wavefront takes at a time
     const int64_t nchunks = (dcols + chunk - 1) / chunk;
     const int waves = kBlock / kWave;
     int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 2;
@@ -240,6 +246,10 @@ hipError_t dispatch_stats(const void *G, int N, int64_t d, int64_t dcols, const 
         case 2: return run_stats<2, T>(G, N, d, dcols, shape, partials, s, grid_out);
         case 3: return run_stats<3, T>(G, N, d, dcols, shape, partials, s, grid_out);
         case 4: return run_stats<4, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 5: return run_stats<5, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 6: return run_stats<6, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 7: return run_stats<7, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 8: return run_stats<8, T>(G, N, d, dcols, shape, partials, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
@@ -264,10 +274,10 @@ hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bo
     if (e == hipSuccess && dcols < d) {
         double *row = partials + (size_t)grid * (2 * N);
         if (dtype == ADACONS_F32)
-            hipLaunchKernelGGL(stats_edge_kernel<float>, dim3(1), dim3(kWave), 0, stream, static_cast<const float *>(G),
+            hipLaunchKernelGGL(stats_edge_kernel<float>, dim3(1), dim3(kNMax), 0, stream, static_cast<const float *>(G),
                                N, d, dcols, row);
         else
-            hipLaunchKernelGGL(stats_edge_kernel<bf16_bits>, dim3(1), dim3(kWave), 0, stream,
+            hipLaunchKernelGGL(stats_edge_kernel<bf16_bits>, dim3(1), dim3(kNMax), 0, stream,
                                static_cast<const bf16_bits *>(G), N, d, dcols, row);
         e = hipGetLastError();
         grid += 1;

@@ -70,7 +70,7 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
     }
-#pragma clang loop unroll_count(NCT > 0 ? (kNMax / kRowsInFlight) : 1)
+#pragma clang loop unroll_count(NCT > 0 ? (NCT + kRowsInFlight - 1) / kRowsInFlight : 1)
     for (int i0 = 0; i0 < N; i0 += kRowsInFlight) {
         float v[UNR][kRowsInFlight][VEC];
 #pragma unroll

@@ -53,7 +53,7 @@ def test_argument_validation_needs_no_gpu(lib):
     EINVAL, EUNSUPPORTED = 1, 2
     assert cdll.adacons_init_state(None, 4, 10, 0.9, 3, None) == EINVAL
     assert cdll.adacons_init_state(ctypes.byref(st), 0, 10, 0.9, 3, None) == EINVAL
-    assert cdll.adacons_init_state(ctypes.byref(st), 65, 10, 0.9, 3, None) == EUNSUPPORTED
+    assert cdll.adacons_init_state(ctypes.byref(st), 129, 10, 0.9, 3, None) == EUNSUPPORTED
     assert b"ADACONS_N_MAX" in cdll.adacons_last_error()
     assert cdll.adacons_init_state(ctypes.byref(st), 4, 0, 0.9, 3, None) == EINVAL
     assert cdll.adacons_init_state(ctypes.byref(st), 4, 10, 1.0, 3, None) == EINVAL

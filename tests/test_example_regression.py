@@ -24,7 +24,7 @@ def _demo():
     return mod
 
 
-@pytest.mark.parametrize("N,B", [(8, 32), (32, 64), (64, 16)])
+@pytest.mark.parametrize("N,B", [(8, 32), (32, 64), (64, 16), (128, 2), (128, 128)])
 def test_regression_loop_matches_oracle_at_every_step(N, B):
     if not torch.cuda.is_available():
         pytest.fail("needs the GPU")

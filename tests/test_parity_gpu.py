@@ -526,6 +526,81 @@ def test_statistics_only_degenerate_rows(pkg):
     agg.close()
 
 
+# ------------------------------------------------------------------ more than 64 workers ----
+@pytest.mark.parametrize("N,d", [(65, 1_000), (65, 40_003), (80, 20_000), (96, 65_536 + 24), (97, 10_001), (112, 30_000),
+                                 (127, 9_999), (128, 131_072 + 8), (128, 5), (128, 1), (128, 4_000_004)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_more_than_64_workers(pkg, N, d, dtype):
+    """64 < N <= 128 (the paper's linear-regression runs go up to 128 workers): stage A1 is the
+    statistics pass (norms and dot products with the summed gradient, Alg. 1 steps 1-2), K is not
+    formed; coefficients, momentum state and output over three steps against the oracle."""
+    agg = pkg.AdaCons(N, d, beta=0.9)
+    ost = o.OracleState(N, beta=0.9)
+    for t in range(3):
+        G = randG(N, d, dtype=dtype, sigma=2.0, seed=77 * N + t)
+        both(pkg, G, agg, ost)
+    with pytest.raises(pkg.AdaConsError) as e:
+        pkg.adacons_read_gram(agg._st, N, None)
+    assert e.value.status == 1        # ADACONS_EINVAL
+    with pytest.raises(pkg.AdaConsError) as e:
+        agg.gram(G)
+    assert e.value.status == 2        # ADACONS_EUNSUPPORTED
+    m, step = agg.export_state()
+    assert step == 3 and np.allclose(m, ost.m, rtol=1e-6, atol=0)
+    # stage A3 alone with given weights, and the fused descent step
+    gamma = np.linspace(-0.5, 1.5, N)
+    out = agg.weighted_sum(G, gamma)
+    ref = o.weighted_sum(workloads.to_oracle_input(G), gamma.astype(np.float32).astype(np.float64))
+    assert rel_l2(out.cpu().numpy(), ref) <= 1e-5
+    w = torch.randn(d, device=DEV)
+    w0 = w.clone()
+    agg.aggregate_apply(G, w, lr=0.5)
+    oout, oinfo = o.aggregate(workloads.to_oracle_input(G), ost)
+    if rank_gap_is_safe(oinfo["raw"]):
+        assert rel_l2(w.cpu().numpy(), w0.cpu().numpy().astype(np.float64) - 0.5 * oout) <= 1e-5
+    agg.close()
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3, 7, 11, 15])
+def test_more_than_64_workers_ablation_flags(pkg, flags):
+    N, d = 100, 20_000
+    agg = pkg.AdaCons(N, d, beta=0.9, flags=flags)
+    ost = o.OracleState(N, beta=0.9, flags=flags)
+    for t in range(3):
+        G = randG(N, d, sigma=2.0, seed=300 + t)
+        if flags & 4:
+            G = G[torch.roll(torch.arange(N), t).to(DEV)].contiguous()
+        both(pkg, G, agg, ost)
+    m, _ = agg.export_state()
+    assert np.allclose(m, ost.m, rtol=1e-6, atol=1e-12)
+    agg.close()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_more_than_64_workers_degenerate_inputs(pkg, dtype):
+    N, d = 128, 30_000
+    agg = pkg.AdaCons(N, d, beta=0.5)
+    ost = o.OracleState(N, beta=0.5)
+    G = randG(N, d, dtype=dtype, sigma=2.0, seed=9)
+    both(pkg, G, agg, ost)
+    Gz = G.clone(); Gz[N - 1] = 0; Gz[70] = 0; Gz[100] = Gz[99]
+    _, info, _ = both(pkg, Gz, agg, ost)
+    assert info["numeric_flags"] & pkg.ADACONS_NUM_ZERO_NORM and info["gamma"][70] == 0.0 and info["gamma"][N - 1] == 0.0
+    m_before, _ = agg.export_state()
+    for bad in (float("inf"), float("nan")):
+        Gn = G.clone(); Gn[90, 12_345] = bad
+        agg.aggregate(Gn)
+        info = agg.coeffs()
+        _, oinfo = o.aggregate(workloads.to_oracle_input(Gn), ost, want_out=False)
+        assert info["numeric_flags"] == oinfo["numeric_flags"] == (pkg.ADACONS_NUM_NONFINITE | pkg.ADACONS_NUM_UNIFORM_FALLBACK)
+        assert np.allclose(info["gamma"], 1.0 / N)
+    m_after, step = agg.export_state()
+    assert np.array_equal(m_before, m_after) and step == 4 == ost.t
+    _, info, _ = both(pkg, torch.zeros(N, d, device=DEV, dtype=dtype), agg, ost)
+    assert info["numeric_flags"] & pkg.ADACONS_NUM_UNIFORM_FALLBACK
+    agg.close()
+
+
 # ------------------------------------------------------------------------- graph capture ----
 def test_aggregate_can_be_captured_in_a_hip_graph(pkg):
     """adacons_aggregate enqueues kernels only (no allocation, no synchronisation, no memset

@@ -97,7 +97,8 @@ def test_worker_stats_unaligned(pkg):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("N,d,dtype", [(8, 1_000_004, torch.float32), (16, 200_000, torch.float32),
-                                       (5, 77_777, torch.float32), (8, 400_008, torch.bfloat16)])
+                                       (5, 77_777, torch.float32), (8, 400_008, torch.bfloat16),
+                                       (128, 30_000, torch.float32)])
 def test_algorithm_1_on_one_gpu(pkg, N, d, dtype):
     """Every step of Algorithm 1 with the collectives replaced by what they would deliver: the sum of
     the gradients (step 1), the gathered pairs (step 2); then the coefficient update (step 3), the
