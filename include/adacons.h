@@ -242,7 +242,8 @@ adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *c
  */
 
 /*
- *   g, gsum    device pointers, d elements of `dtype` each (may be the same pointer)
+ *   g, gsum    device pointers, d elements of `dtype` each (may be the same pointer), aligned to the
+ *              element size; any d
  *   st         supplies the partial-sum workspace; d <= its d_max
  *   stats_dev  device pointer, 3 doubles, 8-byte aligned: ||g||^2, <g, gsum>, ||gsum||^2
  * Asynchronous, allocates nothing.  Errors: EINVAL, EUNSUPPORTED, EALIGN, EHIP.
@@ -272,7 +273,7 @@ adacons_status adacons_worker_scale(void *g, int64_t d, adacons_dtype dtype, con
  * performs similarly.  Here the d columns are split into L contiguous segments ("layers"); every
  * layer gets its own Gram matrix, its own coefficients and its own Eq. 11 momentum state, i.e. the
  * steps A1-A3 above run independently on G[:, offsets[l] : offsets[l+1]) for every l, in three
- * launches for all layers together.  128-bit path only.  For N <= 8 stage A1 forms every layer's
+ * launches for all layers together.  For N <= 8 stage A1 forms every layer's
  * Gram matrix; for N > 8 it forms what Eq. 7 consumes of it, ||g_i||^2 and <g_i, sum_j g_j> over the
  * layer's columns (Alg. 1 steps 1-2 per layer).
  */
@@ -297,7 +298,8 @@ adacons_status adacons_destroy_layers(adacons_layers *ls);
 /*
  * One layer-wise aggregation: out[k] = sum_i gamma[layer(k)][i] G[i][k].  Asynchronous, allocates
  * nothing.  G, N, d, dtype, out as in adacons_aggregate, with d == offsets[L] and dtype as given at
- * init; G and out must be 16-byte aligned and d * sizeof(elem) a multiple of 16 (else EALIGN).
+ * init; G and out aligned to their element size (else EALIGN): as there, any d and any such alignment
+ * run on the 128-bit kernels.
  */
 adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons_dtype dtype,
                                         adacons_layers *ls, float *out, void *hip_stream);

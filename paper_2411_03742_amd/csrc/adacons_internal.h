@@ -76,12 +76,11 @@ hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bo
 adacons_status set_error(adacons_status s, const char *fmt, ...);
 
 // worker.hip
-hipError_t launch_pair_stats(const void *x, const void *y, int64_t d, adacons_dtype dtype, bool vec_ok, int num_cu,
+hipError_t launch_pair_stats(const void *x, const void *y, int64_t d, adacons_dtype dtype, int num_cu,
                              int max_rows, double *partials, double *stats, hipStream_t s);
 hipError_t launch_coeffs_from_stats(const double *q, const double *r, DevState *ds, const CoeffParams &cp,
                                     hipStream_t s);
-hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, bool vec_ok, int num_cu, const float *gamma,
-                        hipStream_t s);
+hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, int num_cu, const float *gamma, hipStream_t s);
 
 // wsum.hip
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,

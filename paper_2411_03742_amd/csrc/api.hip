@@ -258,8 +258,7 @@ adacons_status adacons_worker_stats(const void *g, const void *gsum, int64_t d, 
     const size_t es = elem_size(dtype);
     const uintptr_t a = reinterpret_cast<uintptr_t>(g), b = reinterpret_cast<uintptr_t>(gsum);
     if (a % es || b % es || reinterpret_cast<uintptr_t>(stats_dev) % 8) return fail(ADACONS_EALIGN, "misaligned pointer");
-    const bool vec_ok = (a % 16 == 0) && (b % 16 == 0) && ((uint64_t)d * es % 16 == 0);
-    HIP_TRY(launch_pair_stats(g, gsum, d, dtype, vec_ok, st->num_cu, st->max_rows, st->partials, stats_dev,
+    HIP_TRY(launch_pair_stats(g, gsum, d, dtype, st->num_cu, st->max_rows, st->partials, stats_dev,
                               static_cast<hipStream_t>(hip_stream)));
     return ADACONS_OK;
 }
@@ -287,8 +286,7 @@ adacons_status adacons_worker_scale(void *g, int64_t d, adacons_dtype dtype, con
     const size_t es = elem_size(dtype);
     const uintptr_t a = reinterpret_cast<uintptr_t>(g);
     if (a % es) return fail(ADACONS_EALIGN, "g not aligned to its element size");
-    const bool vec_ok = (a % 16 == 0) && ((uint64_t)d * es % 16 == 0);
-    HIP_TRY(launch_scale(g, d, dtype, vec_ok, st->num_cu, st->ds->gamma32 + worker, static_cast<hipStream_t>(hip_stream)));
+    HIP_TRY(launch_scale(g, d, dtype, st->num_cu, st->ds->gamma32 + worker, static_cast<hipStream_t>(hip_stream)));
     return ADACONS_OK;
 }
 

@@ -5,7 +5,10 @@
 // Every layer is cut into runs of at most run_groups column groups (one group = one 128-bit load per
 // row); a run never crosses a layer boundary.  Layer boundaries need not be multiples of the group
 // width: the group that straddles two layers belongs to a run of each, and the columns that
-// belong to the other layer are masked (zeroed in A1, not stored in A3).
+// belong to the other layer are masked (zeroed in A1, not stored in A3).  Nor need d be one: the
+// last group of a row then holds fewer than VEC columns of it, and is read VEC columns back from
+// the end of the row instead (the columns it shares with the group before are masked).  All
+// 128-bit accesses are issued from element-aligned addresses.
 //   A1  workgroups take runs from a ticket counter in column order (so that at any time all
 //       workgroups read one compact window of every row, and long and short runs balance out).
 //       Inside a run the N(N+1)/2 fp64 sums stay in registers; one partial row is written per
@@ -63,12 +66,14 @@ template <int N, typename T, int VEC, bool EDGE, bool STREAM>
 __device__ __forceinline__ void gram_layers_step(const T *__restrict__ G, int64_t d, int64_t g, int64_t cb, int64_t ce,
                                                  double (&acc)[N * (N + 1) / 2]) {
     const int64_t c0 = g * VEC;
+    // a group that reaches past the end of the row (d not a multiple of VEC) is read from d - VEC
+    const int64_t lb = (EDGE && c0 + VEC > d) ? d - VEC : c0;
     float v[N][VEC];
 #pragma unroll
-    for (int i = 0; i < N; ++i) load_vec<T, VEC, STREAM>(G + (int64_t)i * d + c0, v[i]);
+    for (int i = 0; i < N; ++i) load_vec<T, VEC, STREAM>(G + (int64_t)i * d + lb, v[i]);
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
-        const bool live = !EDGE || (c0 + c >= cb && c0 + c < ce);
+        const bool live = !EDGE || (lb + c >= c0 && lb + c >= cb && lb + c < ce);
         double x[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) x[i] = live ? (double)v[i][c] : 0.0;
@@ -175,16 +180,19 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
             const bool in_run = kInterior || g < g_end;
             const int64_t gc = in_run ? g : g_end - 1;          // clamped: always a group of this run
             const int64_t c0 = gc * VECW;
+            // a group that reaches past the end of the row (d not a multiple of VECW) is read from d - VECW
+            const int64_t lb = (!kInterior && c0 + VECW > d) ? d - VECW : c0;
             u32x4 x[kLoads];
 #pragma unroll
             for (int j = 0; j < kLoads; ++j) {
                 const int row = 4 * j + grp;
                 const int rowc = (kInterior || row < N) ? row : N - 1;
-                x[j] = *reinterpret_cast<const u32x4 *>(G + (int64_t)rowc * d + c0);
+                x[j] = *reinterpret_cast<const gu32x4 *>(G + (int64_t)rowc * d + lb);
             }
             bool live[VECW];
 #pragma unroll
-            for (int k = 0; k < VECW; ++k) live[k] = kInterior || (in_run && c0 + k >= run.cb && c0 + k < run.ce);
+            for (int k = 0; k < VECW; ++k)
+                live[k] = kInterior || (in_run && lb + k >= c0 && lb + k >= run.cb && lb + k < run.ce);
             double ssum[VECW];
 #pragma unroll
             for (int k = 0; k < VECW; ++k) ssum[k] = 0.0;
@@ -348,16 +356,17 @@ wsum_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
 #pragma unroll
                 for (int c = 0; c < VEC; c += 4) {
                     const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
-                    __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(dst + c));
+                    __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(dst + c));
                 }
             }
             continue;
         }
         for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
             const int64_t c0 = (run.g0 + k) * VEC;
+            const int64_t lb = (c0 + VEC > d) ? d - VEC : c0;   // the group at the ragged end of a row
             float v[N][VEC];
 #pragma unroll
-            for (int i = 0; i < N; ++i) load_vec<T, VEC, true>(G + (int64_t)i * d + c0, v[i]);
+            for (int i = 0; i < N; ++i) load_vec<T, VEC, true>(G + (int64_t)i * d + lb, v[i]);
             float acc[VEC];
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
@@ -369,13 +378,14 @@ wsum_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
 #pragma unroll
                 for (int c = 0; c < VEC; c += 4) {
                     const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
-                    __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + c0 + c));
+                    __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(out + c0 + c));
                 }
             } else {
-                // group shared with a neighbouring layer: store only this layer's columns
+                // group shared with a neighbouring layer, or at the ragged end of a row: store only
+                // this group's columns of this layer
 #pragma unroll
                 for (int c = 0; c < VEC; ++c)
-                    if (c0 + c >= cb && c0 + c < ce) out[c0 + c] = acc[c];
+                    if (lb + c >= c0 && lb + c >= cb && lb + c < ce) out[lb + c] = acc[c];
             }
         }
     }
@@ -401,6 +411,7 @@ wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun 
         const int64_t cb = run.cb, ce = run.ce;
         for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
             const int64_t c0 = (run.g0 + k) * VEC;
+            const int64_t lb = (c0 + VEC > d) ? d - VEC : c0;   // the group at the ragged end of a row
             float acc[VEC];
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
@@ -408,7 +419,7 @@ wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun 
                 float v[8][VEC];
 #pragma unroll
                 for (int ii = 0; ii < 8; ++ii)
-                    if (i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + c0, v[ii]);
+                    if (i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + lb, v[ii]);
 #pragma unroll
                 for (int ii = 0; ii < 8; ++ii)
                     if (i0 + ii < N) {
@@ -421,12 +432,12 @@ wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun 
 #pragma unroll
                 for (int c = 0; c < VEC; c += 4) {
                     const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
-                    __builtin_nontemporal_store(x, reinterpret_cast<f32x4 *>(out + c0 + c));
+                    __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(out + c0 + c));
                 }
             } else {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c)
-                    if (c0 + c >= cb && c0 + c < ce) out[c0 + c] = acc[c];
+                    if (lb + c >= c0 && lb + c >= cb && lb + c < ce) out[lb + c] = acc[c];
             }
         }
     }
@@ -544,6 +555,8 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     for (int l = 0; l < L; ++l)
         if (offsets_host[l + 1] <= offsets_host[l]) return lfail(ADACONS_EINVAL, "offsets must ascend strictly");
     if (L > (1 << 20)) return lfail(ADACONS_EINVAL, "too many layers");
+    if (offsets_host[L] < (dtype == ADACONS_BF16 ? 8 : 4))
+        return lfail(ADACONS_EINVAL, "layer-wise aggregation needs d >= one 128-bit group (4 fp32 / 8 bf16 elements)");
 
     int dev = 0;
     hipDeviceProp_t prop;
@@ -630,7 +643,7 @@ adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons
     if (hipGetDevice(&dev) != hipSuccess || dev != ls->device) return lfail(ADACONS_EINVAL, "the layer state lives on another device");
     const size_t es = dtype == ADACONS_BF16 ? 2 : 4;
     const uintptr_t g0 = reinterpret_cast<uintptr_t>(G), o0 = reinterpret_cast<uintptr_t>(out);
-    if (g0 % 16 || o0 % 16 || ((uint64_t)d * es) % 16) return lfail(ADACONS_EALIGN, "layer-wise path needs 16-byte alignment");
+    if (g0 % es || o0 % 4) return lfail(ADACONS_EALIGN, "G or out not aligned to its element size");
     const uintptr_t g1 = g0 + (uint64_t)N * (uint64_t)d * es, o1 = o0 + (uint64_t)d * 4;
     if (o0 < g1 && g0 < o1) return lfail(ADACONS_EINVAL, "out overlaps G");
     CoeffParams cp;

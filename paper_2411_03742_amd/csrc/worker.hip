@@ -16,9 +16,21 @@ constexpr int kPairUnroll = 4;   // column groups per thread and sweep: 8 loads 
 
 template <typename T, int VEC>
 __global__ void __launch_bounds__(kBlock)
-pair_stats_kernel(const T *__restrict__ x, const T *__restrict__ y, int64_t ngroups, double *__restrict__ partials) {
+pair_stats_kernel(const T *__restrict__ x, const T *__restrict__ y, int64_t d, double *__restrict__ partials) {
     __shared__ double lds[4 * 3];
     double acc[3] = {0.0, 0.0, 0.0};   // sum x^2, sum x y, sum y^2
+    // whole 128-bit groups (element-aligned addresses are enough); the d mod VEC elements left over
+    // are taken one each by the first threads of workgroup 0
+    const int64_t ngroups = d / VEC;
+    if (blockIdx.x == 0 && ngroups * VEC + threadIdx.x < d) {
+        float a[1], b[1];
+        load_vec<T, 1, false>(x + ngroups * VEC + threadIdx.x, a);
+        load_vec<T, 1, false>(y + ngroups * VEC + threadIdx.x, b);
+        const double xa = (double)a[0], yb = (double)b[0];
+        acc[0] = xa * xa;
+        acc[1] = xa * yb;
+        acc[2] = yb * yb;
+    }
     const int64_t stride = (int64_t)gridDim.x * kBlock * kPairUnroll;
     for (int64_t g0 = (int64_t)blockIdx.x * kBlock * kPairUnroll + threadIdx.x; g0 < ngroups; g0 += stride) {
         float a[kPairUnroll][VEC], b[kPairUnroll][VEC];
@@ -98,32 +110,34 @@ __device__ __forceinline__ unsigned bf16_round_bits(float f) {   // round to nea
 }
 
 template <typename T, int VEC>
-__global__ void __launch_bounds__(kBlock) scale_kernel(T *__restrict__ g, int64_t ngroups, const float *__restrict__ gamma) {
+__global__ void __launch_bounds__(kBlock) scale_kernel(T *__restrict__ g, int64_t d, const float *__restrict__ gamma) {
     const float w = gamma[0];
     const int64_t stride = (int64_t)gridDim.x * kBlock;
+    // whole 128-bit groups from element-aligned addresses; the first threads of workgroup 0 take the
+    // d mod VEC elements left over
+    const int64_t ngroups = d / VEC;
+    if (blockIdx.x == 0 && ngroups * VEC + threadIdx.x < d) {
+        T *p = g + ngroups * VEC + threadIdx.x;
+        float v[1];
+        load_vec<T, 1, false>(p, v);
+        if constexpr (sizeof(T) == 4) *p = v[0] * w;
+        else *p = (bf16_bits)bf16_round_bits(v[0] * w);
+    }
     for (int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x; k < ngroups; k += stride) {
         float v[VEC];
         load_vec<T, VEC, false>(g + k * VEC, v);
 #pragma unroll
         for (int c = 0; c < VEC; ++c) v[c] *= w;
         if constexpr (sizeof(T) == 4) {
-            if constexpr (VEC == 4) {
-                const f32x4 x = {v[0], v[1], v[2], v[3]};
-                *reinterpret_cast<f32x4 *>(g + k * VEC) = x;
-            } else {
-                g[k] = v[0];
-            }
+            const f32x4 x = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<gf32x4 *>(g + k * VEC) = x;
         } else {
-            if constexpr (VEC == 8) {
-                u32x4 x;
-                x.x = bf16_round_bits(v[0]) | (bf16_round_bits(v[1]) << 16);
-                x.y = bf16_round_bits(v[2]) | (bf16_round_bits(v[3]) << 16);
-                x.z = bf16_round_bits(v[4]) | (bf16_round_bits(v[5]) << 16);
-                x.w = bf16_round_bits(v[6]) | (bf16_round_bits(v[7]) << 16);
-                *reinterpret_cast<u32x4 *>(g + k * VEC) = x;
-            } else {
-                g[k] = (bf16_bits)bf16_round_bits(v[0]);
-            }
+            u32x4 x;
+            x.x = bf16_round_bits(v[0]) | (bf16_round_bits(v[1]) << 16);
+            x.y = bf16_round_bits(v[2]) | (bf16_round_bits(v[3]) << 16);
+            x.z = bf16_round_bits(v[4]) | (bf16_round_bits(v[5]) << 16);
+            x.w = bf16_round_bits(v[6]) | (bf16_round_bits(v[7]) << 16);
+            *reinterpret_cast<gu32x4 *>(g + k * VEC) = x;
         }
     }
 }
@@ -131,26 +145,23 @@ __global__ void __launch_bounds__(kBlock) scale_kernel(T *__restrict__ g, int64_
 template <typename T, int VEC>
 static hipError_t run_pair(const void *x, const void *y, int64_t d, int num_cu, int max_rows, double *partials,
                            double *stats, hipStream_t s) {
-    const int64_t ngroups = (d + VEC - 1) / VEC;
+    const int64_t ngroups = d / VEC;
     int64_t grid = (ngroups + (int64_t)kBlock * kPairUnroll - 1) / ((int64_t)kBlock * kPairUnroll);
     if (grid > (int64_t)num_cu * 4) grid = (int64_t)num_cu * 4;
     if (grid > max_rows) grid = max_rows;
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL((pair_stats_kernel<T, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(x), static_cast<const T *>(y), ngroups, partials);
+                       static_cast<const T *>(x), static_cast<const T *>(y), d, partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(pair_finish_kernel, dim3(1), dim3(kBlock), 0, s, partials, (int)grid, stats);
     return hipGetLastError();
 }
 
-hipError_t launch_pair_stats(const void *x, const void *y, int64_t d, adacons_dtype dtype, bool vec_ok, int num_cu,
+hipError_t launch_pair_stats(const void *x, const void *y, int64_t d, adacons_dtype dtype, int num_cu,
                              int max_rows, double *partials, double *stats, hipStream_t s) {
-    if (dtype == ADACONS_F32)
-        return vec_ok ? run_pair<float, 4>(x, y, d, num_cu, max_rows, partials, stats, s)
-                      : run_pair<float, 1>(x, y, d, num_cu, max_rows, partials, stats, s);
-    return vec_ok ? run_pair<bf16_bits, 8>(x, y, d, num_cu, max_rows, partials, stats, s)
-                  : run_pair<bf16_bits, 1>(x, y, d, num_cu, max_rows, partials, stats, s);
+    if (dtype == ADACONS_F32) return run_pair<float, 4>(x, y, d, num_cu, max_rows, partials, stats, s);
+    return run_pair<bf16_bits, 8>(x, y, d, num_cu, max_rows, partials, stats, s);
 }
 
 hipError_t launch_coeffs_from_stats(const double *q, const double *r, DevState *ds, const CoeffParams &cp,
@@ -161,19 +172,17 @@ hipError_t launch_coeffs_from_stats(const double *q, const double *r, DevState *
 
 template <typename T, int VEC>
 static hipError_t run_scale(void *g, int64_t d, int num_cu, const float *gamma, hipStream_t s) {
-    const int64_t ngroups = (d + VEC - 1) / VEC;
-    int64_t grid = (ngroups + kBlock - 1) / kBlock;
+    int64_t grid = (d / VEC + kBlock - 1) / kBlock;
     if (grid > (int64_t)num_cu * 8) grid = (int64_t)num_cu * 8;
-    hipLaunchKernelGGL((scale_kernel<T, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s, static_cast<T *>(g), ngroups,
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL((scale_kernel<T, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s, static_cast<T *>(g), d,
                        gamma);
     return hipGetLastError();
 }
 
-hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, bool vec_ok, int num_cu, const float *gamma,
-                        hipStream_t s) {
-    if (dtype == ADACONS_F32)
-        return vec_ok ? run_scale<float, 4>(g, d, num_cu, gamma, s) : run_scale<float, 1>(g, d, num_cu, gamma, s);
-    return vec_ok ? run_scale<bf16_bits, 8>(g, d, num_cu, gamma, s) : run_scale<bf16_bits, 1>(g, d, num_cu, gamma, s);
+hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, int num_cu, const float *gamma, hipStream_t s) {
+    if (dtype == ADACONS_F32) return run_scale<float, 4>(g, d, num_cu, gamma, s);
+    return run_scale<bf16_bits, 8>(g, d, num_cu, gamma, s);
 }
 
 }  // namespace adacons

@@ -96,10 +96,13 @@ def _check_layers(pkg, G, off, agg, states, out_tol, check_out=True):
     if check_out:
         got = out.cpu().numpy().astype(np.float64)
         assert np.linalg.norm(got - oout) / np.linalg.norm(oout) <= out_tol
-        # every layer on its own as well (a small layer must not hide in the global norm)
+        # every layer on its own as well (a small layer must not hide in the global norm), measured
+        # against sum_i |gamma_i| |g_i|: what the rounding of an fp32 weighted sum is proportional to (a
+        # layer of a few columns can cancel to a result far smaller than its terms)
+        Gabs = G.float().abs().cpu().numpy().astype(np.float64)
         for l in range(len(oinfos)):
             a, b = off[l], off[l + 1]
-            den = np.linalg.norm(oout[a:b])
+            den = np.linalg.norm((np.abs(info["gamma"][l])[:, None] * Gabs[:, a:b]).sum(0))
             if den > 0:
                 assert np.linalg.norm(got[a:b] - oout[a:b]) / den <= out_tol, l
     return out
@@ -124,6 +127,42 @@ def test_random_layouts_match_oracle(pkg, N, d, L, dtype):
         G = (s[None, :] + 2.0 * torch.randn(N, d, generator=g, device=DEV)).to(dtype).contiguous()
         _check_layers(pkg, G, off, agg, states, 1e-5 if dtype == torch.float32 else 2e-3)
     agg.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("N,d,L,shift", [(2, 1001, 3, 0), (4, 40_003, 17, 1), (8, 300_005, 50, 0), (8, 9, 2, 0), (5, 123_457, 200, 3),
+                                         (8, 1027, 1027, 0), (9, 50_001, 11, 1), (16, 400_006, 40, 0), (33, 100_007, 7, 5),
+                                         (64, 300_002, 25, 0), (64, 71, 1, 1), (8, 300_000, 50, 2)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_layouts_off_the_16_byte_grid(pkg, N, d, L, shift, dtype):
+    """d that is not a multiple of the 128-bit group (the last group of every row is ragged), G and out
+    starting `shift` elements past a 16-byte boundary: same parity bar as the aligned layouts."""
+    rng = np.random.default_rng(N * 11 + L)
+    off = _rand_layout(rng, d, L) if L < d else np.arange(d + 1, dtype=np.int64)
+    g = torch.Generator(device=DEV).manual_seed(L + 1)
+    agg = pkg.AdaConsLayers(N, off, dtype=dtype, beta=0.9)
+    states = [o.OracleState(N, beta=0.9) for _ in range(len(off) - 1)]
+    buf = torch.empty(N * d + shift, device=DEV, dtype=dtype)
+    G = buf[shift:].view(N, d)
+    assert G.is_contiguous()
+    for t in range(2):
+        s = torch.randn(d, generator=g, device=DEV)
+        G.copy_((s[None, :] + 2.0 * torch.randn(N, d, generator=g, device=DEV)).to(dtype))
+        _check_layers(pkg, G, off, agg, states, 1e-5 if dtype == torch.float32 else 2e-3)
+    # an output that starts off the 16-byte grid, with guard elements on both sides
+    obuf = torch.full((d + 2,), 7.0, device=DEV)
+    agg2 = pkg.AdaConsLayers(N, off, dtype=dtype, beta=0.9, flags=0)   # no momentum: same input, same output
+    a = agg2.aggregate(G).clone()
+    b = agg2.aggregate(G, out=obuf[1:d + 1])
+    assert torch.equal(a, b) and obuf[0] == 7.0 and obuf[d + 1] == 7.0
+    agg.close(); agg2.close()
+
+
+@pytest.mark.gpu
+def test_layers_need_one_whole_group(pkg):
+    with pytest.raises(pkg.AdaConsError) as e:
+        pkg.AdaConsLayers(4, [0, 2, 3])
+    assert e.value.status == 1
 
 
 @pytest.mark.gpu

@@ -84,14 +84,26 @@ def test_worker_stats_match_oracle(pkg, d, dtype):
 
 
 @pytest.mark.gpu
-def test_worker_stats_unaligned(pkg):
-    d = 50_001
-    buf = torch.randn(2 * d + 2, device=DEV)
-    x, y = buf[1:d + 1], buf[d + 1:2 * d + 1]
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("d", [1, 3, 7, 9, 50_000, 50_001, 50_003, 50_005, 50_007, 262_150])
+@pytest.mark.parametrize("shift", [0, 1])
+def test_worker_stats_and_scale_off_16_byte_boundaries(pkg, d, dtype, shift):
+    """Vectors that start one element past a 16-byte boundary and lengths with every leftover count:
+    the 128-bit kernels run from element-aligned addresses, the leftover elements go to single threads."""
+    buf = torch.randn(2 * d + 2 * shift + 8, device=DEV).to(dtype)
+    x, y = buf[shift:d + shift], buf[d + shift:2 * d + shift]
     agg = pkg.AdaCons(2, d)
     got = agg.worker_stats(x, y).cpu().numpy()
-    ref = np.array(o.worker_stats(x.cpu().numpy(), y.cpu().numpy()))
+    ref = np.array(o.worker_stats(_bits(x), _bits(y)))
     assert np.allclose(got, ref, rtol=1e-12)
+    agg.weighted_sum(torch.stack([x, y]).contiguous(), [0.75, -1.25])      # sets the weights the scale uses
+    before = buf.clone()
+    agg.worker_scale(x, 1)
+    want = (before[shift:d + shift].float() * (-1.25)).to(dtype)
+    assert torch.equal(x.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                       want.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+    # nothing outside the vector was touched
+    assert torch.equal(buf[:shift], before[:shift]) and torch.equal(buf[d + shift:], before[d + shift:])
     agg.close()
 
 
