@@ -313,6 +313,34 @@ def test_orthogonal_equal_norm_gradients_get_uniform_weights():
     assert np.allclose(info["gamma"], 0.25, rtol=1e-14)
 
 
+@pytest.mark.parametrize("N", [65, 100, 128])
+def test_many_workers_keep_the_same_pins(N):
+    """The paper's regression runs use up to 128 workers (Appendix A); nothing in the oracle depends on
+    N, and the library routines, invariants and special cases pin it there as at small N: K against
+    matmul, the output against a matrix-vector product with weights that sum to one, identical
+    gradients (Sec. 3.2), orthogonal equal-norm gradients, and worker permutation with a carried state
+    (Sec. 3.4)."""
+    d = 700
+    G = _randG(N, d, sigma=2.0)
+    K = o.gram(G)
+    assert np.allclose(K, G.astype(np.float64) @ G.astype(np.float64).T, rtol=1e-12, atol=1e-9)
+    st_a, st_b = _state(N, beta=0.9), _state(N, beta=0.9)
+    for t in range(4):
+        G = _randG(N, d, sigma=2.0)
+        perm = RNG.permutation(N)
+        out_a, info_a = o.aggregate(G, st_a)
+        out_b, info_b = o.aggregate(G[perm], st_b)
+        assert abs(info_a["gamma"].sum() - 1.0) <= 1e-12
+        assert np.allclose(out_a, G.astype(np.float64).T @ info_a["gamma"], rtol=1e-11, atol=1e-12)
+        assert np.allclose(info_b["gamma"], info_a["gamma"][perm], rtol=1e-10)
+        assert np.allclose(out_b, out_a, rtol=1e-8, atol=1e-11)
+    g = RNG.standard_normal(d).astype(np.float32)
+    out, info = o.aggregate(np.tile(g, (N, 1)), _state(N))
+    assert np.allclose(info["gamma"], 1.0 / N, rtol=1e-12) and np.allclose(out, g.astype(np.float64), rtol=1e-12)
+    _, info = o.aggregate((2.0 * np.eye(N, N + 3)).astype(np.float32), _state(N), want_out=False)
+    assert np.allclose(info["gamma"], 1.0 / N, rtol=1e-13)
+
+
 def test_single_worker_and_two_worker_closed_form():
     g = RNG.standard_normal((1, 33)).astype(np.float32)
     out, info = o.aggregate(g, _state(1))
