@@ -30,16 +30,16 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 PMC_TRAFFIC_BYTES = {
     ("C1", "gram_kernel (A1)", ()): 16_802_265 + 24_576,
     ("C1", "wsum_kernel (A3)", ()): 16_791_019 + 4_194_304,
-    ("C2", "gram_kernel (A1)", ()): 826_843_043 + 73_728,
-    ("C2", "wsum_kernel (A3)", ()): 857_044_343 + 102_228_128,
-    ("C3", "gram_kernel (A1)", ()): 5_362_251_980 + 147_456,
-    ("C3", "wsum_kernel (A3)", ()): 5_362_184_750 + 1_340_567_605,
-    ("C4", "gram_kernel (A1)", ()): 6_644_466_645 + 4_259_840,
-    ("C4", "wsum_kernel (A3)", ()): 7_019_504_076 + 102_228_128,
-    ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_823_823_468 + 262_144,
-    ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 7_019_207_350 + 102_228_128,
-    ("C5", "gram_kernel (A1)", ()): 7_964_256_303 + 557_057,
-    ("C5", "wsum_kernel (A3)", ()): 7_964_089_907 + 497_759_232,
+    ("C2", "gram_kernel (A1)", ()): 826_937_790 + 73_728,
+    ("C2", "wsum_kernel (A3)", ()): 856_968_730 + 102_228_128,
+    ("C3", "gram_kernel (A1)", ()): 5_362_245_304 + 147_456,
+    ("C3", "wsum_kernel (A3)", ()): 5_362_187_821 + 1_340_567_555,
+    ("C4", "gram_kernel (A1)", ()): 6_654_447_235 + 4_259_840,
+    ("C4", "wsum_kernel (A3)", ()): 6_874_194_215 + 102_234_827,
+    ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_818_827_424 + 262_144,
+    ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 6_865_485_640 + 102_239_502,
+    ("C5", "gram_kernel (A1)", ()): 7_964_268_156 + 557_057,
+    ("C5", "wsum_kernel (A3)", ()): 7_964_114_115 + 497_815_855,
 }
 
 
@@ -63,7 +63,7 @@ def main() -> int:
                          "parameter tensor of a ResNet-50; not the headline metric")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass / cached_head_mb / "
-                         "mfma_direct_loads / stats_only")
+                         "mfma_direct_loads / stats_only / wsum_park_kb")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 "
@@ -95,7 +95,8 @@ def main() -> int:
             "reverse_second_pass": ada.ADACONS_TUNE_REVERSE_SECOND_PASS,
             "cached_head_mb": ada.ADACONS_TUNE_CACHED_HEAD_MB,
             "mfma_direct_loads": ada.ADACONS_TUNE_MFMA_DIRECT_LOADS,
-            "stats_only": ada.ADACONS_TUNE_STATS_ONLY}
+            "stats_only": ada.ADACONS_TUNE_STATS_ONLY,
+            "wsum_park_kb": ada.ADACONS_TUNE_WSUM_PARK_KB}
     tuned = {}
     for kv in args.tune:
         k, v = kv.split("=")

@@ -212,6 +212,12 @@ typedef enum {
                                              produced and adacons_read_gram() reports ADACONS_EINVAL.  Honoured
                                              by adacons_aggregate / adacons_aggregate_apply; for N <= 8 the
                                              Gram kernel runs.  0 (default): full K */
+    ADACONS_TUNE_WSUM_PARK_KB = 7,        /* A3 with parked output: one workgroup per CU keeps whole tiles of output
+                                             in LDS and writes them back to back when the space is used up,
+                                             instead of storing tile by tile among the loads (a steady trickle of
+                                             stores costs long read streams 7-13 %).  0: never; 1 (default): where
+                                             it measured faster (fp32, N >= 12, d >= 2^24), with 128 KB;
+                                             8 .. 144: always, with that many KB of LDS */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);

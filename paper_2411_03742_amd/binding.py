@@ -29,6 +29,7 @@ ADACONS_TUNE_REVERSE_SECOND_PASS = 3
 ADACONS_TUNE_CACHED_HEAD_MB = 4
 ADACONS_TUNE_MFMA_DIRECT_LOADS = 5
 ADACONS_TUNE_STATS_ONLY = 6
+ADACONS_TUNE_WSUM_PARK_KB = 7
 
 EXPORTS = [
     "adacons_init_state", "adacons_destroy_state", "adacons_reset_state", "adacons_aggregate",

@@ -57,6 +57,7 @@ struct LaunchShape {
     int max_rows;       // capacity of the partials workspace in rows
     int cached_head_mb; // stage A1: MiB at the head of G read with cache-allocating loads; < 0: all
     int mfma_direct;    // stage A1, N > 8: value of ADACONS_TUNE_MFMA_DIRECT_LOADS (which matrix-core kernel)
+    int wsum_park_kb;   // stage A3: value of ADACONS_TUNE_WSUM_PARK_KB (LDS for parked output tiles; 0: store tile by tile)
 };
 
 // gram.hip

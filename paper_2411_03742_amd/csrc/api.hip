@@ -52,7 +52,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 4, 0};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 4, 0, 1};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 
@@ -92,6 +92,7 @@ LaunchShape shape_of(const adacons_state *st, adacons_tune_key key) {
     const int head = st->tune[ADACONS_TUNE_CACHED_HEAD_MB];
     s.cached_head_mb = head >= (1 << 20) ? -1 : head;  // a huge value means all of G
     s.mfma_direct = st->tune[ADACONS_TUNE_MFMA_DIRECT_LOADS];
+    s.wsum_park_kb = st->tune[ADACONS_TUNE_WSUM_PARK_KB];
     return s;
 }
 
@@ -377,6 +378,8 @@ adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value) 
     if (value < 0) value = kTuneDefault[key];
     if ((key == ADACONS_TUNE_GRAM_BLOCKS_PER_CU || key == ADACONS_TUNE_WSUM_BLOCKS_PER_CU) && value > 8)
         return fail(ADACONS_EINVAL, "at most 8 workgroups per CU");
+    if (key == ADACONS_TUNE_WSUM_PARK_KB && value != 0 && value != 1 && (value < 8 || value > 144))
+        return fail(ADACONS_EINVAL, "ADACONS_TUNE_WSUM_PARK_KB takes 0, 1 or 8..144");
     st->tune[key] = value;
     return ADACONS_OK;
 }

@@ -13,6 +13,7 @@
 namespace adacons {
 
 constexpr int kRowsInFlight = 8;
+constexpr int kParkBlock = kBlock;   // workgroup size of wsum_parked_kernel (512 measured 3-8 % slower)
 
 // APPLY = false: out[col..] = acc (non-temporal).  APPLY = true: the descent step of Eq. 4 in
 // place, out[col..] = out[col..] - lr * acc (out is then the parameter vector w: read and written
@@ -56,17 +57,19 @@ __device__ __forceinline__ void store_out_wave8(float *__restrict__ out, int64_t
     }
 }
 
-// One tile = kBlock * UNR column groups: thread t owns groups base + u * kBlock, u < UNR.
+// One tile = BLK * UNR column groups (BLK = workgroup size): thread t owns groups base + u * BLK, u < UNR.
 // FULL: every group of the tile exists, so the loads carry no predicate and are all issued
-// before the first use.
-template <int NCT, typename T, int VEC, int UNR, bool FULL, bool APPLY>
+// before the first use.  PARK (FULL tiles only): the sums go to `park`, an image of the tile's
+// BLK * UNR * VEC output columns in LDS, instead of to memory.
+template <int NCT, typename T, int VEC, int UNR, bool FULL, bool APPLY, bool PARK = false, int BLK = kBlock>
 __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, const int64_t d, const int64_t ngroups,
-                                          const int64_t base, const float *gam, float *__restrict__ out, float lr) {
+                                          const int64_t base, const float *gam, float *__restrict__ out, float lr,
+                                          float *park = nullptr) {
     float acc[UNR][VEC];
     bool live[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-        live[u] = FULL || (base + (int64_t)u * kBlock < ngroups);
+        live[u] = FULL || (base + (int64_t)u * BLK < ngroups);
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
     }
@@ -78,7 +81,7 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
 #pragma unroll
             for (int ii = 0; ii < kRowsInFlight; ++ii)
                 if ((NCT > 0 || i0 + ii < N) && (NCT == 0 || i0 + ii < NCT) && live[u])
-                    load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + (base + (int64_t)u * kBlock) * VEC, v[u][ii]);
+                    load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + (base + (int64_t)u * BLK) * VEC, v[u][ii]);
 #pragma unroll
         for (int u = 0; u < UNR; ++u)
 #pragma unroll
@@ -89,14 +92,23 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
                     for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w, v[u][ii][c], acc[u][c]);
                 }
     }
-    if constexpr (FULL && !APPLY && VEC == 8) {
+    if constexpr (PARK) {
+        static_assert(FULL, "only whole tiles are parked");
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int c = 0; c < VEC; c += 4) {
+                const f32x4 x = {acc[u][c], acc[u][c + 1], acc[u][c + 2], acc[u][c + 3]};
+                *reinterpret_cast<f32x4 *>(park + ((size_t)u * BLK + threadIdx.x) * VEC + c) = x;
+            }
+    } else if constexpr (FULL && !APPLY && VEC == 8) {
         const int64_t wave_base = base - (threadIdx.x & (kWave - 1));   // group of lane 0
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) store_out_wave8(out, (wave_base + (int64_t)u * kBlock) * VEC, acc[u]);
+        for (int u = 0; u < UNR; ++u) store_out_wave8(out, (wave_base + (int64_t)u * BLK) * VEC, acc[u]);
     } else {
 #pragma unroll
         for (int u = 0; u < UNR; ++u)
-            if (live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * kBlock) * VEC, acc[u], lr);
+            if (live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * BLK) * VEC, acc[u], lr);
     }
 }
 
@@ -136,6 +148,87 @@ wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const
     }
 }
 
+// The same sums with the output parked in LDS and written in bursts.  Measured on long streams
+// (N = 64, d = 25.6 M: 6.5 GB read per 102 MB written): stores issued tile by tile, a steady trickle
+// among the reads, cost 170 us on top of the 950 us the reads take; one workgroup per CU that parks
+// `cap` whole tiles of output (128 KB) and then writes them back to back costs 20 us.  Every
+// workgroup takes the same tiles as in wsum_kernel; a partial last tile is stored directly.
+template <int NCT, typename T, int VEC, int UNR, bool APPLY, int BLK>
+__global__ void __launch_bounds__(BLK)
+wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
+                   float *__restrict__ out, int reverse, float lr, int cap) {
+    extern __shared__ __attribute__((aligned(16))) float park[];   // cap tiles of kTileCols floats
+    const int N = (NCT > 0) ? NCT : n_rt;
+    __shared__ float gam_lds[kNMax];
+    float gam_reg[NCT > 0 ? NCT : 1];
+    const float *gam;
+    if constexpr (NCT > 0) {
+#pragma unroll
+        for (int i = 0; i < NCT; ++i) gam_reg[i] = gamma[i];
+        gam = gam_reg;
+    } else {
+        if (threadIdx.x < N) gam_lds[threadIdx.x] = gamma[threadIdx.x];
+        __syncthreads();
+        gam = gam_lds;
+    }
+    constexpr int64_t kTile = (int64_t)BLK * UNR;
+    constexpr int kTileCols = BLK * UNR * VEC;
+    const int64_t ntiles = (ngroups + kTile - 1) / kTile;
+    const int grid = (int)gridDim.x, b = (int)blockIdx.x;
+    const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;
+    // the q-th tile of this workgroup: one per sweep of the grid, as in wsum_kernel (runs of neighbouring
+    // tiles per workgroup measured 10-20 % slower for N >= 12 at d = 25.6 M)
+    auto tile_of = [&](int64_t q) __attribute__((always_inline)) -> int64_t { return (int64_t)slot + q * grid; };
+    // parked tiles are the q_first-th, ... of this workgroup: written out when `cap` of them are waiting
+    auto flush = [&](int64_t q_first, int n) __attribute__((always_inline)) {
+        __syncthreads();   // the images are complete
+        for (int k = 0; k < n; ++k) {
+            const int64_t t = tile_of(q_first + k);
+            const int64_t tt = reverse ? (ntiles - 1 - t) : t;
+            float *dst = out + tt * kTileCols;
+            const float *src = park + (size_t)k * kTileCols;
+#pragma unroll
+            for (int q = 0; q < kTileCols / 4 / BLK; ++q) {
+                const int e = (q * BLK + (int)threadIdx.x) * 4;   // 1 KB per wavefront and instruction
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(src + e);
+                gf32x4 *p = reinterpret_cast<gf32x4 *>(dst + e);
+                if constexpr (APPLY) {
+                    const f32x4 w = *p;
+                    const f32x4 y = {fmaf(-lr, x.x, w.x), fmaf(-lr, x.y, w.y), fmaf(-lr, x.z, w.z), fmaf(-lr, x.w, w.w)};
+                    *p = y;
+                } else {
+                    __builtin_nontemporal_store(x, p);
+                }
+            }
+        }
+        __syncthreads();   // the images may be overwritten
+    };
+    int parked = 0;
+    int64_t q_first = 0;
+    for (int64_t q = 0;; ++q) {   // uniform over the workgroup
+        const int64_t t = tile_of(q);
+        if (t >= ntiles) break;   // tile_of ascends
+        const int64_t tt = reverse ? (ntiles - 1 - t) : t;
+        const int64_t base = tt * kTile + threadIdx.x;
+        if ((tt + 1) * kTile <= ngroups) {
+            if (parked == 0) q_first = q;
+            wsum_tile<NCT, T, VEC, UNR, true, APPLY, true, BLK>(G, N, d, ngroups, base, gam, out, lr,
+                                                           park + (size_t)parked * kTileCols);
+            if (++parked == cap) {
+                flush(q_first, parked);
+                parked = 0;
+            }
+        } else {
+            if (parked > 0) {   // keeps the parked tiles consecutive in this workgroup's sequence
+                flush(q_first, parked);
+                parked = 0;
+            }
+            wsum_tile<NCT, T, VEC, UNR, false, APPLY, false, BLK>(G, N, d, ngroups, base, gam, out, lr);
+        }
+    }
+    if (parked > 0) flush(q_first, parked);
+}
+
 template <typename Kern>
 static int occupancy(Kern k) {
     int nb = 0;
@@ -154,6 +247,35 @@ static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const L
     // (N = 8, 0.8 GB: 138 us against 150 us at one per CU); one per CU for long streams of few rows
     // (N <= 8, 1.6 GB and up: 2-7 % faster); N >= 16 shows no preference beyond noise.
     const bool long_stream = N <= 8 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 28;   // 1.25 GiB
+    // Parked output (wsum_parked_kernel).  Measured, plain -> parked: N = 64, d = 25.6 M 1.16 -> 1.02 ms;
+    // N = 32 0.60 -> 0.52 ms; N = 16 0.295 -> 0.263 ms, and 1.51 -> 1.40 ms at d = 124 M; N = 12 0.220 -> 0.207 ms;
+    // even (+-4 %) at d = 4 M .. 16.7 M, 3-5 % slower for N <= 9, 10-25 % slower at d = 1 M; bf16 inputs
+    // lose (N >= 32: twice the time).  Value 1 leaves the choice to that table.
+    const bool park_pays = sizeof(T) == 4 && N >= 12 && d >= ((int64_t)1 << 24);
+    const int park_kb = shape.wsum_park_kb == 1 ? (park_pays ? 128 : 0) : shape.wsum_park_kb;
+    if (park_kb >= 8) {
+        // output tiles parked in LDS: one workgroup of kParkBlock threads per CU (or as many as asked for,
+        // sharing the LDS)
+        constexpr int kTileBytes = kParkBlock * UNR * VEC * 4;
+        constexpr int kMaxParkBytes = 144 * 1024;
+        static const hipError_t attr = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(wsum_parked_kernel<NCT, T, VEC, UNR, APPLY, kParkBlock>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxParkBytes);
+        if (attr != hipSuccess) return attr;
+        const int per_cu_p = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 1;
+        int64_t bytes = (int64_t)park_kb * 1024;
+        if (bytes > kMaxParkBytes) bytes = kMaxParkBytes;
+        int cap = (int)(bytes / per_cu_p / kTileBytes);
+        if (cap < 1) cap = 1;
+        const int64_t work_p = (ngroups + (int64_t)kParkBlock * UNR - 1) / ((int64_t)kParkBlock * UNR);
+        int64_t grid_p = (int64_t)shape.num_cu * per_cu_p;
+        if (grid_p > work_p) grid_p = work_p;
+        if (grid_p < 1) grid_p = 1;
+        hipLaunchKernelGGL((wsum_parked_kernel<NCT, T, VEC, UNR, APPLY, kParkBlock>), dim3((unsigned)grid_p),
+                           dim3(kParkBlock), (size_t)cap * kTileBytes, s, static_cast<const T *>(G), N, d, ngroups, gamma,
+                           out, reverse ? 1 : 0, lr, cap);
+        return hipGetLastError();
+    }
     int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : (long_stream ? 1 : 8);
     if (per_cu > occ) per_cu = occ;
     int64_t grid = (int64_t)shape.num_cu * per_cu;

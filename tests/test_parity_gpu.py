@@ -526,6 +526,50 @@ def test_statistics_only_degenerate_rows(pkg):
     agg.close()
 
 
+# ------------------------------------------------------------- parked output (stage A3) ----
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("N,d,park_kb,reverse", [(3, 3_000_003, 8, 0), (8, 3_000_000, 24, 0), (8, 4_194_304, 40, 1),
+                                                 (16, 2_000_004, 16, 0), (4, 2_500_000, 128, 0), (40, 1_500_008, 48, 0),
+                                                 (128, 600_000, 144, 0), (8, 1000, 128, 0), (5, 2_100_000, 32, 1)])
+def test_parked_output_matches_oracle_and_plain_kernel(pkg, N, d, park_kb, reverse, dtype):
+    """ADACONS_TUNE_WSUM_PARK_KB: whole output tiles parked in LDS and written in bursts -- several
+    bursts per workgroup, a partial last tile, a ragged d, both orders of the second pass; the
+    output must equal the plain kernel's bit for bit (same sums, only the time of the store differs),
+    and the fused descent step must agree with it too."""
+    G = randG(N, d, dtype=dtype, sigma=2.0, seed=5 * N + park_kb)
+    ref_agg = pkg.AdaCons(N, d)
+    ref_agg.tune(pkg.ADACONS_TUNE_REVERSE_SECOND_PASS, reverse)
+    ref = ref_agg.aggregate(G).clone()
+    agg = pkg.AdaCons(N, d)
+    agg.tune(pkg.ADACONS_TUNE_WSUM_PARK_KB, park_kb)
+    agg.tune(pkg.ADACONS_TUNE_REVERSE_SECOND_PASS, reverse)
+    out, info, oinfo = both(pkg, G, agg, o.OracleState(N))
+    assert torch.equal(out, ref)
+    w = torch.randn(d, device=DEV)
+    w_ref = w.clone()
+    agg.aggregate_apply(G, w, lr=0.5)
+    ref_agg.aggregate_apply(G, w_ref, lr=0.5)
+    assert torch.equal(w, w_ref)
+    agg.close(); ref_agg.close()
+
+
+def test_parked_output_is_the_default_for_long_fp32_streams(pkg):
+    """fp32, N >= 12, d >= 2^24: the default second pass parks its output; bit-identical to the plain
+    kernel (ADACONS_TUNE_WSUM_PARK_KB = 0).  Values other than 0, 1, 8..144 are rejected."""
+    N, d = 12, (1 << 24) + 4100
+    G = randG(N, d, sigma=2.0, seed=3)
+    plain = pkg.AdaCons(N, d)
+    plain.tune(pkg.ADACONS_TUNE_WSUM_PARK_KB, 0)
+    dflt = pkg.AdaCons(N, d)
+    a, b = plain.aggregate(G).clone(), dflt.aggregate(G).clone()
+    assert torch.equal(a, b)
+    for bad in (2, 7, 145):
+        with pytest.raises(pkg.AdaConsError) as e:
+            dflt.tune(pkg.ADACONS_TUNE_WSUM_PARK_KB, bad)
+        assert e.value.status == 1
+    plain.close(); dflt.close()
+
+
 # ------------------------------------------------------------------ more than 64 workers ----
 @pytest.mark.parametrize("N,d", [(65, 1_000), (65, 40_003), (80, 20_000), (96, 65_536 + 24), (97, 10_001), (112, 30_000),
                                  (127, 9_999), (128, 131_072 + 8), (128, 5), (128, 1), (128, 4_000_004)])
