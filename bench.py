@@ -34,8 +34,8 @@ PMC_TRAFFIC_BYTES = {
     ("C2", "wsum_kernel (A3)", ()): 856_968_730 + 102_228_128,
     ("C3", "gram_kernel (A1)", ()): 5_362_245_304 + 147_456,
     ("C3", "wsum_kernel (A3)", ()): 5_362_187_821 + 1_340_567_555,
-    ("C4", "gram_kernel (A1)", ()): 6_654_447_235 + 4_259_840,
-    ("C4", "wsum_kernel (A3)", ()): 6_874_194_215 + 102_234_827,
+    ("C4", "gram_kernel (A1)", ()): 6_651_152_996 + 4_259_840,
+    ("C4", "wsum_kernel (A3)", ()): 6_875_120_105 + 102_235_770,
     ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_818_827_424 + 262_144,
     ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 6_865_485_640 + 102_239_502,
     ("C5", "gram_kernel (A1)", ()): 7_964_268_156 + 557_057,

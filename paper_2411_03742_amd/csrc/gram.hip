@@ -112,10 +112,30 @@ finish_kernel(const double *partials, int nrows, double *K, DevState *ds, CoeffP
     if (with_coeffs) update_coefficients(K_lds, ds, cp, lds, m_old);
 }
 
+// The coefficient update as a launch of its own (N > 44, after reduce_kernel).  Four threads share a
+// row of K: each adds a quarter of it (elements j = quarter, quarter + 4, ...: neighbouring threads
+// read neighbouring addresses, the loads of one thread are independent), the quarters are added in
+// order; a single thread walking its row of N dependent-latency loads took 12 us at N = 64.
 __global__ void __launch_bounds__(kBlock) coeff_kernel(const double *K, DevState *ds, CoeffParams cp) {
     __shared__ double lds[3 * kNMax];
-    const double m_old = ((int)threadIdx.x < cp.N) ? ds->m[threadIdx.x] : 0.0;
-    update_coefficients(K, ds, cp, lds, m_old);
+    __shared__ double part[4][ADACONS_GRAM_N_MAX];
+    static_assert(4 * ADACONS_GRAM_N_MAX <= kBlock, "four threads per row");
+    const int N = cp.N, tid = threadIdx.x;
+    const double m_old = (tid < N) ? ds->m[tid] : 0.0;
+    const int row = tid >> 2, quarter = tid & 3;
+    if (row < N) {
+        double acc = 0.0;
+#pragma unroll 4
+        for (int j = quarter; j < N; j += 4) acc += K[(size_t)row * N + j];
+        part[quarter][row] = acc;
+    }
+    __syncthreads();
+    double q = 0.0, r = 0.0;
+    if (tid < N) {
+        q = K[(size_t)tid * N + tid];
+        r = ((part[0][tid] + part[1][tid]) + part[2][tid]) + part[3][tid];
+    }
+    update_coefficients_from_stats(q, r, ds, cp, lds, m_old);
 }
 
 // ------------------------------------------------------------------------------------------
