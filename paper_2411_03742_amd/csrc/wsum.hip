@@ -258,10 +258,17 @@ static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const L
         // sharing the LDS)
         constexpr int kTileBytes = kParkBlock * UNR * VEC * 4;
         constexpr int kMaxParkBytes = 144 * 1024;
-        static const hipError_t attr = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(wsum_parked_kernel<NCT, T, VEC, UNR, APPLY, kParkBlock>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxParkBytes);
-        if (attr != hipSuccess) return attr;
+        // more than 64 KB of dynamic LDS has to be allowed once per kernel and device (setting it again is harmless)
+        static bool allowed[64] = {};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64 || !allowed[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(wsum_parked_kernel<NCT, T, VEC, UNR, APPLY, kParkBlock>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxParkBytes);
+            if (e != hipSuccess) return e;
+            if (dev >= 0 && dev < 64) allowed[dev] = true;
+        }
         const int per_cu_p = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 1;
         int64_t bytes = (int64_t)park_kb * 1024;
         if (bytes > kMaxParkBytes) bytes = kMaxParkBytes;
