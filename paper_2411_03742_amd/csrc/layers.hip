@@ -443,6 +443,146 @@ wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun 
     }
 }
 
+// The same with the output parked in LDS and written in bursts (long fp32 streams of many rows: a
+// steady trickle of stores among the loads costs such a pass about a tenth of its time).  One
+// workgroup per CU; a piece that lies inside its run and its layer leaves an image of its
+// kWsumPiece * VEC output columns in LDS, and `cap` images are written back to back; the other
+// pieces go group by group with masks as above.  Same sums in the same order as the kernel above.
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kBlock)
+wsum_layers_rt_parked_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *__restrict__ runs, int nruns,
+                             const DevState *__restrict__ ds_all, float *__restrict__ out, int run_groups, int cap) {
+    constexpr int kPiece = kWsumPiece;
+    constexpr int kPieceCols = kPiece * VEC;
+    extern __shared__ __attribute__((aligned(16))) float park[];            // cap images of kPieceCols floats ...
+    int64_t *dest = reinterpret_cast<int64_t *>(park + (size_t)cap * kPieceCols);   // ... and their first columns
+    const int split = run_groups / kPiece;
+    const int grid = (int)gridDim.x, b = (int)blockIdx.x;
+    const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;   // XCD-contiguous pieces
+    const int64_t npieces = (int64_t)nruns * split;
+    int parked = 0;
+    auto flush = [&]() __attribute__((always_inline)) {
+        __syncthreads();   // images and destinations are complete
+        for (int k = 0; k < parked; ++k) {
+            float *dst = out + dest[k];
+            const float *src = park + (size_t)k * kPieceCols;
+#pragma unroll
+            for (int q = 0; q < kPieceCols / 4 / kBlock; ++q) {
+                const int e = (q * kBlock + (int)threadIdx.x) * 4;   // 1 KB per wavefront and instruction
+                __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(src + e), reinterpret_cast<gf32x4 *>(dst + e));
+            }
+        }
+        __syncthreads();   // the images may be overwritten
+        parked = 0;
+    };
+    for (int64_t pc = slot; pc < npieces; pc += grid) {   // uniform over the workgroup
+        const LayerRun run = runs[pc / split];
+        const int first = (int)(pc % split) * kPiece;
+        if (first >= run.n) continue;
+        const int last = (first + kPiece < run.n) ? first + kPiece : run.n;
+        const float *gam = ds_all[run.layer].gamma32;
+        const int64_t cb = run.cb, ce = run.ce;
+        const int64_t p0 = (run.g0 + first) * VEC;   // first column of the piece
+        if (first + kPiece <= run.n && p0 >= cb && p0 + (int64_t)kPieceCols <= ce) {
+            constexpr int U = kPiece / kBlock;   // groups per thread
+            float acc[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
+            for (int i0 = 0; i0 < N; i0 += 8) {
+                float v[U][8][VEC];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int ii = 0; ii < 8; ++ii)
+                        if (i0 + ii < N)
+                            load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + p0 + ((int64_t)u * kBlock + threadIdx.x) * VEC, v[u][ii]);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int ii = 0; ii < 8; ++ii)
+                        if (i0 + ii < N) {
+                            const float w = gam[i0 + ii];
+#pragma unroll
+                            for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w, v[u][ii][c], acc[u][c]);
+                        }
+            }
+            float *img = park + (size_t)parked * kPieceCols;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < VEC; c += 4) {
+                    const f32x4 x = {acc[u][c], acc[u][c + 1], acc[u][c + 2], acc[u][c + 3]};
+                    *reinterpret_cast<f32x4 *>(img + ((size_t)u * kBlock + threadIdx.x) * VEC + c) = x;
+                }
+            if (threadIdx.x == 0) dest[parked] = p0;
+            if (++parked == cap) flush();
+            continue;
+        }
+        for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
+            const int64_t c0 = (run.g0 + k) * VEC;
+            const int64_t lb = (c0 + VEC > d) ? d - VEC : c0;   // the group at the ragged end of a row
+            float acc[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+            for (int i0 = 0; i0 < N; i0 += 8) {
+                float v[8][VEC];
+#pragma unroll
+                for (int ii = 0; ii < 8; ++ii)
+                    if (i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + lb, v[ii]);
+#pragma unroll
+                for (int ii = 0; ii < 8; ++ii)
+                    if (i0 + ii < N) {
+                        const float w = gam[i0 + ii];
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w, v[ii][c], acc[c]);
+                    }
+            }
+            if (c0 >= cb && c0 + VEC <= ce) {
+#pragma unroll
+                for (int c = 0; c < VEC; c += 4) {
+                    const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+                    __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(out + c0 + c));
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c)
+                    if (lb + c >= c0 && lb + c >= cb && lb + c < ce) out[lb + c] = acc[c];
+            }
+        }
+    }
+    if (parked > 0) flush();
+}
+
+// Launch of stage A3 for N > 8: parked output where it measured faster model-wise (fp32, N >= 12,
+// d >= 2^24), else the plain kernel.
+template <typename T, int VEC>
+static hipError_t launch_wsum_layers_rt(const void *G, int N, int64_t d, const LayerRun *runs, int nruns, int run_groups,
+                                        int wsum_grid, const DevState *ds_all, float *out, hipStream_t s) {
+    if (sizeof(T) == 4 && N >= 12 && d >= ((int64_t)1 << 24)) {
+        constexpr int kImageBytes = kWsumPiece * VEC * 4;
+        constexpr int cap = 128 * 1024 / kImageBytes;
+        constexpr int lds_bytes = cap * kImageBytes + cap * 8;
+        static bool allowed[64] = {};   // more than 64 KB of dynamic LDS: allowed once per kernel and device
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64 || !allowed[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(wsum_layers_rt_parked_kernel<T, VEC>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e != hipSuccess) return e;
+            if (dev >= 0 && dev < 64) allowed[dev] = true;
+        }
+        hipLaunchKernelGGL((wsum_layers_rt_parked_kernel<T, VEC>), dim3(wsum_grid / 8), dim3(kBlock), lds_bytes, s,
+                           static_cast<const T *>(G), N, d, runs, nruns, ds_all, out, run_groups, cap);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL((wsum_layers_rt_kernel<T, VEC>), dim3(wsum_grid), dim3(kBlock), 0, s, static_cast<const T *>(G),
+                       N, d, runs, nruns, ds_all, out, run_groups);
+    return hipGetLastError();
+}
+
 template <int NT, typename T, int VEC>
 static hipError_t run_layers_stats(const void *G, int N, int64_t d, const LayerRun *runs, int nruns, int run_groups, const int *order,
                                    int gram_grid, int wsum_grid, const int *layer_entry0, int L, double *partials,
@@ -455,9 +595,7 @@ static hipError_t run_layers_stats(const void *G, int N, int64_t d, const LayerR
     hipLaunchKernelGGL(finish_layers_kernel, dim3(L), dim3(kLayerFinishBlock), 0, s, partials, layer_entry0, K_all,
                        ds_all, cp, ticket);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((wsum_layers_rt_kernel<T, VEC>), dim3(wsum_grid), dim3(kBlock), 0, s, static_cast<const T *>(G),
-                       N, d, runs, nruns, ds_all, out, run_groups);
-    return hipGetLastError();
+    return launch_wsum_layers_rt<T, VEC>(G, N, d, runs, nruns, run_groups, wsum_grid, ds_all, out, s);
 }
 
 template <typename T, int VEC, typename... A>

@@ -159,6 +159,24 @@ def test_layouts_off_the_16_byte_grid(pkg, N, d, L, shift, dtype):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("N,L", [(12, 40), (16, 161)])
+def test_long_fp32_streams_of_many_workers(pkg, N, L):
+    """fp32, N >= 12, d >= 2^24: the second pass parks whole pieces of output in LDS and writes them in
+    bursts; pieces on layer boundaries and at the ragged end of a row take the masked path."""
+    d = (1 << 24) + 12_345
+    rng = np.random.default_rng(L)
+    off = _rand_layout(rng, d, L)
+    g = torch.Generator(device=DEV).manual_seed(N)
+    agg = pkg.AdaConsLayers(N, off, beta=0.9)
+    states = [o.OracleState(N, beta=0.9) for _ in range(L)]
+    for t in range(2):
+        s = torch.randn(d, generator=g, device=DEV)
+        G = (s[None, :] + 2.0 * torch.randn(N, d, generator=g, device=DEV)).contiguous()
+        _check_layers(pkg, G, off, agg, states, 1e-5)
+    agg.close()
+
+
+@pytest.mark.gpu
 def test_layers_need_one_whole_group(pkg):
     with pytest.raises(pkg.AdaConsError) as e:
         pkg.AdaConsLayers(4, [0, 2, 3])
