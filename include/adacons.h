@@ -216,7 +216,8 @@ typedef enum {
                                              in LDS and writes them back to back when the space is used up,
                                              instead of storing tile by tile among the loads (a steady trickle of
                                              stores costs long read streams 7-13 %).  0: never; 1 (default): where
-                                             it measured faster (fp32, N >= 12, d >= 2^24), with 128 KB;
+                                             it measured faster (fp32, d >= 2^24, and N >= 12 or at least
+                                             1.25 GiB of gradients with N other than 4 and 8), with 128 KB;
                                              8 .. 144: always, with that many KB of LDS */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;

@@ -249,9 +249,13 @@ static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const L
     const bool long_stream = N <= 8 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 28;   // 1.25 GiB
     // Parked output (wsum_parked_kernel).  Measured, plain -> parked: N = 64, d = 25.6 M 1.16 -> 1.02 ms;
     // N = 32 0.60 -> 0.52 ms; N = 16 0.295 -> 0.263 ms, and 1.51 -> 1.40 ms at d = 124 M; N = 12 0.220 -> 0.207 ms;
-    // even (+-4 %) at d = 4 M .. 16.7 M, 3-5 % slower for N <= 9, 10-25 % slower at d = 1 M; bf16 inputs
-    // lose (N >= 32: twice the time).  Value 1 leaves the choice to that table.
-    const bool park_pays = sizeof(T) == 4 && N >= 12 && d >= ((int64_t)1 << 24);
+    // even (+-4 %) at d = 4 M .. 16.7 M, 3-5 % slower for N <= 9 at d = 25.6 M, 10-25 % slower at d = 1 M; bf16
+    // inputs lose (N >= 32: twice the time).  Streams of 1.25 GiB and more through the run-time-N kernel
+    // (N other than 4, 8, 16) gain too: N = 1, 2, 3, 5 4-8 %, N = 9, 10, 11 7-12 %, N = 6, 7 even; the
+    // kernels compiled for N = 4 and N = 8 stay 4-6 % ahead of it at any length.  Value 1 leaves the
+    // choice to that table.
+    const bool long_generic = NCT == 0 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 28;
+    const bool park_pays = sizeof(T) == 4 && d >= ((int64_t)1 << 24) && (N >= 12 || long_generic);
     const int park_kb = shape.wsum_park_kb == 1 ? (park_pays ? 128 : 0) : shape.wsum_park_kb;
     if (park_kb >= 8) {
         // output tiles parked in LDS: one workgroup of kParkBlock threads per CU (or as many as asked for,

@@ -553,10 +553,11 @@ def test_parked_output_matches_oracle_and_plain_kernel(pkg, N, d, park_kb, rever
     agg.close(); ref_agg.close()
 
 
-def test_parked_output_is_the_default_for_long_fp32_streams(pkg):
-    """fp32, N >= 12, d >= 2^24: the default second pass parks its output; bit-identical to the plain
-    kernel (ADACONS_TUNE_WSUM_PARK_KB = 0).  Values other than 0, 1, 8..144 are rejected."""
-    N, d = 12, (1 << 24) + 4100
+@pytest.mark.parametrize("N,d", [(12, (1 << 24) + 4100), (5, 70_000_004)])
+def test_parked_output_is_the_default_for_long_fp32_streams(pkg, N, d):
+    """fp32, d >= 2^24, and N >= 12 or 1.25 GiB of gradients through the run-time-N kernel: the default
+    second pass parks its output; bit-identical to the plain kernel (ADACONS_TUNE_WSUM_PARK_KB = 0).
+    Values other than 0, 1, 8..144 are rejected."""
     G = randG(N, d, sigma=2.0, seed=3)
     plain = pkg.AdaCons(N, d)
     plain.tune(pkg.ADACONS_TUNE_WSUM_PARK_KB, 0)
