@@ -391,6 +391,42 @@ wsum_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
     }
 }
 
+// One column group of stage A3 for a run-time number of rows: rows eight at a time, weights through
+// uniform loads; a group shared with a neighbouring layer or at the ragged end of a row stores only
+// this group's columns of this layer [cb, ce).
+template <typename T, int VEC>
+__device__ __forceinline__ void wsum_layers_rt_group(const T *__restrict__ G, int N, int64_t d, const float *gam,
+                                                     int64_t c0, int64_t cb, int64_t ce, float *__restrict__ out) {
+    const int64_t lb = (c0 + VEC > d) ? d - VEC : c0;   // a group that reaches past the row is read from d - VEC
+    float acc[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+    for (int i0 = 0; i0 < N; i0 += 8) {
+        float v[8][VEC];
+#pragma unroll
+        for (int ii = 0; ii < 8; ++ii)
+            if (i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + lb, v[ii]);
+#pragma unroll
+        for (int ii = 0; ii < 8; ++ii)
+            if (i0 + ii < N) {
+                const float w = gam[i0 + ii];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w, v[ii][c], acc[c]);
+            }
+    }
+    if (c0 >= cb && c0 + VEC <= ce) {
+#pragma unroll
+        for (int c = 0; c < VEC; c += 4) {
+            const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+            __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(out + c0 + c));
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c)
+            if (lb + c >= c0 && lb + c >= cb && lb + c < ce) out[lb + c] = acc[c];
+    }
+}
+
 // A3 for N > 8: the number of rows is a run-time value, rows are walked eight at a time, the
 // weights are read through uniform (scalar) loads of the run's layer.
 template <typename T, int VEC>
@@ -410,35 +446,7 @@ wsum_layers_rt_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun 
         const float *gam = ds_all[run.layer].gamma32;
         const int64_t cb = run.cb, ce = run.ce;
         for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
-            const int64_t c0 = (run.g0 + k) * VEC;
-            const int64_t lb = (c0 + VEC > d) ? d - VEC : c0;   // the group at the ragged end of a row
-            float acc[VEC];
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
-            for (int i0 = 0; i0 < N; i0 += 8) {
-                float v[8][VEC];
-#pragma unroll
-                for (int ii = 0; ii < 8; ++ii)
-                    if (i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + lb, v[ii]);
-#pragma unroll
-                for (int ii = 0; ii < 8; ++ii)
-                    if (i0 + ii < N) {
-                        const float w = gam[i0 + ii];
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w, v[ii][c], acc[c]);
-                    }
-            }
-            if (c0 >= cb && c0 + VEC <= ce) {
-#pragma unroll
-                for (int c = 0; c < VEC; c += 4) {
-                    const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
-                    __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(out + c0 + c));
-                }
-            } else {
-#pragma unroll
-                for (int c = 0; c < VEC; ++c)
-                    if (lb + c >= c0 && lb + c >= cb && lb + c < ce) out[lb + c] = acc[c];
-            }
+            wsum_layers_rt_group<T, VEC>(G, N, d, gam, (run.g0 + k) * VEC, cb, ce, out);
         }
     }
 }
@@ -521,35 +529,7 @@ wsum_layers_rt_parked_kernel(const T *__restrict__ G, int N, int64_t d, const La
             continue;
         }
         for (int k = first + (int)threadIdx.x; k < last; k += kBlock) {
-            const int64_t c0 = (run.g0 + k) * VEC;
-            const int64_t lb = (c0 + VEC > d) ? d - VEC : c0;   // the group at the ragged end of a row
-            float acc[VEC];
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
-            for (int i0 = 0; i0 < N; i0 += 8) {
-                float v[8][VEC];
-#pragma unroll
-                for (int ii = 0; ii < 8; ++ii)
-                    if (i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + lb, v[ii]);
-#pragma unroll
-                for (int ii = 0; ii < 8; ++ii)
-                    if (i0 + ii < N) {
-                        const float w = gam[i0 + ii];
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w, v[ii][c], acc[c]);
-                    }
-            }
-            if (c0 >= cb && c0 + VEC <= ce) {
-#pragma unroll
-                for (int c = 0; c < VEC; c += 4) {
-                    const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
-                    __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(out + c0 + c));
-                }
-            } else {
-#pragma unroll
-                for (int c = 0; c < VEC; ++c)
-                    if (lb + c >= c0 && lb + c >= cb && lb + c < ce) out[lb + c] = acc[c];
-            }
+            wsum_layers_rt_group<T, VEC>(G, N, d, gam, (run.g0 + k) * VEC, cb, ce, out);
         }
     }
     if (parked > 0) flush();
