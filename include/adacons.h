@@ -211,7 +211,8 @@ typedef enum {
                                              steps 1-2), in O(N) operations per column; K itself is then not
                                              produced and adacons_read_gram() reports ADACONS_EINVAL.  Honoured
                                              by adacons_aggregate / adacons_aggregate_apply; for N <= 8 the
-                                             Gram kernel runs.  0 (default): full K */
+                                             Gram kernel runs.  0 (default): full K (N > ADACONS_GRAM_N_MAX
+                                             takes this pass whatever the value) */
     ADACONS_TUNE_WSUM_PARK_KB = 7,        /* A3 with parked output: one workgroup per CU keeps whole tiles of output
                                              in LDS and writes them back to back when the space is used up,
                                              instead of storing tile by tile among the loads (a steady trickle of
@@ -293,7 +294,8 @@ typedef struct adacons_layers adacons_layers; /* opaque, library-owned */
  *   N             workers, 1 <= N <= ADACONS_GRAM_N_MAX
  *   L             number of layers, >= 1
  *   offsets_host  host pointer, L + 1 ascending column offsets, offsets[0] = 0, offsets[L] = d;
- *                 empty layers (equal consecutive offsets) are not allowed
+ *                 empty layers (equal consecutive offsets) are not allowed; d must be at least one
+ *                 128-bit group (4 fp32 / 8 bf16 elements)
  *   dtype         element type later calls will pass (fixes the tile geometry)
  *   beta, flags   as in adacons_init_state
  * Errors: EINVAL, EUNSUPPORTED (N > ADACONS_GRAM_N_MAX, unknown dtype), ENOMEM, EHIP.
