@@ -30,16 +30,16 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 PMC_TRAFFIC_BYTES = {
     ("C1", "gram_kernel (A1)", ()): 16_802_265 + 24_576,
     ("C1", "wsum_kernel (A3)", ()): 16_791_019 + 4_194_304,
-    ("C2", "gram_kernel (A1)", ()): 826_937_790 + 73_728,
-    ("C2", "wsum_kernel (A3)", ()): 856_968_730 + 102_228_128,
-    ("C3", "gram_kernel (A1)", ()): 5_362_245_304 + 147_456,
-    ("C3", "wsum_kernel (A3)", ()): 5_362_187_821 + 1_340_567_555,
-    ("C4", "gram_kernel (A1)", ()): 6_651_152_996 + 4_259_840,
-    ("C4", "wsum_kernel (A3)", ()): 6_875_120_105 + 102_235_770,
-    ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_818_827_424 + 262_144,
-    ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 6_865_485_640 + 102_239_502,
-    ("C5", "gram_kernel (A1)", ()): 7_964_268_156 + 557_057,
-    ("C5", "wsum_kernel (A3)", ()): 7_964_114_115 + 497_815_855,
+    ("C2", "gram_kernel (A1)", ()): 827_018_672 + 73_728,
+    ("C2", "wsum_kernel (A3)", ()): 857_087_758 + 102_228_128,
+    ("C3", "gram_kernel (A1)", ()): 5_362_252_093 + 147_456,
+    ("C3", "wsum_kernel (A3)", ()): 5_362_179_118 + 1_340_567_567,
+    ("C4", "gram_kernel (A1)", ()): 6_649_439_709 + 4_259_841,
+    ("C4", "wsum_kernel (A3)", ()): 6_872_719_799 + 102_235_506,
+    ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_817_238_509 + 262_144,
+    ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 6_866_971_759 + 102_241_828,
+    ("C5", "gram_kernel (A1)", ()): 7_964_266_137 + 557_057,
+    ("C5", "wsum_kernel (A3)", ()): 7_964_113_733 + 497_818_019,
 }
 
 
@@ -146,12 +146,23 @@ def main() -> int:
         agg.aggregate(bufs[i % 2], out=out, stream=stream)
     prof = agg.profile_end(stream=stream)
 
+    # What an event pair measures with nothing between its two records, on the same stream: the part of
+    # every bracketed stage time that is not the kernel (4.4 us on the boxes this ran on; with it taken
+    # off, the stage times agree with the kernel durations rocprofv3 reports to about a microsecond).
+    pairs0 = [torch.cuda.Event(enable_timing=True) for _ in range(202)]
+    for e in pairs0:
+        e.record(stream)
+    torch.cuda.synchronize()
+    gaps = sorted(pairs0[i].elapsed_time(pairs0[i + 1]) for i in range(1, 201))
+    bracket_ms = gaps[len(gaps) // 2]
+
     floor = w.floor_bytes
     gbps = floor / (ms_per_step * 1e-3) / 1e9
     eb = w.elem_bytes
+    net = lambda ms: max(ms - bracket_ms, 0.5 * ms)
     stages = {
-        "gram_kernel (A1)": (w.N * w.d * eb, prof["gram_ms"]),
-        "wsum_kernel (A3)": (w.N * w.d * eb + 4 * w.d, prof["wsum_ms"]),
+        "gram_kernel (A1)": (w.N * w.d * eb, net(prof["gram_ms"])),
+        "wsum_kernel (A3)": (w.N * w.d * eb + 4 * w.d, net(prof["wsum_ms"])),
     }
     dom = max(stages, key=lambda k: stages[k][1])
     dom_bytes, dom_ms = stages[dom]
@@ -160,7 +171,10 @@ def main() -> int:
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": PMC_TRAFFIC_BYTES.get((args.workload, dom, tuple(sorted(tuned.items())))),
         "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 5),
-        "stages_ms": dict({k: round(v[1], 5) for k, v in stages.items()}, **{"finish_kernel (A2)": round(prof["coeff_ms"], 5)}),
+        "event_bracket_ms": round(bracket_ms, 5),
+        "stages_ms": dict({k: round(v[1], 5) for k, v in stages.items()}, **{"finish_kernel (A2)": round(net(prof["coeff_ms"]), 5)}),
+        "stages_ms_as_bracketed": {"gram_kernel (A1)": round(prof["gram_ms"], 5), "wsum_kernel (A3)": round(prof["wsum_ms"], 5),
+                                   "finish_kernel (A2)": round(prof["coeff_ms"], 5)},
         "stages_GBps": {k: round(v[0] / (v[1] * 1e-3) / 1e9, 1) for k, v in stages.items()},
     }
 
