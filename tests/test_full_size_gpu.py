@@ -1,21 +1,29 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+"""GPU parity at the benchmark's full sizes and full step counts, in the launch configuration
+bench.py times.
 
-The oracle computes the whole float64 Gram matrix and coefficients for these inputs (seconds on
-the host's cores); the d-length output is compared on sampled columns, which the oracle evaluates
-one by one: the first and last 256 columns (tile heads and ragged tails) and 8192 seeded random
-ones.  Multi-step configurations run a prefix of their step count here; the whole step count runs
-at reduced length in test_parity_gpu.py.
+Every configuration runs as it is defined: C2 20 steps, C3 1 step, C4 10 steps, C5 100 steps, each
+at its full gradient length with the Eq. 11 state carried from step to step.  At every step the
+oracle computes the whole float64 Gram matrix and the coefficients from the same input bits
+(copied through one reused pinned host buffer), and gamma, the first-order and the smoothed
+coefficients are compared one to one.  The d-length output is compared in full -- every element
+against the rounding bound of the fp32 sum, and the stated relative L2 tolerance over the whole
+vector -- at every step for C2, C3 and C4, and on the first, every tenth and the last step for C5
+(in blocks of 2^24 columns so that host memory stays bounded); on the other C5 steps it is checked
+to be completely written and finite.
 """
+from dataclasses import replace
+
 import numpy as np
 import pytest
 import torch
 
 import workloads
 from oracle import adacons_oracle as o
+from parity_checks import OUT_TOL, assert_out_elementwise, check_coefficients
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-OUT_TOL = {"f32": 1e-5, "bf16": 2e-3}
+BLOCK = 1 << 24
 
 
 @pytest.fixture(scope="module")
@@ -26,45 +34,76 @@ def pkg():
     return p
 
 
-def sample_columns(d, seed):
-    rng = np.random.default_rng(seed)
-    edge = min(256, d)
-    idx = np.concatenate([np.arange(edge), np.arange(d - edge, d), rng.integers(0, d, 8192)])
-    return np.unique(idx)
+class HostCopy:
+    """One pinned host buffer, reused for every step's device-to-host copy of G."""
+
+    def __init__(self, N, d, dtype):
+        self.N, self.d = N, d
+        self.t = torch.empty((N, d), dtype=dtype, pin_memory=True)
+
+    def fetch(self, G):
+        self.t.copy_(G)            # synchronous for a pinned destination once the call returns ...
+        torch.cuda.synchronize()   # ... and made certain here
+        if self.t.dtype == torch.bfloat16:
+            return self.t.view(torch.int16).numpy().view(np.uint16)
+        return self.t.numpy()
 
 
-@pytest.mark.parametrize("name,steps,stats_only", [("C2", 20, 0), ("C3", 1, 0), ("C4", 2, 0), ("C5", 3, 0),
+def check_whole_out(out, Gh, gamma_gpu, gamma_ref, tol):
+    """All d elements, block by block: the element-wise bound against the oracle's weighted sum of the
+    weights the GPU applied, and the relative L2 error against the oracle's own output."""
+    d = Gh.shape[1]
+    num = den = 0.0
+    for a in range(0, d, BLOCK):
+        b = min(d, a + BLOCK)
+        Gb = np.ascontiguousarray(Gh[:, a:b])
+        got = out[a:b].cpu().numpy()
+        assert_out_elementwise(got, Gb, gamma_gpu)
+        ref = o.weighted_sum(Gb, gamma_ref)
+        diff = got.astype(np.float64) - ref
+        num += float(diff @ diff)
+        den += float(ref @ ref)
+    assert np.sqrt(num / den) <= tol
+
+
+@pytest.mark.parametrize("name,steps,stats_only", [("C2", 20, 0), ("C3", 1, 0), ("C4", 10, 0), ("C5", 100, 0),
                                                    ("C4", 2, 1), ("C5", 2, 1), ("C4-bf16", 2, 0)])
-def test_full_size_configuration(pkg, name, steps, stats_only):
+@pytest.mark.timeout(900)
+def test_full_size_configuration(pkg, capsys, name, steps, stats_only):
     if name == "C4-bf16":     # C4's shape and recipe stored as bf16: the bf16 matrix-core Gram at full length
-        from dataclasses import replace
         w = replace(workloads.C4, name="C4-bf16", dtype="bf16")
     else:
         w = workloads.CONFIGS[name]
+    if not stats_only and name in workloads.CONFIGS:
+        assert steps == w.steps          # the configuration as defined
     w = w.scaled(w.d, steps)
     agg = pkg.AdaCons(w.N, w.d, beta=0.99)
     agg.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)   # 1: stage A1 computes diag K and row sums only
     ost = o.OracleState(w.N, beta=0.99)
-    out = torch.empty(w.d, dtype=torch.float32, device=DEV)
+    host = HostCopy(w.N, w.d, torch.bfloat16 if w.dtype == "bf16" else torch.float32)
+    out = torch.full((w.d,), float("nan"), dtype=torch.float32, device=DEV)
+    whole_every = 10 if name == "C5" else 1
     for t, G in enumerate(workloads.stream(w, DEV)):
         agg.aggregate(G, out=out)
         info = agg.coeffs()
-        Gh = workloads.to_oracle_input(G)
+        Gh = host.fetch(G)
+        state_was_zero = not ost.m.any()
         _, oinfo = o.aggregate(Gh, ost, want_out=False)
-        assert info["numeric_flags"] == oinfo["numeric_flags"] == 0
-        s = np.sort(oinfo["raw"])
-        assert np.diff(s).min() > 1e-9 * np.abs(s).max()           # ranks are unambiguous
-        for key in ("gamma", "raw", "smoothed"):
-            ref = oinfo[key]
-            assert np.linalg.norm(info[key] - ref) / np.linalg.norm(ref) <= 1e-6, (name, t, key)
-            assert (np.abs(info[key] - ref) / np.abs(ref)).max() <= 1e-6, (name, t, key)
-        idx = sample_columns(w.d, seed=t)
-        ref = o.weighted_sum_at(Gh, oinfo["gamma"], idx)
-        got = out[torch.from_numpy(idx).to(DEV)].cpu().numpy().astype(np.float64)
-        assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= OUT_TOL[w.dtype], (name, t)
-        # every element was written: the output of an all-positive-weight step cannot keep the
-        # poison the buffer is refilled with below
-        assert torch.isfinite(out).all()
+        assert oinfo["numeric_flags"] == 0
+        strict = check_coefficients(info, oinfo, ost.m, ost.flags, state_was_zero)
+        assert strict, (name, t)
+        assert abs(info["gamma"].sum() - 1.0) <= 1e-9
+        if name == "C5":      # the adversarial worker, wherever the shuffle put it, is the one negative weight
+            assert info["gamma"].min() < 0 and (info["gamma"] > 0).sum() == w.N - 1
+        if t % whole_every == 0 or t == steps - 1:
+            check_whole_out(out, Gh, info["gamma"], oinfo["gamma"], OUT_TOL[w.dtype])
+        else:
+            assert torch.isfinite(out).all()      # every element written: the buffer held NaN before the call
         out.fill_(float("nan"))
-        del Gh
+        if (t + 1) % 10 == 0 and t + 1 < steps:
+            with capsys.disabled():      # a progress line the terminal sees while the long streams run
+                print(f" [{name}: {t + 1}/{steps} steps agree]", end="", flush=True)
+    m, step = agg.export_state()
+    assert step == steps
+    assert np.abs(m - ost.m).max() <= 1e-6 * np.abs(ost.m).max()
     agg.close()
