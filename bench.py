@@ -23,24 +23,48 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
-# Bytes per launch that crossed the L2 <-> memory fabric (fetched + written), from rocprofv3 --pmc
-# FETCH_SIZE and WRITE_SIZE runs of this script, scaled by the readings of a plain device copy of
-# known size in the same run (profiles/*_hbm_traffic_pmc.txt).  Default launch configuration,
-# except the entry with a tuning tuple.
-PMC_TRAFFIC_BYTES = {
-    ("C1", "gram_kernel (A1)", ()): 16_802_265 + 24_576,
-    ("C1", "wsum_kernel (A3)", ()): 16_791_019 + 4_194_304,
-    ("C2", "gram_kernel (A1)", ()): 827_018_672 + 73_728,
-    ("C2", "wsum_kernel (A3)", ()): 857_087_758 + 102_228_128,
-    ("C3", "gram_kernel (A1)", ()): 5_362_252_093 + 147_456,
-    ("C3", "wsum_kernel (A3)", ()): 5_362_179_118 + 1_340_567_567,
-    ("C4", "gram_kernel (A1)", ()): 6_649_439_709 + 4_259_841,
-    ("C4", "wsum_kernel (A3)", ()): 6_872_719_799 + 102_235_506,
-    ("C4", "gram_kernel (A1)", (("stats_only", 1),)): 6_817_238_509 + 262_144,
-    ("C4", "wsum_kernel (A3)", (("stats_only", 1),)): 6_866_971_759 + 102_241_828,
-    ("C5", "gram_kernel (A1)", ()): 7_964_266_137 + 557_057,
-    ("C5", "wsum_kernel (A3)", ()): 7_964_113_733 + 497_818_019,
-}
+PROFILES = os.path.join(ROOT, "profiles")
+# kernels of each stage, as rocprofv3 names them
+STAGE_KERNELS = {"gram_kernel (A1)": ("gram_", "stats_wave", "stats_edge"), "wsum_kernel (A3)": ("wsum_",)}
+
+
+def pmc_traffic(workload: str, tuned: dict):
+    """Bytes per launch that crossed the L2 <-> memory fabric (fetched + written), per stage, read
+    from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/ that was made with this
+    workload and tuning (its `bench_args:` line says which).  Returns ({stage: bytes}, file name), or
+    (None, None) when no summary covers the configuration: the counters cannot be collected from
+    inside a timed run, so a configuration nobody profiled reports null."""
+    import glob
+    import re
+    want = (workload, tuple(sorted((k, int(v)) for k, v in tuned.items() if k != "graph_calls")))
+    for path in sorted(glob.glob(os.path.join(PROFILES, "*_hbm_traffic_pmc.txt"))):
+        text = open(path).read()
+        m = re.search(r"^bench_args: (.*)$", text, re.M)
+        if not m:
+            continue
+        words = m.group(1).split()
+        wl = words[words.index("--workload") + 1] if "--workload" in words else "C2"
+        tune = tuple(sorted((w.split("=")[0], int(w.split("=")[1]))
+                            for i, w in enumerate(words) if i > 0 and words[i - 1] == "--tune"))
+        if (wl, tune) != want:
+            continue
+        per_stage = {}
+        for name, nbytes in re.findall(r"^\s+(adacons::\S.*?)\s+n=\s*\d+ mean reading .*\((\d+) B\)\s*$", text, re.M):
+            for stage, keys in STAGE_KERNELS.items():
+                if any(k in name for k in keys):
+                    per_stage[stage] = per_stage.get(stage, 0) + int(nbytes)
+        return per_stage, os.path.basename(path)
+    return None, None
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main() -> int:
@@ -167,10 +191,16 @@ def main() -> int:
     dom = max(stages, key=lambda k: stages[k][1])
     dom_bytes, dom_ms = stages[dom]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic, traffic_file = pmc_traffic(args.workload, tuned)
+    dom_bracketed_ms = prof["gram_ms"] if dom.startswith("gram") else prof["wsum_ms"]
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": PMC_TRAFFIC_BYTES.get((args.workload, dom, tuple(sorted(tuned.items())))),
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "traffic": traffic.get(dom) if traffic else None,
+        "traffic_source": ("profiles/" + traffic_file) if traffic else None,
         "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": round(dom_ms, 5),
+        # the same fraction from the stage time as bracketed by its two events, empty-bracket time not taken off
+        "frac_as_bracketed": round(dom_bytes / (dom_bracketed_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "event_bracket_ms": round(bracket_ms, 5),
         "stages_ms": dict({k: round(v[1], 5) for k, v in stages.items()}, **{"finish_kernel (A2)": round(net(prof["coeff_ms"]), 5)}),
         "stages_ms_as_bracketed": {"gram_kernel (A1)": round(prof["gram_ms"], 5), "wsum_kernel (A3)": round(prof["wsum_ms"], 5),
@@ -210,7 +240,7 @@ def main() -> int:
         "value": round(gbps, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": "%s: N=%d workers, d=%d %s gradients, beta=0.99, momentum+normalisation"
                                % (w.name, w.N, w.d, w.dtype), "tuning": tuned},
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
@@ -258,7 +288,7 @@ def bench_layers(args, w, bufs, out) -> int:
         "metric": "layer-wise aggregation effective HBM bandwidth (N=%d, d=%d, %s, %d layers)" % (w.N, w.d, w.dtype, len(off) - 1),
         "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": "%s cut into the 161 parameter tensors of a ResNet-50, layer-wise coefficients" % w.name},
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2), "roofline": None, "cpu_baseline": None}))
     agg.close()
@@ -334,7 +364,7 @@ def cpu_baseline(w, G) -> dict:
     o.set_num_threads(cores)
     floor1 = 2 * w.N * d1 * w.elem_bytes + 4 * d1
     return {"value": round(w.floor_bytes / med / 1e9, 3), "unit": "GB/s", "cores": cores,
-            "kind": "oracle", "seconds_per_aggregation": round(med, 4),
+            "kind": "oracle", "cpu_model": cpu_model(), "host_logical_cpus": os.cpu_count(), "seconds_per_aggregation": round(med, 4),
             "aggregations_per_s": round(1.0 / med, 4),
             "sample": "%d whole aggregations of the full %s input (one step of the stream) in %.0f s, median time"
                       % (len(times), w.name, sum(times)),
