@@ -138,6 +138,31 @@ adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_
                                        adacons_state *st, float *w, float lr, void *hip_stream);
 
 /*
+ * adacons_aggregate() for callers that cannot allocate device memory and therefore cannot call
+ * adacons_init_state(): code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It calls no hipMalloc, hipFree or other allocating routine.  Stages A1, A2, A3 run with
+ * the same kernels and default launch shapes as adacons_aggregate() (results are bit-identical to it);
+ * what that call keeps in its state -- the partial sums of stage A1, K, the coefficient block -- lives in
+ * a 6 MiB array in the library's device image (one copy per GPU, held until the process ends), and the
+ * carried state of the momentum is the caller's:
+ *   beta, flags       as in adacons_init_state
+ *   m_dev             device pointer, N doubles, 8-byte aligned, read and rewritten: the EMA vector m (sorted
+ *                     order); zeros before the first step
+ *   coeffs_dev        device pointer, 3 N doubles (gamma, then the first-order, then the smoothed
+ *                     coefficients), written; or NULL
+ *   numeric_flags_dev device pointer, one 32-bit word (ADACONS_NUM_* of this call), written; or NULL
+ *   G, N, d, dtype, out, hip_stream   as in adacons_aggregate
+ * Limits: N <= ADACONS_N_MAX (ADACONS_EUNSUPPORTED beyond, with a message naming the limit); any d >= 1.
+ * Asynchronous; never synchronises.  All calls on one GPU share that GPU's array: calls that overlap in
+ * time on one GPU (two streams, two threads) race; calls ordered on one stream do not.  The first call on
+ * a device looks the array's address up (hipGetSymbolAddress, once per device): make it outside a graph
+ * capture.  Errors: EINVAL, EUNSUPPORTED, EALIGN, EHIP.
+ */
+adacons_status adacons_aggregate_noalloc(const void *G, int N, int64_t d, adacons_dtype dtype, double beta,
+                                         unsigned flags, double *m_dev, double *coeffs_dev,
+                                         uint32_t *numeric_flags_dev, float *out, void *hip_stream);
+
+/*
  * Read back the coefficients of the most recent adacons_aggregate() on this state
  * (the three stages of Fig. 7: first-order, after momentum, after normalisation).
  * Copies on `hip_stream` and waits for it: the only synchronising call of the hot API.

@@ -38,6 +38,7 @@ EXPORTS = [
     "adacons_profile_end", "adacons_status_string", "adacons_last_error",
     "adacons_aggregate_apply", "adacons_worker_stats", "adacons_update_from_stats", "adacons_worker_scale",
     "adacons_init_layers", "adacons_destroy_layers", "adacons_aggregate_layers", "adacons_layer_coeffs",
+    "adacons_aggregate_noalloc",
 ]
 
 
@@ -62,6 +63,7 @@ def _load() -> ctypes.CDLL:
         "adacons_reset_state": [vp, vp],
         "adacons_aggregate": [vp, i32, i64, i32, vp, vp, vp],
         "adacons_aggregate_apply": [vp, i32, i64, i32, vp, vp, ctypes.c_float, vp],
+        "adacons_aggregate_noalloc": [vp, i32, i64, i32, dbl, u32, vp, vp, vp, vp, vp],
         "adacons_worker_stats": [vp, vp, i64, i32, vp, vp, vp],
         "adacons_update_from_stats": [vp, dp, dp, vp],
         "adacons_worker_scale": [vp, i64, i32, vp, i32, vp],
@@ -160,6 +162,29 @@ def adacons_aggregate_apply(G: torch.Tensor, st, w: torch.Tensor, lr: float, str
         raise ValueError("w must be a contiguous float32 device tensor of d elements")
     _check(_lib.adacons_aggregate_apply(g, N, d, dt, st, ctypes.c_void_p(w.data_ptr()), float(lr), _stream(stream)),
            "adacons_aggregate_apply")
+
+
+def adacons_aggregate_noalloc(G: torch.Tensor, m: torch.Tensor, out: torch.Tensor, beta: float = 0.99,
+                              flags: int = ADACONS_FLAG_DEFAULT, coeffs: torch.Tensor | None = None,
+                              numeric_flags: torch.Tensor | None = None, stream=None) -> None:
+    """m: N float64 on the device (the carried state, updated in place); coeffs: 3 N float64 on the
+    device or None; numeric_flags: one int32 on the device or None."""
+    g, N, d, dt = _matrix(G)
+    if out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous() or out.numel() != d:
+        raise ValueError("out must be a contiguous float32 device tensor of d elements")
+    if m.dtype != torch.float64 or not m.is_cuda or not m.is_contiguous() or m.numel() != N:
+        raise ValueError("m must be a contiguous float64 device tensor of N elements")
+    if coeffs is not None and (coeffs.dtype != torch.float64 or not coeffs.is_cuda or not coeffs.is_contiguous()
+                               or coeffs.numel() != 3 * N):
+        raise ValueError("coeffs must be a contiguous float64 device tensor of 3 N elements")
+    if numeric_flags is not None and (numeric_flags.dtype != torch.int32 or not numeric_flags.is_cuda
+                                      or numeric_flags.numel() != 1):
+        raise ValueError("numeric_flags must be a device tensor of one int32")
+    _check(_lib.adacons_aggregate_noalloc(g, N, d, dt, float(beta), int(flags), ctypes.c_void_p(m.data_ptr()),
+                                          ctypes.c_void_p(coeffs.data_ptr()) if coeffs is not None else None,
+                                          ctypes.c_void_p(numeric_flags.data_ptr()) if numeric_flags is not None else None,
+                                          ctypes.c_void_p(out.data_ptr()), _stream(stream)),
+           "adacons_aggregate_noalloc")
 
 
 def _vector(v: torch.Tensor):

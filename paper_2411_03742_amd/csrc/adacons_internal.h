@@ -67,6 +67,9 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
 hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStream_t stream);
 int gram_rows_needed(int N, int num_cu);
 hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t stream);  // K may be NULL
+hipError_t launch_state_load(DevState *ds, int N, const double *m_in, hipStream_t stream);
+hipError_t launch_state_store(const DevState *ds, int N, double *m_out, double *coeffs, unsigned *numeric_flags,
+                              hipStream_t stream);  // coeffs (3 N doubles) and numeric_flags may be NULL
 
 // stats.hip: A1 reduced to diag K and its row sums, then A2 (N > 8)
 hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok, const LaunchShape &shape,

@@ -4,12 +4,27 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "adacons_internal.h"
 
 using namespace adacons;
+
+// ---- what adacons_aggregate_noalloc() works in --------------------------------------------------
+// Everything adacons_init_state() would allocate for one call -- the device state block, K and the
+// partial-sum workspace of stage A1 -- laid out in one file-scope device array.  Every GPU the
+// library runs on holds its own copy at its own address until the process ends; in host code the
+// array's name is only a handle for hipGetSymbolAddress(), never an address to pass on.
+constexpr size_t kScratchBytes = (size_t)6 << 20;   // 6 MiB per GPU
+constexpr size_t kScratchStateOff = 0;
+constexpr size_t kScratchKOff = (sizeof(DevState) + 255) / 256 * 256;
+constexpr size_t kScratchKBytes = ((size_t)ADACONS_N_MAX * ADACONS_N_MAX + 2 * (size_t)ADACONS_N_MAX) * sizeof(double);
+constexpr size_t kScratchPartialsOff = (kScratchKOff + kScratchKBytes + 255) / 256 * 256;
+constexpr size_t kScratchPartialsBytes = kScratchBytes - kScratchPartialsOff;
+static_assert(kScratchPartialsOff < kScratchBytes, "scratch too small");
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 struct adacons_state {
     int N;
@@ -55,6 +70,12 @@ adacons_status hip_fail(hipError_t e, const char *what) {
 const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 4, 0, 1};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
+
+// Doubles in one partial row of stage A1: N (N + 1) / 2 sums of products, or q and r per worker (2 N)
+// where K is not formed; at least the 3 sums of the one-worker statistics.
+size_t partial_row_doubles(int N) {
+    return N > ADACONS_GRAM_N_MAX ? 2 * (size_t)N : (size_t)(num_pairs(N) < 3 ? 3 : num_pairs(N));
+}
 
 // Checks shared by the three compute entry points.  out may be NULL (stage A1 alone).
 adacons_status check_call(const void *G, int N, int64_t d, adacons_dtype dtype, const adacons_state *st,
@@ -122,6 +143,38 @@ hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d,
                        st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s, between);
 }
 
+
+// Per device: the address of that device's copy of `scratch`, resolved once with the device current.
+struct DeviceScratch {
+    void *ptr;
+    int num_cu;
+    bool resolved;
+};
+constexpr int kMaxDevices = 64;
+DeviceScratch g_scratch[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+adacons_status scratch_of(int dev, DeviceScratch *out) {
+    if (dev < 0 || dev >= kMaxDevices) return fail(ADACONS_EUNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    DeviceScratch &e = g_scratch[dev];
+    if (!e.resolved) {
+        hipDeviceProp_t prop;
+        HIP_TRY(hipGetDeviceProperties(&prop, dev));
+        if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+            return fail(ADACONS_EUNSUPPORTED, "built for gfx950 only, device is %s", prop.gcnArchName);
+        void *p = nullptr;
+        hipError_t rc = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the current device's copy
+        if (rc != hipSuccess) return hip_fail(rc, "hipGetSymbolAddress(scratch)");
+        if (!p) return fail(ADACONS_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+        e.ptr = p;
+        e.num_cu = prop.multiProcessorCount;
+        e.resolved = true;
+    }
+    *out = e;
+    return ADACONS_OK;
+}
+
 }  // namespace
 
 adacons_status adacons::set_error(adacons_status s, const char *fmt, ...) {
@@ -184,9 +237,7 @@ adacons_status adacons_init_state(adacons_state **out_st, int N, int64_t d_max, 
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&st->ds), sizeof(DevState));
-    // a partial row: N (N + 1) / 2 sums of products, or q and r per worker (2 N) where K is not formed;
-    // at least the 3 sums of the one-worker statistics
-    const size_t row_doubles = N > ADACONS_GRAM_N_MAX ? 2 * (size_t)N : (size_t)(num_pairs(N) < 3 ? 3 : num_pairs(N));
+    const size_t row_doubles = partial_row_doubles(N);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->partials), (size_t)st->max_rows * row_doubles * sizeof(double));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->K), ((size_t)N * N + 2 * (size_t)N) * sizeof(double));
     if (e == hipSuccess) e = launch_clear_state(st->ds, st->K, N * N, s);
@@ -418,6 +469,60 @@ adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *c
     if (calls) *calls = n;
     st->prof_capacity = 0;
     st->prof_calls = 0;
+    return ADACONS_OK;
+}
+
+adacons_status adacons_aggregate_noalloc(const void *G, int N, int64_t d, adacons_dtype dtype, double beta,
+                                         unsigned flags, double *m_dev, double *coeffs_dev,
+                                         uint32_t *numeric_flags_dev, float *out, void *hip_stream) {
+    if (N < 1) return fail(ADACONS_EINVAL, "N=%d < 1", N);
+    if (N > ADACONS_N_MAX)
+        return fail(ADACONS_EUNSUPPORTED, "N=%d beyond the maximum of %d workers this entry point's scratch array holds", N,
+                    ADACONS_N_MAX);
+    if (!(beta >= 0.0 && beta < 1.0)) return fail(ADACONS_EINVAL, "beta=%g outside [0, 1)", beta);
+    if (flags & ~ADACONS_FLAG_ALL_) return fail(ADACONS_EINVAL, "unknown flag bits 0x%x", flags);
+    if (!m_dev) return fail(ADACONS_EINVAL, "m_dev is NULL");
+    if (reinterpret_cast<uintptr_t>(m_dev) % 8 || reinterpret_cast<uintptr_t>(coeffs_dev) % 8 ||
+        reinterpret_cast<uintptr_t>(numeric_flags_dev) % 4)
+        return fail(ADACONS_EALIGN, "m_dev / coeffs_dev / numeric_flags_dev not aligned to their element size");
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    DeviceScratch sc;
+    adacons_status rc = scratch_of(dev, &sc);
+    if (rc != ADACONS_OK) return rc;
+    unsigned char *base = static_cast<unsigned char *>(sc.ptr);
+
+    // a state on this frame whose device pointers lie in the scratch array: default launch shapes
+    adacons_state tmp;
+    tmp.N = N;
+    tmp.d_max = d;
+    tmp.beta = beta;
+    tmp.flags = flags;
+    tmp.device = dev;
+    tmp.num_cu = sc.num_cu;
+    tmp.ds = reinterpret_cast<DevState *>(base + kScratchStateOff);
+    tmp.K = reinterpret_cast<double *>(base + kScratchKOff);
+    tmp.partials = reinterpret_cast<double *>(base + kScratchPartialsOff);
+    const size_t row_doubles = partial_row_doubles(N);
+    size_t rows = kScratchPartialsBytes / (row_doubles * sizeof(double));
+    const size_t want_rows = (size_t)gram_rows_needed(N, sc.num_cu);
+    if (rows > want_rows) rows = want_rows;
+    if (rows < 2) return fail(ADACONS_EUNSUPPORTED, "scratch array too small for N=%d", N);
+    tmp.max_rows = (int)rows;   // the first pass never launches more workgroups than it has rows for
+    tmp.k_valid = false;
+    for (int k = 0; k < ADACONS_TUNE_COUNT_; ++k) tmp.tune[k] = kTuneDefault[k];
+    tmp.prof_capacity = 0;
+    tmp.prof_calls = 0;
+
+    bool vec_ok = false;
+    rc = check_call(G, N, d, dtype, &tmp, out, true, &vec_ok);
+    if (rc != ADACONS_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(launch_state_load(tmp.ds, N, m_dev, s));
+    HIP_TRY(launch_first_pass(&tmp, G, N, d, dtype, vec_ok, s, nullptr));
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(&tmp, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), tmp.ds->gamma32, out,
+                        false, s));
+    HIP_TRY(launch_state_store(tmp.ds, N, m_dev, coeffs_dev, numeric_flags_dev, s));
     return ADACONS_OK;
 }
 

@@ -1028,6 +1028,43 @@ hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t strea
     return hipGetLastError();
 }
 
+// The carried state of Eq. 11 moved between a caller's array and a state block (the entry point that
+// works in the library's file-scope scratch array keeps no state of its own between calls).
+__global__ void __launch_bounds__(kNMax) state_load_kernel(DevState *ds, int N, const double *__restrict__ m_in) {
+    const int i = threadIdx.x;
+    ds->m[i] = (i < N) ? m_in[i] : 0.0;
+    if (i == 0) {
+        ds->numeric_flags = 0u;
+        ds->blocks_done = 0u;
+    }
+}
+
+__global__ void __launch_bounds__(kNMax)
+state_store_kernel(const DevState *ds, int N, double *__restrict__ m_out, double *__restrict__ coeffs,
+                   unsigned *__restrict__ numeric_flags) {
+    const int i = threadIdx.x;
+    if (i < N) {
+        m_out[i] = ds->m[i];
+        if (coeffs) {
+            coeffs[i] = ds->gamma[i];
+            coeffs[N + i] = ds->a_raw[i];
+            coeffs[2 * N + i] = ds->a_smooth[i];
+        }
+    }
+    if (i == 0 && numeric_flags) *numeric_flags = ds->numeric_flags;
+}
+
+hipError_t launch_state_load(DevState *ds, int N, const double *m_in, hipStream_t stream) {
+    hipLaunchKernelGGL(state_load_kernel, dim3(1), dim3(kNMax), 0, stream, ds, N, m_in);
+    return hipGetLastError();
+}
+
+hipError_t launch_state_store(const DevState *ds, int N, double *m_out, double *coeffs, unsigned *numeric_flags,
+                              hipStream_t stream) {
+    hipLaunchKernelGGL(state_store_kernel, dim3(1), dim3(kNMax), 0, stream, ds, N, m_out, coeffs, numeric_flags);
+    return hipGetLastError();
+}
+
 hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStream_t stream) {
     hipLaunchKernelGGL(coeff_kernel, dim3(1), dim3(kBlock), 0, stream, K, ds, cp);
     return hipGetLastError();

@@ -110,3 +110,18 @@ def test_no_cuda_shims_or_dual_paths():
         text = open(os.path.join(pkg, f)).read()
         for banned in ("__HIP_PLATFORM_AMD__", "__CUDACC__", "cuda_runtime", "hipify"):
             assert banned not in text
+
+
+def test_noalloc_entry_point_rejects_sizes_beyond_its_maximum_before_touching_a_gpu(lib):
+    cdll = ctypes.CDLL(lib.library_path())
+    vp = ctypes.c_void_p
+    cdll.adacons_aggregate_noalloc.argtypes = [vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_double,
+                                               ctypes.c_uint, vp, vp, vp, vp, vp]
+    cdll.adacons_last_error.restype = ctypes.c_char_p
+    EINVAL, EUNSUPPORTED, EALIGN = 1, 2, 3
+    assert cdll.adacons_aggregate_noalloc(None, 129, 10, 0, 0.9, 3, 8, None, None, 16, None) == EUNSUPPORTED
+    assert b"maximum of 128 workers" in cdll.adacons_last_error()
+    assert cdll.adacons_aggregate_noalloc(None, 0, 10, 0, 0.9, 3, 8, None, None, 16, None) == EINVAL
+    assert cdll.adacons_aggregate_noalloc(None, 4, 10, 0, 1.5, 3, 8, None, None, 16, None) == EINVAL
+    assert cdll.adacons_aggregate_noalloc(None, 4, 10, 0, 0.9, 3, None, None, None, 16, None) == EINVAL
+    assert cdll.adacons_aggregate_noalloc(None, 4, 10, 0, 0.9, 3, 12, None, None, 16, None) == EALIGN
