@@ -86,8 +86,8 @@ def main() -> int:
                     help="time the layer-wise entry point instead (C2 or C4): one coefficient set per "
                          "parameter tensor of a ResNet-50; not the headline metric")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
-                    help="gram_blocks_per_cu / wsum_blocks_per_cu / fuse_coeffs / reverse_second_pass / cached_head_mb / "
-                         "mfma_direct_loads / stats_only / wsum_park_kb")
+                    help="gram_blocks_per_cu / wsum_blocks_per_cu / cached_head_mb / gram_products / stats_only / "
+                         "wsum_park_kb")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 "
@@ -115,10 +115,8 @@ def main() -> int:
     agg = ada.AdaCons(w.N, w.d, beta=0.99)
     keys = {"gram_blocks_per_cu": ada.ADACONS_TUNE_GRAM_BLOCKS_PER_CU,
             "wsum_blocks_per_cu": ada.ADACONS_TUNE_WSUM_BLOCKS_PER_CU,
-            "fuse_coeffs": ada.ADACONS_TUNE_FUSE_COEFFS,
-            "reverse_second_pass": ada.ADACONS_TUNE_REVERSE_SECOND_PASS,
             "cached_head_mb": ada.ADACONS_TUNE_CACHED_HEAD_MB,
-            "mfma_direct_loads": ada.ADACONS_TUNE_MFMA_DIRECT_LOADS,
+            "gram_products": ada.ADACONS_TUNE_GRAM_PRODUCTS,
             "stats_only": ada.ADACONS_TUNE_STATS_ONLY,
             "wsum_park_kb": ada.ADACONS_TUNE_WSUM_PARK_KB}
     tuned = {}

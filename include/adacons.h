@@ -143,7 +143,7 @@ adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_
  * hipMalloc.  It calls no hipMalloc, hipFree or other allocating routine.  Stages A1, A2, A3 run with
  * the same kernels and default launch shapes as adacons_aggregate() (results are bit-identical to it);
  * what that call keeps in its state -- the partial sums of stage A1, K, the coefficient block -- lives in
- * a 6 MiB array in the library's device image (one copy per GPU, held until the process ends), and the
+ * a 20 MiB array in the library's device image (one copy per GPU, held until the process ends), and the
  * carried state of the momentum is the caller's:
  *   beta, flags       as in adacons_init_state
  *   m_dev             device pointer, N doubles, 8-byte aligned, read and rewritten: the EMA vector m (sorted
@@ -189,8 +189,8 @@ adacons_status adacons_read_gram(const adacons_state *st, double *K_host, void *
 
 /*
  * Stage A3 alone: out = sum_i gamma_i g_i (Eq. 12) with caller-supplied weights.
- *   gamma_host  host pointer, N doubles (rounded to fp32 for the kernel); copied to the
- *               state's weight buffer on the stream, overwriting the last aggregate's weights
+ *   gamma_host  host pointer, N doubles (rounded to fp32 for the kernel); copied to a buffer of the
+ *               state on the stream; what adacons_coeffs() reports is not touched
  * Other arguments as in adacons_aggregate.  Synchronises the stream once (host weights).
  */
 adacons_status adacons_weighted_sum(const void *G, int N, int64_t d, adacons_dtype dtype,
@@ -207,44 +207,29 @@ adacons_status adacons_state_import(adacons_state *st, const double *m_host, int
                                     void *hip_stream);
 
 /*
- * Tuning knobs (launch shape only; results stay within the documented tolerances, and are
+ * Tuning knobs (launch shape and choice of kernel; results stay within the documented tolerances, and are
  * bit-identical between runs for a fixed setting).  value < 0 restores the default.
  */
 typedef enum {
-    ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0,  /* persistent workgroups per CU in stage A1 */
-    ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1,  /* persistent workgroups per CU in stage A3 */
-    ADACONS_TUNE_FUSE_COEFFS = 2,         /* 1: last workgroup of A1 runs A2 (only with 16-byte aligned rows);
-                                             0 (default): A2 is its own launch */
-    ADACONS_TUNE_REVERSE_SECOND_PASS = 3, /* 1: A3 walks its column tiles backwards; 0 (default): forwards */
-    ADACONS_TUNE_CACHED_HEAD_MB = 4,      /* A1 reads the first `value` MiB of G with cache-allocating loads and
-                                             streams the rest past the caches (non-temporal), so that A3 finds
-                                             the head in the 256 MB memory-side cache.  Default 320; >= 2^20
-                                             means all of G.  For N > 8 the streamed part is used only when
-                                             every row of G starts on a 128-byte line (fp32 on the 128-bit
-                                             path); otherwise those kernels use ordinary loads throughout */
-    ADACONS_TUNE_MFMA_DIRECT_LOADS = 5,   /* A1, N > 8: 1 = matrix-core operands loaded straight from memory;
-                                             0 = workgroup tiles staged through LDS with coalesced loads;
-                                             2 = coalesced loads, per-wavefront transpose through
-                                             LDS; 3 = as 2, with every fp32 product formed from six exact bf16
-                                             products on the sixteen times faster bf16 matrix-core path (fp32
-                                             = sum of three bf16; dropped terms < 2^-24 of the product).
-                                             4 (default) = 3 for N > 32, else 2.  bf16 inputs go to the bf16
-                                             matrix-core instruction as they are (exact products; 3 = 2).
-                                             0 and 1 need 16-byte aligned rows; other inputs take 4 instead */
-    ADACONS_TUNE_STATS_ONLY = 6,          /* 1: for N > 8 stage A1 computes only what Eq. 7 consumes, the diagonal
-                                             of K and its row sums (||g_i||^2 and <g_i, sum_j g_j>: Alg. 1
-                                             steps 1-2), in O(N) operations per column; K itself is then not
-                                             produced and adacons_read_gram() reports ADACONS_EINVAL.  Honoured
-                                             by adacons_aggregate / adacons_aggregate_apply; for N <= 8 the
-                                             Gram kernel runs.  0 (default): full K (N > ADACONS_GRAM_N_MAX
-                                             takes this pass whatever the value) */
-    ADACONS_TUNE_WSUM_PARK_KB = 7,        /* A3 with parked output: one workgroup per CU keeps whole tiles of output
-                                             in LDS and writes them back to back when the space is used up,
-                                             instead of storing tile by tile among the loads (a steady trickle of
-                                             stores costs long read streams 7-13 %).  0: never; 1 (default): where
-                                             it measured faster (fp32, d >= 2^24, and N >= 12 or at least
-                                             1.25 GiB of gradients with N other than 4 and 8), with 128 KB;
-                                             8 .. 144: always, with that many KB of LDS */
+    ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0, /* persistent workgroups per CU in stage A1 (at most 8) */
+    ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1, /* persistent workgroups per CU in stage A3 (at most 8) */
+    ADACONS_TUNE_CACHED_HEAD_MB = 2,     /* A1 reads the first `value` MiB of G with cache-allocating loads and
+                                            streams the rest past the caches, so that A3 finds the head in the
+                                            memory-side cache.  Default 320; >= 2^20 means all of G */
+    ADACONS_TUNE_GRAM_PRODUCTS = 3,      /* A1, 8 < N <= 64, fp32 inputs: 0 = products on the fp32 matrix-core
+                                            instruction; 1 = every product formed from six exact bf16 products on
+                                            the bf16 matrix-core instruction (an fp32 value is the exact sum of
+                                            three bf16 values; dropped terms < 2^-24 of the product); 2 (default)
+                                            = 1 for N > 32, else 0.  bf16 inputs always take the bf16 instruction */
+    ADACONS_TUNE_STATS_ONLY = 4,         /* 1: for N > 8 stage A1 computes only what Eq. 7 consumes, the diagonal
+                                            of K and its row sums (||g_i||^2 and <g_i, sum_j g_j>: Alg. 1 steps
+                                            1-2), in O(N) operations per column; K is then not produced and
+                                            adacons_read_gram() reports ADACONS_EINVAL.  0 (default): full K
+                                            (N > ADACONS_GRAM_N_MAX takes this pass whatever the value) */
+    ADACONS_TUNE_WSUM_PARK_KB = 5,       /* A3 keeps whole tiles of output in LDS and writes them in bursts instead of
+                                            tile by tile among the loads.  0: never; 1 (default): where it measured
+                                            faster (long fp32 streams of many rows); 8 .. 144: always, with that
+                                            many KB of LDS */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);
@@ -302,8 +287,8 @@ adacons_status adacons_worker_scale(void *g, int64_t d, adacons_dtype dtype, con
 
 /*
  * ---- Layer-wise aggregation --------------------------------------------------------------
- * Sec. 4 of the paper computes the aggregation model-wise and notes that layer-wise aggregation
- * performs similarly.  Here the d columns are split into L contiguous segments ("layers"); every
+ * Sec. 4 of the paper computes the aggregation model-wise and mentions the layer-wise variant beside it.
+ * Here the d columns are split into L contiguous segments ("layers"); every
  * layer gets its own Gram matrix, its own coefficients and its own Eq. 11 momentum state, i.e. the
  * steps A1-A3 above run independently on G[:, offsets[l] : offsets[l+1]) for every l, in three
  * launches for all layers together.  For N <= 8 stage A1 forms every layer's
@@ -316,14 +301,14 @@ typedef struct adacons_layers adacons_layers; /* opaque, library-owned */
  * Build the per-layer state (L zero-initialised momentum vectors, tile tables, workspaces) on the
  * current device.  Allocates; synchronises `hip_stream` once.
  *   ls            out: receives the handle
- *   N             workers, 1 <= N <= ADACONS_GRAM_N_MAX
+ *   N             workers, 1 <= N <= ADACONS_N_MAX
  *   L             number of layers, >= 1
  *   offsets_host  host pointer, L + 1 ascending column offsets, offsets[0] = 0, offsets[L] = d;
  *                 empty layers (equal consecutive offsets) are not allowed; d must be at least one
  *                 128-bit group (4 fp32 / 8 bf16 elements)
  *   dtype         element type later calls will pass (fixes the tile geometry)
  *   beta, flags   as in adacons_init_state
- * Errors: EINVAL, EUNSUPPORTED (N > ADACONS_GRAM_N_MAX, unknown dtype), ENOMEM, EHIP.
+ * Errors: EINVAL, EUNSUPPORTED (N > ADACONS_N_MAX, unknown dtype), ENOMEM, EHIP.
  */
 adacons_status adacons_init_layers(adacons_layers **ls, int N, int L, const int64_t *offsets_host,
                                    adacons_dtype dtype, double beta, unsigned flags, void *hip_stream);

@@ -24,12 +24,10 @@ ADACONS_FLAG_INDEX_EMA, ADACONS_FLAG_LAMBDA_EQ13 = 4, 8
 ADACONS_NUM_ZERO_NORM, ADACONS_NUM_NONFINITE, ADACONS_NUM_UNIFORM_FALLBACK = 1, 2, 4
 ADACONS_TUNE_GRAM_BLOCKS_PER_CU = 0
 ADACONS_TUNE_WSUM_BLOCKS_PER_CU = 1
-ADACONS_TUNE_FUSE_COEFFS = 2
-ADACONS_TUNE_REVERSE_SECOND_PASS = 3
-ADACONS_TUNE_CACHED_HEAD_MB = 4
-ADACONS_TUNE_MFMA_DIRECT_LOADS = 5
-ADACONS_TUNE_STATS_ONLY = 6
-ADACONS_TUNE_WSUM_PARK_KB = 7
+ADACONS_TUNE_CACHED_HEAD_MB = 2
+ADACONS_TUNE_GRAM_PRODUCTS = 3
+ADACONS_TUNE_STATS_ONLY = 4
+ADACONS_TUNE_WSUM_PARK_KB = 5
 
 EXPORTS = [
     "adacons_init_state", "adacons_destroy_state", "adacons_reset_state", "adacons_aggregate",

@@ -22,7 +22,7 @@ struct DevState {
     float gamma32[kNMax];    // gamma rounded for the weighted-sum kernel
     unsigned long long step; // number of coefficient updates so far
     unsigned numeric_flags;  // ADACONS_NUM_* of the last update
-    unsigned blocks_done;    // ticket counter of the Gram kernel's last-workgroup tail
+    unsigned pad_;
 };
 static_assert(sizeof(DevState) % sizeof(unsigned) == 0, "DevState is cleared word by word");
 
@@ -32,19 +32,12 @@ struct CoeffParams {
     unsigned flags;
 };
 
-// What a Gram kernel does once its own partial row is written.
-enum GramMode {
-    kGramPartialsOnly = 0,  // a later launch reduces the partial rows
-    kGramFinishK = 1,       // last workgroup reduces the partial rows into K
-    kGramFinishCoeffs = 2   // ... and also runs the coefficient update (stage A2)
-};
-
-struct GramTail {
+// Where stage A1 leaves its results and what stage A2 works on.
+struct GramWork {
     double *partials;  // [rows][N(N+1)/2], one row per workgroup
     double *K;         // [N][N]
     DevState *ds;
     CoeffParams cp;
-    int mode;
 };
 
 __host__ __device__ inline int num_pairs(int N) { return N * (N + 1) / 2; }
@@ -56,13 +49,13 @@ struct LaunchShape {
     int blocks_per_cu;  // <= 0: let the launcher decide
     int max_rows;       // capacity of the partials workspace in rows
     int cached_head_mb; // stage A1: MiB at the head of G read with cache-allocating loads; < 0: all
-    int mfma_direct;    // stage A1, N > 8: value of ADACONS_TUNE_MFMA_DIRECT_LOADS (which matrix-core kernel)
+    int gram_products;  // stage A1, 8 < N <= 64, fp32: value of ADACONS_TUNE_GRAM_PRODUCTS
     int wsum_park_kb;   // stage A3: value of ADACONS_TUNE_WSUM_PARK_KB (LDS for parked output tiles; 0: store tile by tile)
 };
 
 // gram.hip
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
-                       const LaunchShape &shape, const GramTail &want, bool fuse, hipStream_t stream,
+                       const LaunchShape &shape, const GramWork &want, bool with_coeffs, hipStream_t stream,
                        hipEvent_t between = nullptr);  // `between`: recorded after the main Gram kernel
 hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStream_t stream);
 int gram_rows_needed(int N, int num_cu);
@@ -88,7 +81,7 @@ hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, int num_cu, con
 
 // wsum.hip
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
-                       const LaunchShape &shape, const float *gamma, float *out, bool reverse,
-                       hipStream_t stream, bool apply = false, float lr = 0.f);  // apply: out -= lr * sum
+                       const LaunchShape &shape, const float *gamma, float *out, hipStream_t stream,
+                       bool apply = false, float lr = 0.f);  // apply: out -= lr * sum
 
 }  // namespace adacons

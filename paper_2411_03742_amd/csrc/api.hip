@@ -17,7 +17,7 @@ using namespace adacons;
 // partial-sum workspace of stage A1 -- laid out in one file-scope device array.  Every GPU the
 // library runs on holds its own copy at its own address until the process ends; in host code the
 // array's name is only a handle for hipGetSymbolAddress(), never an address to pass on.
-constexpr size_t kScratchBytes = (size_t)6 << 20;   // 6 MiB per GPU
+constexpr size_t kScratchBytes = (size_t)20 << 20;   // 20 MiB per GPU: room for the 1024 partial rows of the N = 64 Gram pass
 constexpr size_t kScratchStateOff = 0;
 constexpr size_t kScratchKOff = (sizeof(DevState) + 255) / 256 * 256;
 constexpr size_t kScratchKBytes = ((size_t)ADACONS_N_MAX * ADACONS_N_MAX + 2 * (size_t)ADACONS_N_MAX) * sizeof(double);
@@ -67,7 +67,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 0, 0, 320, 4, 0, 1};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 320, 2, 0, 1};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 
@@ -112,20 +112,19 @@ LaunchShape shape_of(const adacons_state *st, adacons_tune_key key) {
     s.max_rows = st->max_rows;
     const int head = st->tune[ADACONS_TUNE_CACHED_HEAD_MB];
     s.cached_head_mb = head >= (1 << 20) ? -1 : head;  // a huge value means all of G
-    s.mfma_direct = st->tune[ADACONS_TUNE_MFMA_DIRECT_LOADS];
+    s.gram_products = st->tune[ADACONS_TUNE_GRAM_PRODUCTS];
     s.wsum_park_kb = st->tune[ADACONS_TUNE_WSUM_PARK_KB];
     return s;
 }
 
-GramTail tail_of(adacons_state *st, int mode) {
-    GramTail t;
+GramWork work_of(adacons_state *st) {
+    GramWork t;
     t.partials = st->partials;
     t.K = st->K;
     t.ds = st->ds;
     t.cp.N = st->N;
     t.cp.beta = st->beta;
     t.cp.flags = st->flags;
-    t.mode = mode;
     return t;
 }
 
@@ -135,12 +134,10 @@ hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d,
     const LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
     if ((st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8) || N > ADACONS_GRAM_N_MAX) {
         st->k_valid = false;
-        const GramTail t = tail_of(st, kGramFinishCoeffs);
-        return launch_stats(G, N, d, dtype, vec_ok, shape, st->partials, st->ds, t.cp, s, between);
+        return launch_stats(G, N, d, dtype, vec_ok, shape, st->partials, st->ds, work_of(st).cp, s, between);
     }
     st->k_valid = true;
-    return launch_gram(G, N, d, dtype, vec_ok, shape, tail_of(st, kGramFinishCoeffs),
-                       st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0, s, between);
+    return launch_gram(G, N, d, dtype, vec_ok, shape, work_of(st), true, s, between);
 }
 
 
@@ -239,7 +236,9 @@ adacons_status adacons_init_state(adacons_state **out_st, int N, int64_t d_max, 
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&st->ds), sizeof(DevState));
     const size_t row_doubles = partial_row_doubles(N);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->partials), (size_t)st->max_rows * row_doubles * sizeof(double));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->K), ((size_t)N * N + 2 * (size_t)N) * sizeof(double));
+    // K, then q and r of adacons_update_from_stats (2 N doubles), then the caller's weights of
+    // adacons_weighted_sum as fp32 (N floats)
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&st->K), ((size_t)N * N + 3 * (size_t)N) * sizeof(double));
     if (e == hipSuccess) e = launch_clear_state(st->ds, st->K, N * N, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
@@ -280,8 +279,7 @@ adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype 
     if (prof) HIP_TRY(hipEventRecord(ev[0], s));
     HIP_TRY(launch_first_pass(st, G, N, d, dtype, vec_ok, s, prof ? ev[1] : nullptr));
     if (prof) HIP_TRY(hipEventRecord(ev[2], s));
-    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out,
-                        st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s));
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out, s));
     if (prof) {
         HIP_TRY(hipEventRecord(ev[3], s));
         st->prof_calls += 1;
@@ -297,8 +295,7 @@ adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_
     if (!std::isfinite(lr)) return fail(ADACONS_EINVAL, "lr is not finite");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     HIP_TRY(launch_first_pass(st, G, N, d, dtype, vec_ok, s, nullptr));
-    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, w,
-                        st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s, true, lr));
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, w, s, true, lr));
     return ADACONS_OK;
 }
 
@@ -366,8 +363,7 @@ adacons_status adacons_gram(const void *G, int N, int64_t d, adacons_dtype dtype
     if (N > ADACONS_GRAM_N_MAX)
         return fail(ADACONS_EUNSUPPORTED, "K is formed for N <= %d only (N=%d)", ADACONS_GRAM_N_MAX, N);
     st->k_valid = true;
-    HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU),
-                        tail_of(st, kGramFinishK), st->tune[ADACONS_TUNE_FUSE_COEFFS] != 0,
+    HIP_TRY(launch_gram(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU), work_of(st), false,
                         static_cast<hipStream_t>(hip_stream)));
     return ADACONS_OK;
 }
@@ -391,11 +387,11 @@ adacons_status adacons_weighted_sum(const void *G, int N, int64_t d, adacons_dty
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     float g32[kNMax];
     for (int i = 0; i < N; ++i) g32[i] = (float)gamma_host[i];
-    HIP_TRY(hipMemcpyAsync(st->ds->gamma, gamma_host, (size_t)N * sizeof(double), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(st->ds->gamma32, g32, (size_t)N * sizeof(float), hipMemcpyHostToDevice, s));
+    // the caller's weights get a buffer of their own: what adacons_coeffs() reports stays the last aggregation's
+    float *user_gamma = reinterpret_cast<float *>(st->K + (size_t)N * N + 2 * (size_t)N);
+    HIP_TRY(hipMemcpyAsync(user_gamma, g32, (size_t)N * sizeof(float), hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));  // g32 lives on this frame
-    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out,
-                        st->tune[ADACONS_TUNE_REVERSE_SECOND_PASS] != 0, s));
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), user_gamma, out, s));
     return ADACONS_OK;
 }
 
@@ -429,6 +425,7 @@ adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value) 
     if (value < 0) value = kTuneDefault[key];
     if ((key == ADACONS_TUNE_GRAM_BLOCKS_PER_CU || key == ADACONS_TUNE_WSUM_BLOCKS_PER_CU) && value > 8)
         return fail(ADACONS_EINVAL, "at most 8 workgroups per CU");
+    if (key == ADACONS_TUNE_GRAM_PRODUCTS && value > 2) return fail(ADACONS_EINVAL, "ADACONS_TUNE_GRAM_PRODUCTS takes 0, 1 or 2");
     if (key == ADACONS_TUNE_WSUM_PARK_KB && value != 0 && value != 1 && (value < 8 || value > 144))
         return fail(ADACONS_EINVAL, "ADACONS_TUNE_WSUM_PARK_KB takes 0, 1 or 8..144");
     st->tune[key] = value;
@@ -520,8 +517,7 @@ adacons_status adacons_aggregate_noalloc(const void *G, int N, int64_t d, adacon
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     HIP_TRY(launch_state_load(tmp.ds, N, m_dev, s));
     HIP_TRY(launch_first_pass(&tmp, G, N, d, dtype, vec_ok, s, nullptr));
-    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(&tmp, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), tmp.ds->gamma32, out,
-                        false, s));
+    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(&tmp, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), tmp.ds->gamma32, out, s));
     HIP_TRY(launch_state_store(tmp.ds, N, m_dev, coeffs_dev, numeric_flags_dev, s));
     return ADACONS_OK;
 }

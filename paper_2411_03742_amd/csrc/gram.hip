@@ -1,18 +1,20 @@
 // Stage A1 (K = G G^T) and stage A2 (coefficients, sorted momentum, normalisation).
 //
 // A1 computes every inner product <g_i, g_j> of Eq. 7 (third line) / the double sum of Eq. 8
-// in one pass over G.  Two kernels:
-//   gram_vec_kernel   N <= 8: one thread owns VEC consecutive columns of all N rows
-//                     (N 128-bit loads in flight) and keeps the N(N+1)/2 sums in fp64 registers.
-//   gram_mfma_kernel  8 < N <= 64: rows grouped in tiles of 16; one wavefront feeds
-//                     v_mfma_f32_16x16x4_f32 with the same registers as A and B operand
-//                     (K is G times its own transpose), fp32 tile accumulators flushed into
-//                     fp64 every kFlush steps.
-// Both are persistent grids; every workgroup writes one row of partial sums, there are no
+// in one pass over G:
+//   gram_vec_kernel         N <= 8: one thread owns VEC consecutive columns of all N rows
+//                           (N 128-bit loads in flight) and keeps the N(N+1)/2 sums in fp64 registers.
+//   gram_mfma_wave_kernel   8 < N <= 64: rows grouped in tiles of 16; a wavefront loads a chunk of all
+//                           rows with coalesced instructions, transposes it through its own LDS slice
+//                           and feeds the matrix cores with the same registers as A and B operand
+//                           (K is G times its own transpose); fp32 tile sums flushed into fp64.
+//   gram_mfma_split_coop_kernel  fp32 inputs with every product formed from six exact bf16 products,
+//                           two wavefronts sharing a chunk (default for N > 32).
+// All are persistent grids; every workgroup writes one row of partial sums, there are no
 // floating-point atomics, and the rows are added in a fixed order, so results are
 // bit-identical from run to run for a given launch shape.
 //
-// A2 is a single workgroup (the last one of A1 to finish, or a launch of its own).
+// A2 is a single workgroup launched between the two streaming passes.
 #include "adacons_internal.h"
 #include "coeff_device.h"
 #include "device_util.h"
@@ -63,35 +65,20 @@ __device__ void reduce_partial_rows(const double *partials, int nrows, int N, do
     __syncthreads();
 }
 
-// Called by every workgroup of a Gram kernel after its partial row is stored.  The workgroup
-// that takes the last ticket reduces all rows (and runs A2 when asked).  No workgroup waits for
-// another: every wave reaches the end of the kernel.
-__device__ void gram_tail(const GramTail &tail, double *lds) {
-    if (tail.mode == kGramPartialsOnly) return;
-    __shared__ unsigned s_ticket;
-    __threadfence();  // release: this workgroup's partial row is visible device-wide
-    __syncthreads();
-    if (threadIdx.x == 0) s_ticket = atomicAdd(&tail.ds->blocks_done, 1u);
-    __syncthreads();
-    if (s_ticket != gridDim.x - 1) return;
-    __threadfence();  // acquire: see every other workgroup's row
-    const double m_old = ((int)threadIdx.x < tail.cp.N) ? tail.ds->m[threadIdx.x] : 0.0;
-    reduce_partial_rows(tail.partials, (int)gridDim.x, tail.cp.N, tail.K, lds);
-    if (tail.mode == kGramFinishCoeffs) update_coefficients(tail.K, tail.ds, tail.cp, lds, m_old);
-    if (threadIdx.x == 0) tail.ds->blocks_done = 0;  // ready for the next launch on this stream
-}
-
 // Reduction of the partial rows as a launch of its own (large N: more pairs than one workgroup
-// has threads).  Workgroup c owns pairs [64 c, 64 c + 64); four interleaved sub-sums per pair.
+// has threads).  Workgroup c owns pairs [16 c, 16 c + 16); sixteen interleaved sub-sums per pair
+// (rows s, s + 16, ...), added in slice order.
+constexpr int kReducePairs = 16, kReduceSlices = kBlock / kReducePairs;
 __global__ void __launch_bounds__(kBlock) reduce_kernel(const double *partials, int nrows, int N, double *K) {
     __shared__ double lds[kBlock];
     const int np = num_pairs(N);
-    const int pl = threadIdx.x & 63, s = threadIdx.x >> 6;
-    const int p = blockIdx.x * 64 + pl;
-    lds[s * 64 + pl] = (p < np) ? sum_rows(partials, np, p, s, 4, nrows) : 0.0;
+    const int pl = threadIdx.x % kReducePairs, s = threadIdx.x / kReducePairs;
+    const int p = blockIdx.x * kReducePairs + pl;
+    lds[s * kReducePairs + pl] = (p < np) ? sum_rows(partials, np, p, s, kReduceSlices, nrows) : 0.0;
     __syncthreads();
     if (s == 0 && p < np) {
-        const double tot = ((lds[pl] + lds[64 + pl]) + lds[128 + pl]) + lds[192 + pl];
+        double tot = 0.0;
+        for (int q = 0; q < kReduceSlices; ++q) tot += lds[q * kReducePairs + pl];
         int i, j;
         unpack_pair(p, N, i, j);
         K[(size_t)i * N + j] = tot;
@@ -166,7 +153,8 @@ __device__ __forceinline__ void gram_vec_step(const T *__restrict__ G, int64_t d
 
 template <int N, typename T, int VEC>
 __global__ void __launch_bounds__(kBlock, 2)
-gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cached_groups, GramTail tail) {
+gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cached_groups,
+                double *__restrict__ partials) {
     constexpr int NP = N * (N + 1) / 2;
     __shared__ double lds[(4 * NP > kBlock) ? 4 * NP : kBlock];
     double acc[NP];
@@ -193,10 +181,8 @@ gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cac
     __syncthreads();
     if (threadIdx.x < NP) {
         const int p = threadIdx.x;
-        tail.partials[(size_t)blockIdx.x * NP + p] = ((lds[p] + lds[NP + p]) + lds[2 * NP + p]) + lds[3 * NP + p];
+        partials[(size_t)blockIdx.x * NP + p] = ((lds[p] + lds[NP + p]) + lds[2 * NP + p]) + lds[3 * NP + p];
     }
-    __syncthreads();
-    gram_tail(tail, lds);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -214,7 +200,6 @@ gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cac
 // accumulation rounds with a small systematic bias (measured ~2e-7 relative on a sum of squares
 // after 128 products, ~4e-7 after 256), so the fp32 chains are kept to 8 steps = 128 products.
 constexpr int kFlush = 8;
-constexpr int kUnits = 4;   // 16-column steps a wavefront loads back to back (one chunk)
 
 // Block-level end of an MFMA Gram kernel: add the four wavefronts' tile sums in order through LDS
 // (lds[(p * 4 + r) * 64 + lane], NT(NT+1)/2 * 256 doubles) and scatter them into this workgroup's
@@ -250,247 +235,6 @@ __device__ __forceinline__ void mfma_store_partial_row(const double (&acc64)[NT 
         if (i < N && j < N && i <= j) row_out[pair_index(i, j, N)] = lds[e];
     }
 }
-
-// Load one chunk (kUnits * 16 columns of all NT row tiles) in operand layout.  Rows >= N and
-// columns >= d count as zero: the load itself goes to a clamped (valid) address and the value is
-// replaced afterwards, so that the loads stay free of branches and the waits on them exact.
-// STREAM: non-temporal loads.
-template <int NT, typename T, bool STREAM>
-__device__ __forceinline__ void mfma_load_chunk(const T *__restrict__ G, int N, int64_t d, int64_t ch, int r16,
-                                                int kq, float (&v)[kUnits][NT][4]) {
-#pragma unroll
-    for (int u = 0; u < kUnits; ++u) {
-        const int64_t col = (ch * kUnits + u) * 16 + kq * 4;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int row = t * 16 + r16;
-            const int rowc = row < N ? row : N - 1;
-            // d is a multiple of the vector width here (>= 4 for fp32, >= 8 for bf16)
-            const bool live = row < N && col < d;
-            const int64_t colc = col < d ? col : d - 4;
-            const T *p = G + (int64_t)rowc * d + colc;
-            float w[4];
-            if constexpr (sizeof(T) == 4) {
-                load_vec<float, 4, STREAM>(reinterpret_cast<const float *>(p), w);
-            } else {
-                // 4 bf16 = one 64-bit load
-                typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-                const u32x2 *q = reinterpret_cast<const u32x2 *>(p);
-                u32x2 x;
-                if constexpr (STREAM) x = __builtin_nontemporal_load(q); else x = *q;
-                w[0] = __uint_as_float(x.x << 16);
-                w[1] = __uint_as_float(x.x & 0xffff0000u);
-                w[2] = __uint_as_float(x.y << 16);
-                w[3] = __uint_as_float(x.y & 0xffff0000u);
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) v[u][t][c] = live ? w[c] : 0.f;
-        }
-    }
-}
-
-// STREAM selects non-temporal loads (kept for measurement; the launcher uses ordinary loads).
-// The next chunk's loads are issued before the current chunk's MFMAs, so that the matrix
-// cores and the memory pipeline work at the same time even with one wavefront per SIMD.
-template <int NT, typename T, bool STREAM>
-__global__ void __launch_bounds__(kBlock, (NT >= 3) ? 1 : 2)
-gram_mfma_kernel(const T *__restrict__ G, int N, int64_t d, int64_t nchunks, GramTail tail) {
-    constexpr int NPT = NT * (NT + 1) / 2;
-    __shared__ double lds[(NPT * 256 > kBlock) ? NPT * 256 : kBlock];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int r16 = lane & 15, kq = lane >> 4;
-
-    f32x4 acc32[NPT];
-    double acc64[NPT][4];
-#pragma unroll
-    for (int p = 0; p < NPT; ++p) {
-        acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
-    }
-
-    // a chunk = kUnits * 16 consecutive columns, taken by one wavefront
-    const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
-    int since_flush = 0;
-    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
-    int64_t ch = (int64_t)slot * (kBlock / kWave) + wave;
-    float cur[kUnits][NT][4], nxt[kUnits][NT][4];
-    if (ch < nchunks) mfma_load_chunk<NT, T, STREAM>(G, N, d, ch, r16, kq, cur);
-    while (ch < nchunks) {
-        const int64_t chn = ch + wstride;
-        // past the end the last chunk is simply loaded again (in bounds, never used)
-        mfma_load_chunk<NT, T, STREAM>(G, N, d, chn < nchunks ? chn : nchunks - 1, r16, kq, nxt);
-#pragma unroll
-        for (int u = 0; u < kUnits; ++u) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                int p = 0;
-#pragma unroll
-                for (int I = 0; I < NT; ++I)
-#pragma unroll
-                    for (int J = I; J < NT; ++J) {
-                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur[u][I][c], cur[u][J][c], acc32[p], 0, 0, 0);
-                        ++p;
-                    }
-            }
-        }
-        since_flush += kUnits;
-        if (since_flush >= kFlush) {
-            since_flush = 0;
-#pragma unroll
-            for (int p = 0; p < NPT; ++p) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
-                acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnits; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) cur[u][t][c] = nxt[u][t][c];
-        ch = chn;
-    }
-#pragma unroll
-    for (int p = 0; p < NPT; ++p)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
-
-    mfma_store_partial_row<NT>(acc64, lds, N, tail.partials + (size_t)blockIdx.x * num_pairs(N));
-    __syncthreads();
-    gram_tail(tail, lds);
-}
-
-
-// ------------------------------------------------------------------------------------------
-// A1, 8 < N <= 64, 128-bit path: tiles staged through LDS
-// ------------------------------------------------------------------------------------------
-// The direct kernel above touches 16 rows with every load instruction and cycles through all
-// 16 NT rows sixteen times per 64 columns; with rows ~100 MB apart that thrashes the per-CU
-// address-translation cache (measured at N = 64: one miss per four requests).  Here the
-// workgroup stages a tile of 16 NT rows x kSegs KB per row in LDS: every load instruction reads
-// 1 KB of ONE row, fully coalesced, and each row is visited once per tile.  Then each wavefront
-// takes a quarter of the tile's columns and feeds the matrix cores from LDS (ds_read in operand
-// layout).  The 16-byte chunks of a tile row are XOR-swizzled with the row number so that the
-// column-wise operand reads hit distinct banks.  The next tile's global loads are in flight
-// while the current tile is multiplied.
-template <int NT> struct LdsTileShape {
-    static constexpr int kRows = 16 * NT;
-    static constexpr int kSegs = (NT == 1) ? 4 : (NT == 2) ? 2 : 1;   // 1 KB segments per tile row
-    static constexpr int kLoads = kRows * kSegs / (kBlock / kWave);   // load instructions per wavefront
-    static constexpr int kRowBytes = kSegs * 1024;
-    static constexpr int kTileBytes = kRows * kRowBytes;              // <= 64 KB
-};
-
-template <int NT, typename T>
-__global__ void __launch_bounds__(kBlock, (NT >= 4) ? 1 : 2)
-gram_mfma_lds_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ntiles, double *__restrict__ partials) {
-    typedef LdsTileShape<NT> S;
-    constexpr int NPT = NT * (NT + 1) / 2;
-    constexpr int kVec = 16 / (int)sizeof(T);                 // elements per 16-byte chunk
-    constexpr int kTileCols = S::kRowBytes / (int)sizeof(T);  // columns per tile
-    constexpr int kUnitsPerWave = kTileCols / 64;             // 16-column MFMA steps per wavefront and tile
-    static_assert(NPT * 256 * 8 <= S::kTileBytes, "the final reduction reuses the tile buffer");
-    __shared__ __attribute__((aligned(16))) unsigned char tile[S::kTileBytes];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int r16 = lane & 15, kq = lane >> 4;
-
-    f32x4 acc32[NPT];
-    double acc64[NPT][4];
-#pragma unroll
-    for (int p = 0; p < NPT; ++p) {
-        acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
-    }
-
-    // stage registers: load j of this wavefront covers tile row (wave * kLoads + j) / kSegs,
-    // segment (wave * kLoads + j) % kSegs, bytes [16 lane, 16 lane + 16) of that segment
-    u32x4 stage[S::kLoads];
-    auto load_tile = [&](int64_t t) {
-#pragma unroll
-        for (int j = 0; j < S::kLoads; ++j) {
-            const int idx = wave * S::kLoads + j;
-            const int row = idx / S::kSegs, seg = idx % S::kSegs;
-            const int64_t col = t * kTileCols + (int64_t)seg * (1024 / (int)sizeof(T)) + lane * kVec;
-            const bool live = row < N && col < d;   // d is a multiple of kVec on this path
-            const int rowc = row < N ? row : N - 1;
-            const int64_t colc = col < d ? col : d - kVec;
-            const u32x4 x = *reinterpret_cast<const u32x4 *>(G + (int64_t)rowc * d + colc);
-            stage[j] = live ? x : u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-
-    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
-    int64_t t = slot;
-    int since_flush = 0;
-    if (t < ntiles) load_tile(t);
-    while (t < ntiles) {   // t is uniform over the workgroup: every thread takes the same trips
-#pragma unroll
-        for (int j = 0; j < S::kLoads; ++j) {
-            const int idx = wave * S::kLoads + j;
-            const int row = idx / S::kSegs, seg = idx % S::kSegs;
-            const int chunk = (seg * 64 + lane) ^ (row & 15);
-            *reinterpret_cast<u32x4 *>(tile + row * S::kRowBytes + chunk * 16) = stage[j];
-        }
-        __syncthreads();
-        const int64_t tn = t + gridDim.x;
-        load_tile(tn < ntiles ? tn : ntiles - 1);   // past the end: the last tile again, never used
-
-#pragma unroll
-        for (int u = 0; u < kUnitsPerWave; ++u) {
-            float v[NT][4];
-            const int col = wave * (kTileCols / 4) + u * 16 + kq * 4;   // first of this lane's 4 columns
-#pragma unroll
-            for (int tt = 0; tt < NT; ++tt) {
-                const int row = tt * 16 + r16;
-                const int byte = col * (int)sizeof(T);
-                const int chunk = (byte >> 4) ^ (row & 15);
-                const unsigned char *src = tile + row * S::kRowBytes + chunk * 16 + (byte & 15);
-                if constexpr (sizeof(T) == 4) {
-                    const f32x4 x = *reinterpret_cast<const f32x4 *>(src);
-                    v[tt][0] = x.x; v[tt][1] = x.y; v[tt][2] = x.z; v[tt][3] = x.w;
-                } else {
-                    const uint2 x = *reinterpret_cast<const uint2 *>(src);
-                    v[tt][0] = __uint_as_float(x.x << 16);
-                    v[tt][1] = __uint_as_float(x.x & 0xffff0000u);
-                    v[tt][2] = __uint_as_float(x.y << 16);
-                    v[tt][3] = __uint_as_float(x.y & 0xffff0000u);
-                }
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                int p = 0;
-#pragma unroll
-                for (int I = 0; I < NT; ++I)
-#pragma unroll
-                    for (int J = I; J < NT; ++J) {
-                        acc32[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[I][c], v[J][c], acc32[p], 0, 0, 0);
-                        ++p;
-                    }
-            }
-            if (++since_flush == kFlush) {
-                since_flush = 0;
-#pragma unroll
-                for (int p = 0; p < NPT; ++p) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
-                    acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-            }
-        }
-        __syncthreads();   // all operand reads done before the tile buffer is overwritten
-        t = tn;
-    }
-#pragma unroll
-    for (int p = 0; p < NPT; ++p)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
-    mfma_store_partial_row<NT>(acc64, reinterpret_cast<double *>(tile), N,
-                               partials + (size_t)blockIdx.x * num_pairs(N));
-}
-
 
 // ------------------------------------------------------------------------------------------
 // A1, 8 < N <= 64, fp32, 128-bit path: coalesced loads, per-wavefront transpose through LDS
@@ -640,49 +384,73 @@ gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, 
 }
 
 // ------------------------------------------------------------------------------------------
-// A1, 8 < N <= 64, fp32, 128-bit path: products on the bf16 matrix-core path, fp32-exact by splitting
+// A1, 8 < N <= 64, fp32: products on the bf16 matrix-core path, fp32-exact by splitting
 // ------------------------------------------------------------------------------------------
 // The fp32 matrix-core instruction multiplies 32 element pairs per cycle and SIMD; the bf16 one
 // sixteen times as many.  An fp32 value is the exact sum of three bf16 values, x = h + m + l
 // (8 significant bits each, by truncation: h = top half of x's bits, m = top half of x - h,
 // l = x - h - m), so x y = hh + (hm + mh) + (hl + lh + mm) + terms below 2^-24 |x y|: six bf16
-// products, each exact, replace one fp32 product at 2.7 times the rate.  The wavefront loads its
-// 64-column chunk as in gram_mfma_wave_kernel, splits it in registers and parks the three planes
-// in its own LDS slice (rows of 64 bf16 = 128 B, 16-byte pieces XOR-swizzled with the row number);
-// operands for v_mfma_f32_16x16x32_bf16 (lane l: row l % 16, columns 8 (l / 16) .. + 7 of a 32-column
-// half) are read back with one 128-bit LDS load each.  Sums stay in fp32 inside the instruction;
-// the tile sums are flushed into fp64 registers every two chunks, as in the fp32 kernels.
+// products, each exact, replace one fp32 product at 2.7 times the rate.  A chunk of 64 columns of all
+// rows is loaded as in gram_mfma_wave_kernel (4 rows x 256 B per instruction), split in registers, and
+// its three planes are parked in LDS (rows of 64 bf16 = 128 B, 16-byte pieces XOR-swizzled with the row
+// number); operands for v_mfma_f32_16x16x32_bf16 (lane l: row l % 16, columns 8 (l / 16) .. + 7 of a
+// 32-column half) are read back with one 128-bit LDS load each.  Sums stay in fp32 inside the
+// instruction; the tile sums are flushed into fp64 registers every two chunks, as in the fp32 kernel.
+//
+// A workgroup of W = 2 wavefronts shares one chunk: each loads, splits and parks half of the rows, and
+// each owns half of the tile pairs -- half of the accumulators and operands (176 registers at N = 64
+// where one wavefront with all ten tile pairs needs about 300), so two wavefronts fit a SIMD, four
+// workgroups a CU, and one wavefront's vector work (the split) overlaps another's matrix-core work.
+// Two workgroup barriers per chunk (planes complete / planes free again).  The tile pairs of the
+// wavefronts are disjoint, so each scatters its own sums into the workgroup's partial row without a
+// reduction between them.  Measured on N = 64, d = 25,557,032: 1.06 ms against 1.12 ms for one
+// wavefront per chunk; four wavefronts per chunk (110 registers, sixteen wavefronts per CU) 1.18 ms, six
+// workgroups of two per CU 1.15 ms.
 
-template <int NT>
-__global__ void __launch_bounds__(kBlock, (NT >= 3) ? 1 : 2)
-gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks,
-                       int64_t cached_chunks, double *__restrict__ partials) {
-    constexpr int NPT = NT * (NT + 1) / 2;
-    constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
+// Which of the two wavefronts owns tile pair p (pairs in row-major upper-triangle order): the first
+// half of the pairs, which share the first row tiles, and the second half.
+__host__ __device__ constexpr int coop_role(int NT, int W, int p) { return p < (NT * (NT + 1) / 2 + W - 1) / W ? 0 : 1; }
+__host__ __device__ constexpr int coop_local(int NT, int W, int p) {   // index of pair p among its owner's pairs
+    int n = 0;
+    for (int q = 0; q < p; ++q) n += coop_role(NT, W, q) == coop_role(NT, W, p) ? 1 : 0;
+    return n;
+}
+__host__ __device__ constexpr int coop_max_pairs(int NT, int W) {
+    int best = 0;
+    for (int p = 0; p < NT * (NT + 1) / 2; ++p) best = coop_local(NT, W, p) + 1 > best ? coop_local(NT, W, p) + 1 : best;
+    return best;
+}
+
+template <int NT, int W>
+__global__ void __launch_bounds__(W * kWave, 2)
+gram_mfma_split_coop_kernel(const float *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks,
+                            int64_t cached_chunks, double *__restrict__ partials) {
+    constexpr int NPW = coop_max_pairs(NT, W);                // tile pairs per wavefront at most
+    constexpr int kRows = 16 * NT;
+    constexpr int kLoads = 4 * NT;                            // load instructions per chunk (4 rows each) ...
+    constexpr int kLoadsW = kLoads / W;                       // ... per wavefront
+    static_assert(W == 2 && kLoads % W == 0, "two wavefronts, the rows split evenly over them");
     constexpr int kPlaneBytes = kRows * 128;                  // kRows x 64 bf16
-    constexpr int kSliceBytes = 3 * kPlaneBytes;              // h, m, l of one wavefront's chunk
-    static_assert(NPT * 256 * 8 <= 4 * kSliceBytes, "the final reduction reuses the slices");
-    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * kSliceBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char planes[3 * kPlaneBytes];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int r16 = lane & 15, kq = lane >> 4;
-    unsigned char *slice = lds_raw + wave * kSliceBytes;
 
-    f32x4 acc32[NPT];
-    double acc64[NPT][4];
+    f32x4 acc32[NPW];
+    double acc64[NPW][4];
 #pragma unroll
-    for (int p = 0; p < NPT; ++p) {
+    for (int p = 0; p < NPW; ++p) {
         acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc64[p][r] = 0.0;
     }
 
-    // load j of a chunk: row 4 j + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
-    f32x4 stage[kLoads];
+    // load j of this wavefront: row 4 (wave kLoadsW + j) + lane / 16, columns chunk * 64 + 4 (lane % 16) .. + 3
+    f32x4 stage[kLoadsW];
     // interior: every row exists (N = 16 NT) and the chunk lies inside d, so no clamp and no zero-fill
-    auto load_chunk_as = [&](int64_t ch, auto stream, auto interior) __attribute__((always_inline)) {
+    auto load_chunk = [&](int64_t ch, auto stream, auto interior) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            const int row = 4 * j + (lane >> 4);
+        for (int j = 0; j < kLoadsW; ++j) {
+            const int row = 4 * (wave * kLoadsW + j) + (lane >> 4);
             const int64_t col = ch * 64 + (lane & 15) * 4;
             if constexpr (decltype(interior)::value) {
                 const gf32x4 *src = reinterpret_cast<const gf32x4 *>(G + (int64_t)row * d + col);
@@ -701,20 +469,65 @@ gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t dc
         }
     };
     const int64_t full_chunks = (N == kRows) ? dcols / 64 : 0;   // chunks below this index are interior
-    auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
-        if (ch < full_chunks) load_chunk_as(ch, stream, std::true_type{});
-        else load_chunk_as(ch, stream, std::false_type{});
-    };
 
-    const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
-    const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
-    int64_t ch = (int64_t)slot * (kBlock / kWave) + wave;
+    const int64_t stride = (int64_t)gridDim.x;
+    int64_t ch = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);   // uniform over the workgroup
     int since_flush = 0;
-    auto step = [&](auto stream) __attribute__((always_inline)) {
-        // split into three bf16 planes and park them
+    // the products of the tile pairs wavefront ROLE owns for one 32-column half; operand tiles that none of
+    // its pairs touch are not read
+    auto multiply = [&](auto role, int u) __attribute__((always_inline)) {
+        constexpr int ROLE = decltype(role)::value;
+        bf16x8 op[3][NT];
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            const int row = 4 * j + (lane >> 4), cl = lane & 15;
+        for (int t = 0; t < NT; ++t) {
+            bool used = false;
+            int p = 0;
+#pragma unroll
+            for (int I = 0; I < NT; ++I)
+#pragma unroll
+                for (int J = I; J < NT; ++J) {
+                    if (coop_role(NT, W, p) == ROLE && (I == t || J == t)) used = true;
+                    ++p;
+                }
+            if (used) {
+                const int row = t * 16 + r16;
+                const int piece = (u * 4 + kq) ^ (row & 7);
+#pragma unroll
+                for (int P = 0; P < 3; ++P)
+                    op[P][t] = *reinterpret_cast<const bf16x8 *>(planes + P * kPlaneBytes + row * 128 + piece * 16);
+            }
+        }
+        // term by term across the pairs, so that consecutive instructions write different accumulators;
+        // per pair the smallest terms first
+        auto term = [&](auto a, auto b) __attribute__((always_inline)) {
+            int p = 0;
+#pragma unroll
+            for (int I = 0; I < NT; ++I)
+#pragma unroll
+                for (int J = I; J < NT; ++J) {
+                    if (coop_role(NT, W, p) == ROLE) {
+                        const int q = coop_local(NT, W, p);
+                        acc32[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[decltype(a)::value][I], op[decltype(b)::value][J],
+                                                                           acc32[q], 0, 0, 0);
+                    }
+                    ++p;
+                }
+        };
+        using P_h = std::integral_constant<int, 0>;
+        using P_m = std::integral_constant<int, 1>;
+        using P_l = std::integral_constant<int, 2>;
+        term(P_m{}, P_m{});
+        term(P_h{}, P_l{});
+        term(P_l{}, P_h{});
+        term(P_h{}, P_m{});
+        term(P_m{}, P_h{});
+        term(P_h{}, P_h{});
+    };
+    auto step = [&](auto stream, auto interior_next) __attribute__((always_inline)) {
+        // split this wavefront's rows into three bf16 planes and park them
+#pragma unroll
+        for (int j = 0; j < kLoadsW; ++j) {
+            const int row = 4 * (wave * kLoadsW + j) + (lane >> 4), cl = lane & 15;
             unsigned hb[4], mb[4], lb[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -730,62 +543,68 @@ gram_mfma_split_kernel(const float *__restrict__ G, int N, int64_t d, int64_t dc
             const u32x2 ph = {__builtin_amdgcn_perm(hb[1], hb[0], 0x07060302u), __builtin_amdgcn_perm(hb[3], hb[2], 0x07060302u)};
             const u32x2 pm = {__builtin_amdgcn_perm(mb[1], mb[0], 0x07060302u), __builtin_amdgcn_perm(mb[3], mb[2], 0x07060302u)};
             const u32x2 pl = {__builtin_amdgcn_perm(lb[1], lb[0], 0x07060302u), __builtin_amdgcn_perm(lb[3], lb[2], 0x07060302u)};
-            *reinterpret_cast<u32x2 *>(slice + off) = ph;
-            *reinterpret_cast<u32x2 *>(slice + kPlaneBytes + off) = pm;
-            *reinterpret_cast<u32x2 *>(slice + 2 * kPlaneBytes + off) = pl;
+            *reinterpret_cast<u32x2 *>(planes + off) = ph;
+            *reinterpret_cast<u32x2 *>(planes + kPlaneBytes + off) = pm;
+            *reinterpret_cast<u32x2 *>(planes + 2 * kPlaneBytes + off) = pl;
         }
-        const int64_t chn = ch + wstride;
-        load_chunk(chn < nchunks ? chn : nchunks - 1, stream);   // past the end: the last chunk again, never used
+        __syncthreads();   // every wavefront's share of the planes is in place
+        const int64_t chn = ch + stride;
+        load_chunk(chn < nchunks ? chn : nchunks - 1, stream, interior_next);   // past the end: the last chunk again, never used
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            bf16x8 op[3][NT];
-#pragma unroll
-            for (int P = 0; P < 3; ++P)
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const int row = t * 16 + r16;
-                    const int piece = (u * 4 + kq) ^ (row & 7);
-                    op[P][t] = *reinterpret_cast<const bf16x8 *>(slice + P * kPlaneBytes + row * 128 + piece * 16);
-                }
-            int p = 0;
-#pragma unroll
-            for (int I = 0; I < NT; ++I)
-#pragma unroll
-                for (int J = I; J < NT; ++J) {
-                    f32x4 a = acc32[p];
-                    // smallest terms first
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[1][I], op[1][J], a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[0][I], op[2][J], a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[2][I], op[0][J], a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[0][I], op[1][J], a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[1][I], op[0][J], a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[0][I], op[0][J], a, 0, 0, 0);
-                    acc32[p] = a;
-                    ++p;
-                }
+            if (wave == 0) multiply(std::integral_constant<int, 0>{}, u);
+            else multiply(std::integral_constant<int, 1>{}, u);
         }
         since_flush += 4;
         if (since_flush >= kFlush) {
             since_flush = 0;
 #pragma unroll
-            for (int p = 0; p < NPT; ++p) {
+            for (int p = 0; p < NPW; ++p) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
                 acc32[p] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         }
+        __syncthreads();   // every wavefront has read its operands: the planes may be overwritten
         ch = chn;
     };
-    if (ch < nchunks) load_chunk(ch, std::false_type{});
-    while (ch < nchunks && ch + wstride < cached_chunks) step(std::false_type{});
-    while (ch < nchunks) step(std::true_type{});
+    if (ch < nchunks) load_chunk(ch, std::false_type{}, std::false_type{});
+    // Four loops in a row rather than one loop with branches: chunks whose successor is interior first
+    // (the head of G with ordinary loads, then the streamed part), then whatever is left -- the ragged
+    // end of the rows, or everything when N is not a multiple of 16 -- with clamped addresses and
+    // zero-fill.  Kept apart so that the address arithmetic of the general path, which the compiler
+    // computes ahead of its loop, does not occupy registers during the fast loops.
+    const int64_t fast_end = full_chunks < cached_chunks ? full_chunks : cached_chunks;
+    while (ch < nchunks && ch + stride < fast_end) step(std::false_type{}, std::true_type{});
+    while (ch < nchunks && ch + stride < full_chunks) step(std::true_type{}, std::true_type{});
+    while (ch < nchunks && ch + stride < cached_chunks) step(std::false_type{}, std::false_type{});
+    while (ch < nchunks) step(std::true_type{}, std::false_type{});
 #pragma unroll
-    for (int p = 0; p < NPT; ++p)
+    for (int p = 0; p < NPW; ++p)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc64[p][r] += (double)acc32[p][r];
-    __syncthreads();   // every wavefront is done with its slice before the buffer is reused
-    mfma_store_partial_row<NT>(acc64, reinterpret_cast<double *>(lds_raw), N,
-                               partials + (size_t)blockIdx.x * num_pairs(N));
+
+    // lane l, register r of tile pair (I, J) holds K[16 I + 4 (l / 16) + r][16 J + l % 16]
+    double *row_out = partials + (size_t)blockIdx.x * num_pairs(N);
+    auto scatter = [&](auto role) __attribute__((always_inline)) {
+        constexpr int ROLE = decltype(role)::value;
+        int p = 0;
+#pragma unroll
+        for (int I = 0; I < NT; ++I)
+#pragma unroll
+            for (int J = I; J < NT; ++J) {
+                if (coop_role(NT, W, p) == ROLE) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = I * 16 + 4 * kq + r, j = J * 16 + r16;
+                        if (i < N && j < N && i <= j) row_out[pair_index(i, j, N)] = acc64[coop_local(NT, W, p)][r];
+                    }
+                }
+                ++p;
+            }
+    };
+    if (wave == 0) scatter(std::integral_constant<int, 0>{});
+    else scatter(std::integral_constant<int, 1>{});
 }
 
 // ------------------------------------------------------------------------------------------
@@ -816,7 +635,7 @@ int gram_rows_needed(int N, int num_cu) {
 
 // dcols: the columns this launch covers, a multiple of VEC (rows are d elements apart).
 template <int N, typename T, int VEC>
-static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchShape &shape, const GramTail &tail,
+static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchShape &shape, double *partials,
                           hipStream_t s, int *grid_out) {
     static const int occ = occupancy(gram_vec_kernel<N, T, VEC>);
     const int64_t ngroups = dcols / VEC;
@@ -828,66 +647,36 @@ static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchS
     if (shape.cached_head_mb >= 0)
         cached_groups = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
     hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC>), dim3(grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), d, ngroups, cached_groups, tail);
+                       static_cast<const T *>(G), d, ngroups, cached_groups, partials);
     return hipGetLastError();
 }
 
 template <typename T, int VEC>
 static hipError_t dispatch_vec(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                               const GramTail &tail, hipStream_t s, int *grid_out) {
+                               double *partials, hipStream_t s, int *grid_out) {
     switch (N) {
-        case 1: return run_vec<1, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
-        case 2: return run_vec<2, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
-        case 3: return run_vec<3, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
-        case 4: return run_vec<4, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
-        case 5: return run_vec<5, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
-        case 6: return run_vec<6, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
-        case 7: return run_vec<7, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
-        case 8: return run_vec<8, T, VEC>(G, d, dcols, shape, tail, s, grid_out);
+        case 1: return run_vec<1, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 2: return run_vec<2, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 3: return run_vec<3, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 4: return run_vec<4, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 5: return run_vec<5, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 6: return run_vec<6, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 7: return run_vec<7, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 8: return run_vec<8, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
 
-template <int NT, typename T, bool STREAM>
-static hipError_t run_mfma_as(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
-                              hipStream_t s, int *grid_out) {
-    static const int occ = occupancy(gram_mfma_kernel<NT, T, STREAM>);
-    const int64_t cols_per_chunk = 16 * kUnits;
-    const int64_t nchunks = (d + cols_per_chunk - 1) / cols_per_chunk;
-    const int waves = kBlock / kWave;
-    const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, NT >= 3 ? 1 : 2);
-    *grid_out = grid;
-    hipLaunchKernelGGL((gram_mfma_kernel<NT, T, STREAM>), dim3(grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), N, d, nchunks, tail);
-    return hipGetLastError();
-}
-
-template <int NT, typename T>
-static hipError_t run_mfma_lds(const void *G, int N, int64_t d, const LaunchShape &shape, const GramTail &tail,
-                               hipStream_t s, int *grid_out) {
-    const int64_t tile_cols = LdsTileShape<NT>::kRowBytes / (int64_t)sizeof(T);
-    const int64_t ntiles = (d + tile_cols - 1) / tile_cols;
-    const int grid = grid_for(ntiles, shape, NT >= 4 ? 1 : 2, NT >= 4 ? 1 : 2);   // 64 KB of LDS per workgroup
-    *grid_out = grid;
-    hipLaunchKernelGGL((gram_mfma_lds_kernel<NT, T>), dim3(grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N,
-                       d, ntiles, tail.partials);
-    return hipGetLastError();
-}
-
-// SPLIT (fp32 only): products on the bf16 matrix-core path (gram_mfma_split_kernel) instead of the fp32 one.
 // dcols: the columns this launch covers, a multiple of the 128-bit vector width (rows are d elements apart).
-template <int NT, typename T, bool SPLIT>
+template <int NT, typename T>
 static hipError_t run_mfma_wave(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                                const GramTail &tail, hipStream_t s, int *grid_out) {
-    auto kern = [] {
-        if constexpr (SPLIT && sizeof(T) == 4) return gram_mfma_split_kernel<NT>;
-        else return gram_mfma_wave_kernel<NT, T>;
-    }();
+                                double *partials, hipStream_t s, int *grid_out) {
+    auto kern = gram_mfma_wave_kernel<NT, T>;
     static const int occ = occupancy(kern);
     const int64_t cols = 16 * VecWidth<T>::value;   // columns per chunk
     const int64_t nchunks = (dcols + cols - 1) / cols;
     const int waves = kBlock / kWave;
-    const int dflt = SPLIT ? (NT >= 3 ? 1 : 2) : (NT >= 4 ? 1 : 2);
+    const int dflt = NT >= 4 ? 1 : 2;
     const int grid = grid_for((nchunks + waves - 1) / waves, shape, occ, dflt);
     *grid_out = grid;
     // Non-temporal loads past the cached head pay off only when every row starts on a 128-byte line
@@ -899,42 +688,53 @@ static hipError_t run_mfma_wave(const void *G, int N, int64_t d, int64_t dcols, 
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N, d, dcols, nchunks,
-                       cached_chunks, tail.partials);
+                       cached_chunks, partials);
     return hipGetLastError();
 }
 
-// The wavefront-transpose kernels (variants 2 and 3) take any element-aligned G and any dcols that is a
-// multiple of the vector width; the direct and LDS-tile kernels (variants 1 and 0) and the fused tail
-// need 16-byte aligned rows and dcols = d, which the caller guarantees before selecting them.
+// The split-bf16 products with W wavefronts per chunk: one chunk and one partial row per workgroup.
+template <int NT, int W>
+static hipError_t run_mfma_coop(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
+                                double *partials, hipStream_t s, int *grid_out) {
+    static const int occ = [] {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gram_mfma_split_coop_kernel<NT, W>, W * kWave, 0) != hipSuccess || nb < 1) nb = 1;
+        return nb;
+    }();
+    const int64_t nchunks = (dcols + 63) / 64;
+    const int grid = grid_for(nchunks, shape, occ, 4);   // four workgroups per CU measured best (three: +8 %, six: +9 %)
+    *grid_out = grid;
+    const bool rows_on_lines = reinterpret_cast<uintptr_t>(G) % 128 == 0 && (d * 4) % 128 == 0;
+    int64_t cached_chunks = nchunks + (int64_t)grid;   // beyond every prefetch
+    if (shape.cached_head_mb >= 0 && rows_on_lines)
+        cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
+    hipLaunchKernelGGL((gram_mfma_split_coop_kernel<NT, W>), dim3(grid), dim3(W * kWave), 0, s, static_cast<const float *>(G), N,
+                       d, dcols, nchunks, cached_chunks, partials);
+    return hipGetLastError();
+}
+
+// shape.gram_products: 0 = the fp32 matrix-core instruction, 1 = split-bf16 products, 2 = by N.
+// Measured at d = 25.6 M, fp32: the split-bf16 products win at N = 64 (1.06 against 1.29 ms) and N = 48
+// (0.80 against 0.88 ms) and are even at N <= 32 (where the whole step measured 2 % slower with them).
+// bf16 inputs need no split: their products are exact on the bf16 instruction as they are.
 template <int NT, typename T>
 static hipError_t run_mfma(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                           const GramTail &tail, hipStream_t s, int *grid_out) {
-    // 4 = automatic: measured at d = 25.6 M, the split-bf16 products win at N = 64 (1.10 against
-    // 1.29 ms) and N = 48 (0.80 against 0.88 ms) and are even at N <= 32 (where the whole step
-    // measured 2 % slower with them).  bf16 inputs need no split (3 = 2).
-    const int variant = shape.mfma_direct == 4 ? ((NT >= 3 && sizeof(T) == 4) ? 3 : 2) : shape.mfma_direct;
-    if (tail.mode == kGramPartialsOnly && variant == 2)
-        return run_mfma_wave<NT, T, false>(G, N, d, dcols, shape, tail, s, grid_out);
-    if (tail.mode == kGramPartialsOnly && variant == 3)
-        return run_mfma_wave<NT, T, true>(G, N, d, dcols, shape, tail, s, grid_out);
-    if (dcols != d) return hipErrorInvalidValue;
-    // the LDS-staged kernel leaves the reduction to a later launch
-    if (tail.mode == kGramPartialsOnly && shape.mfma_direct == 0)
-        return run_mfma_lds<NT, T>(G, N, d, shape, tail, s, grid_out);
-    // Ordinary loads only: one load instruction takes 64 contiguous bytes of each of 16 rows, so
-    // the other half of every 128-byte line is needed by the next instruction; non-temporal loads
-    // do not keep the line and measured 20 % slower here.
-    return run_mfma_as<NT, T, false>(G, N, d, shape, tail, s, grid_out);
+                           double *partials, hipStream_t s, int *grid_out) {
+    if constexpr (sizeof(T) == 4) {
+        if (shape.gram_products == 1 || (shape.gram_products == 2 && NT >= 3))
+            return run_mfma_coop<NT, 2>(G, N, d, dcols, shape, partials, s, grid_out);
+    }
+    return run_mfma_wave<NT, T>(G, N, d, dcols, shape, partials, s, grid_out);
 }
 
 template <typename T>
 static hipError_t dispatch_mfma(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                                const GramTail &tail, hipStream_t s, int *grid_out) {
+                                double *partials, hipStream_t s, int *grid_out) {
     switch ((N + 15) / 16) {
-        case 1: return run_mfma<1, T>(G, N, d, dcols, shape, tail, s, grid_out);
-        case 2: return run_mfma<2, T>(G, N, d, dcols, shape, tail, s, grid_out);
-        case 3: return run_mfma<3, T>(G, N, d, dcols, shape, tail, s, grid_out);
-        case 4: return run_mfma<4, T>(G, N, d, dcols, shape, tail, s, grid_out);
+        case 1: return run_mfma<1, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 2: return run_mfma<2, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 3: return run_mfma<3, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 4: return run_mfma<4, T>(G, N, d, dcols, shape, partials, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
@@ -960,34 +760,29 @@ gram_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, double
     }
 }
 
-// tail.mode names the state wanted at the end (K reduced, or K and the coefficient update).
-// With `fuse` and N(N+1)/2 <= kBlock the Gram kernel's last workgroup does it; otherwise one
-// finish_kernel launch does (N <= 44), or a multi-workgroup reduction followed by coeff_kernel.
+// Stage A1, then the reduction of the partial rows into K and (with_coeffs) stage A2: one finish_kernel
+// launch for N <= 44, a multi-workgroup reduction followed by coeff_kernel above.
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
-                       const LaunchShape &shape_in, const GramTail &want, bool fuse, hipStream_t stream,
+                       const LaunchShape &shape_in, const GramWork &want, bool with_coeffs, hipStream_t stream,
                        hipEvent_t between) {
     // Without 16-byte aligned rows (vec_ok false) the same 128-bit kernels run from element-aligned
-    // addresses over the whole groups of every row, the columns left over (fewer than one group) go
-    // through gram_edge_kernel into one more partial row, and nothing is fused into the Gram kernel.
+    // addresses over the whole groups of every row, and the columns left over (fewer than one group) go
+    // through gram_edge_kernel into one more partial row.
     const int64_t vec = (dtype == ADACONS_F32) ? 4 : 8;
     const int64_t dcols = vec_ok ? d : d / vec * vec;
     LaunchShape shape = shape_in;
     if (!vec_ok) {
         if (shape.max_rows < 2) return hipErrorInvalidValue;
         shape.max_rows -= 1;   // room for the edge row
-        if (shape.mfma_direct != 2 && shape.mfma_direct != 3) shape.mfma_direct = 4;
     }
-    GramTail tail = want;
-    const bool fused = fuse && vec_ok && num_pairs(N) <= kBlock;
-    if (!fused) tail.mode = kGramPartialsOnly;
     int grid = 0;
     hipError_t e;
     if (N <= 8) {
-        e = (dtype == ADACONS_F32) ? dispatch_vec<float, 4>(G, N, d, dcols, shape, tail, stream, &grid)
-                                   : dispatch_vec<bf16_bits, 8>(G, N, d, dcols, shape, tail, stream, &grid);
+        e = (dtype == ADACONS_F32) ? dispatch_vec<float, 4>(G, N, d, dcols, shape, want.partials, stream, &grid)
+                                   : dispatch_vec<bf16_bits, 8>(G, N, d, dcols, shape, want.partials, stream, &grid);
     } else {
-        e = (dtype == ADACONS_F32) ? dispatch_mfma<float>(G, N, d, dcols, shape, tail, stream, &grid)
-                                   : dispatch_mfma<bf16_bits>(G, N, d, dcols, shape, tail, stream, &grid);
+        e = (dtype == ADACONS_F32) ? dispatch_mfma<float>(G, N, d, dcols, shape, want.partials, stream, &grid)
+                                   : dispatch_mfma<bf16_bits>(G, N, d, dcols, shape, want.partials, stream, &grid);
     }
     if (e == hipSuccess && dcols < d) {
         double *row = want.partials + (size_t)grid * num_pairs(N);
@@ -1001,16 +796,16 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
         grid += 1;
     }
     if (e == hipSuccess && between) e = hipEventRecord(between, stream);
-    if (e != hipSuccess || fused) return e;
+    if (e != hipSuccess) return e;
     if (N <= kFinishMaxN) {
         hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kFinishBlock), 0, stream, want.partials, grid, want.K,
-                           want.ds, want.cp, want.mode == kGramFinishCoeffs ? 1 : 0);
+                           want.ds, want.cp, with_coeffs ? 1 : 0);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(reduce_kernel, dim3((num_pairs(N) + 63) / 64), dim3(kBlock), 0, stream,
+    hipLaunchKernelGGL(reduce_kernel, dim3((num_pairs(N) + kReducePairs - 1) / kReducePairs), dim3(kBlock), 0, stream,
                        want.partials, grid, N, want.K);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (want.mode == kGramFinishCoeffs) return launch_coeffs(want.cp, want.K, want.ds, stream);
+    if (with_coeffs) return launch_coeffs(want.cp, want.K, want.ds, stream);
     return hipSuccess;
 }
 
@@ -1033,10 +828,7 @@ hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t strea
 __global__ void __launch_bounds__(kNMax) state_load_kernel(DevState *ds, int N, const double *__restrict__ m_in) {
     const int i = threadIdx.x;
     ds->m[i] = (i < N) ? m_in[i] : 0.0;
-    if (i == 0) {
-        ds->numeric_flags = 0u;
-        ds->blocks_done = 0u;
-    }
+    if (i == 0) ds->numeric_flags = 0u;
 }
 
 __global__ void __launch_bounds__(kNMax)

@@ -1,6 +1,6 @@
-// Layer-wise AdaCons aggregation (Sec. 4 of the paper: "layer-wise aggregation presents similar
-// performance"): steps A1-A3 run independently on every contiguous column segment of G, with one
-// coefficient set and one Eq. 11 momentum state per layer -- in three launches for all layers.
+// Layer-wise AdaCons aggregation (the variant Sec. 4 of the paper mentions beside the model-wise one):
+// steps A1-A3 run independently on every contiguous column segment of G, with one coefficient set
+// and one Eq. 11 momentum state per layer -- in three launches for all layers.
 //
 // Every layer is cut into runs of at most run_groups column groups (one group = one 128-bit load per
 // row); a run never crosses a layer boundary.  Layer boundaries need not be multiples of the group
@@ -9,12 +9,14 @@
 // last group of a row then holds fewer than VEC columns of it, and is read VEC columns back from
 // the end of the row instead (the columns it shares with the group before are masked).  All
 // 128-bit accesses are issued from element-aligned addresses.
-//   A1  workgroups take runs from a ticket counter in column order (so that at any time all
-//       workgroups read one compact window of every row, and long and short runs balance out).
+//   A1  workgroup b takes the runs order[b], order[b + grid], ... -- full-length runs in column order (so
+//       that at any time all workgroups read one compact window of every row), then the short ones,
+//       longest first; a run's descriptor comes through scalar loads, the next one's is in flight
+//       while the current run streams.
 //       Inside a run the N(N+1)/2 fp64 sums stay in registers; one partial row is written per
 //       run, indexed by the run, so the result does not depend on which workgroup took which run.
-//       Runs are numbered in column order, so the runs of one layer are consecutive.  The loop
-//       ends when the ticket passes the last run: no workgroup ever waits for another.
+//       Runs are numbered in column order, so the runs of one layer are consecutive.  No
+//       workgroup ever waits for another.
 //   A2  one workgroup per layer adds that layer's partial rows in a fixed order and runs the
 //       coefficient update on the layer's own state.
 //   A3  grid-stride over the runs; the run's layer selects the weights.
@@ -91,20 +93,28 @@ __device__ __forceinline__ void gram_layers_step(const T *__restrict__ G, int64_
 template <int N, typename T, int VEC>
 __global__ void __launch_bounds__(kBlock, 2)
 gram_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restrict__ runs, int nruns,
-                   const int *__restrict__ order, unsigned *__restrict__ ticket, double *__restrict__ partials,
-                   int64_t cached_groups) {
+                   const int *__restrict__ order, double *__restrict__ partials, int64_t cached_groups) {
     constexpr int NP = N * (N + 1) / 2;
     __shared__ double lds[4 * NP];
-    __shared__ unsigned s_next;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);
-    __syncthreads();
-    unsigned tk = s_next;
-    while (tk < (unsigned)nruns) {   // tk is workgroup-uniform
-        __syncthreads();             // everyone has read s_next
-        if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);   // next ticket: in flight during this run
-        const int r = order[tk];
-        const LayerRun run = runs[r];
+    // Workgroup b takes the runs order[b], order[b + grid], ...: the index is uniform, so a run's
+    // descriptor comes through scalar loads, and the next run's is requested while this run streams.
+    int k = (int)blockIdx.x;
+    int r = 0;
+    LayerRun run = {};
+    if (k < nruns) {
+        r = order[k];
+        run = runs[r];
+    }
+    while (k < nruns) {
+        const int kn = k + (int)gridDim.x;
+        int rn = 0;
+        LayerRun run_next = run;
+        if (kn < nruns) {
+            rn = order[kn];
+            run_next = runs[rn];
+        }
+        __syncthreads();             // the previous run's sums have been read out of LDS
         double acc[NP];
 #pragma unroll
         for (int p = 0; p < NP; ++p) acc[p] = 0.0;
@@ -139,44 +149,57 @@ gram_layers_kernel(const T *__restrict__ G, int64_t d, const LayerRun *__restric
             const int p = threadIdx.x;
             partials[(size_t)r * NP + p] = ((lds[p] + lds[NP + p]) + lds[2 * NP + p]) + lds[3 * NP + p];
         }
-        tk = s_next;   // written by thread 0 before the barrier above
+        k = kn;
+        r = rn;
+        run = run_next;
     }
 }
 
 // A1 for N > 8.  Same run bookkeeping as above; inside a run wavefront w takes the chunks
-// w, w + 4, ... of 16 column groups.  Load j of a chunk: row 4 j + lane / 16, group lane % 16
-// (four rows by 256 contiguous bytes per instruction).  Column sums s over the rows (in-lane, then
-// across the four lane groups), then q_i += <v_i, v_i>, r_i += <v_i, s> in fp64.  Groups past the
+// w, w + 4, ... of LPR column groups.  Load j of a chunk: row RPL j + lane / LPR, group lane % LPR
+// (four rows by 256 contiguous bytes per instruction up to 64 rows; eight rows by 128 bytes above,
+// which keeps the registers of the 64-row instantiation).  Column sums s over the rows (in-lane, then
+// across the lane groups), then q_i += <v_i, v_i>, r_i += <v_i, s> in fp64.  Groups past the
 // end of the run and columns of a straddling group that belong to the neighbouring layer are
 // zeroed.  One partial row [q_0 .. q_{N-1}, r_0 .. r_{N-1}] per run.
 template <int NT, typename T>
-__global__ void __launch_bounds__(kBlock, (NT * VecWidth<T>::value >= 12) ? 1 : 2)
+__global__ void __launch_bounds__(kBlock, (((NT > 4) ? 2 * NT : 4 * NT) * VecWidth<T>::value >= 48) ? 1 : 2)
 stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *__restrict__ runs, int nruns,
-                    const int *__restrict__ order, unsigned *__restrict__ ticket, double *__restrict__ partials) {
+                    const int *__restrict__ order, double *__restrict__ partials) {
     constexpr int VECW = VecWidth<T>::value;
-    constexpr int kLoads = 4 * NT;
+    constexpr int RPL = (NT > 4) ? 8 : 4;          // rows per load instruction
+    constexpr int LPR = kWave / RPL;               // lanes (column groups) side by side in one row
+    constexpr int kLoads = 16 * NT / RPL;
     __shared__ double lds[kBlock / kWave][2 * kNMax];
-    __shared__ unsigned s_next;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int grp = lane >> 4, cl = lane & 15;
-    if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);
-    __syncthreads();
-    unsigned tk = s_next;
-    while (tk < (unsigned)nruns) {   // tk is workgroup-uniform
-        __syncthreads();             // everyone has read s_next and the previous run's LDS sums
-        if (threadIdx.x == 0) s_next = atomicAdd(ticket, 1u);   // next ticket: in flight during this run
-        const int r = order[tk];
-        const LayerRun run = runs[r];
+    const int grp = lane / LPR, cl = lane % LPR;
+    // runs order[b], order[b + grid], ... of workgroup b; the next run's descriptor is requested early
+    int k = (int)blockIdx.x;
+    int r = 0;
+    LayerRun run = {};
+    if (k < nruns) {
+        r = order[k];
+        run = runs[r];
+    }
+    while (k < nruns) {
+        const int kn = k + (int)gridDim.x;
+        int rn = 0;
+        LayerRun run_next = run;
+        if (kn < nruns) {
+            rn = order[kn];
+            run_next = runs[rn];
+        }
+        __syncthreads();             // the previous run's sums have been read out of LDS
         double qacc[kLoads], racc[kLoads];
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) qacc[j] = racc[j] = 0.0;
         const int64_t g_end = run.g0 + run.n;
-        const int nchunks = (run.n + 15) / 16;
-        // interior chunk: all sixteen groups belong to the run, none of their columns to a neighbouring
+        const int nchunks = (run.n + LPR - 1) / LPR;
+        // interior chunk: all of its groups belong to the run, none of their columns to a neighbouring
         // layer, and every row exists -- no clamps, no masks (they cost more than the arithmetic)
         auto chunk = [&](int c, auto interior) __attribute__((always_inline)) {
             constexpr bool kInterior = decltype(interior)::value;
-            const int64_t g = run.g0 + 16 * (int64_t)c + cl;
+            const int64_t g = run.g0 + LPR * (int64_t)c + cl;
             const bool in_run = kInterior || g < g_end;
             const int64_t gc = in_run ? g : g_end - 1;          // clamped: always a group of this run
             const int64_t c0 = gc * VECW;
@@ -185,7 +208,7 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
             u32x4 x[kLoads];
 #pragma unroll
             for (int j = 0; j < kLoads; ++j) {
-                const int row = 4 * j + grp;
+                const int row = RPL * j + grp;
                 const int rowc = (kInterior || row < N) ? row : N - 1;
                 x[j] = *reinterpret_cast<const gu32x4 *>(G + (int64_t)rowc * d + lb);
             }
@@ -200,20 +223,20 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
             for (int j = 0; j < kLoads; ++j) {
                 float v[VECW];
                 widen_bits<T>(x[j], v);
-                const bool row_ok = kInterior || 4 * j + grp < N;
+                const bool row_ok = kInterior || RPL * j + grp < N;
 #pragma unroll
                 for (int k = 0; k < VECW; ++k) ssum[k] += (row_ok && live[k]) ? (double)v[k] : 0.0;
             }
 #pragma unroll
             for (int k = 0; k < VECW; ++k) {
-                ssum[k] += __shfl_xor(ssum[k], 16, kWave);
-                ssum[k] += __shfl_xor(ssum[k], 32, kWave);
+#pragma unroll
+                for (int off = LPR; off < kWave; off <<= 1) ssum[k] += __shfl_xor(ssum[k], off, kWave);
             }
 #pragma unroll
             for (int j = 0; j < kLoads; ++j) {
                 float v[VECW];
                 widen_bits<T>(x[j], v);
-                const bool row_ok = kInterior || 4 * j + grp < N;
+                const bool row_ok = kInterior || RPL * j + grp < N;
 #pragma unroll
                 for (int k = 0; k < VECW; ++k) {
                     const double y = (row_ok && live[k]) ? (double)v[k] : 0.0;
@@ -223,23 +246,23 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
             }
         };
         for (int c = wave; c < nchunks; c += kBlock / kWave) {
-            const int64_t first = (run.g0 + 16 * (int64_t)c) * VECW;      // the chunk's columns [first, first + 16 VECW)
-            const bool interior = N == 16 * NT && 16 * c + 16 <= run.n && first >= run.cb && first + 16 * VECW <= run.ce;
+            const int64_t first = (run.g0 + LPR * (int64_t)c) * VECW;      // the chunk's columns [first, first + LPR VECW)
+            const bool interior = N == 16 * NT && LPR * c + LPR <= run.n && first >= run.cb && first + LPR * VECW <= run.ce;
             if (interior) chunk(c, std::true_type{});
             else chunk(c, std::false_type{});
         }
-        // the sixteen lanes of a group in a fixed butterfly order, then the wavefronts in index order
+        // the lanes of a group in a fixed butterfly order, then the wavefronts in index order
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             double q = qacc[j], rr = racc[j];
 #pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) {
+            for (int off = LPR / 2; off >= 1; off >>= 1) {
                 q += __shfl_xor(q, off, kWave);
                 rr += __shfl_xor(rr, off, kWave);
             }
             if (cl == 0) {
-                lds[wave][4 * j + grp] = q;
-                lds[wave][kNMax + 4 * j + grp] = rr;
+                lds[wave][RPL * j + grp] = q;
+                lds[wave][kNMax + RPL * j + grp] = rr;
             }
         }
         __syncthreads();
@@ -248,7 +271,9 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
             const int e = t < N ? t : kNMax + (t - N);
             partials[(size_t)r * (2 * N) + t] = ((lds[0][e] + lds[1][e]) + lds[2][e]) + lds[3][e];
         }
-        tk = s_next;   // written by thread 0 before the barrier above
+        k = kn;
+        r = rn;
+        run = run_next;
     }
 }
 
@@ -258,8 +283,7 @@ stats_layers_kernel(const T *__restrict__ G, int N, int64_t d, const LayerRun *_
 constexpr int kLayerFinishBlock = 1024;
 __global__ void __launch_bounds__(kLayerFinishBlock)
 finish_layers_kernel(const double *__restrict__ partials, const int *__restrict__ layer_entry0, double *K_all,
-                     DevState *ds_all, CoeffParams cp, unsigned *ticket) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;   // A1 is over: ready for the next call
+                     DevState *ds_all, CoeffParams cp) {
     __shared__ double lds[4 * kNMax];
     __shared__ double K_lds[kLayersMaxN * kLayersMaxN];
     const bool stats = cp.N > kLayersMaxN;                   // rows hold [q, r] instead of the packed K
@@ -566,14 +590,14 @@ static hipError_t launch_wsum_layers_rt(const void *G, int N, int64_t d, const L
 template <int NT, typename T, int VEC>
 static hipError_t run_layers_stats(const void *G, int N, int64_t d, const LayerRun *runs, int nruns, int run_groups, const int *order,
                                    int gram_grid, int wsum_grid, const int *layer_entry0, int L, double *partials,
-                                   double *K_all, DevState *ds_all, unsigned *ticket, CoeffParams cp, float *out,
+                                   double *K_all, DevState *ds_all, CoeffParams cp, float *out,
                                    hipStream_t s) {
     hipLaunchKernelGGL((stats_layers_kernel<NT, T>), dim3(gram_grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N,
-                       d, runs, nruns, order, ticket, partials);
+                       d, runs, nruns, order, partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(finish_layers_kernel, dim3(L), dim3(kLayerFinishBlock), 0, s, partials, layer_entry0, K_all,
-                       ds_all, cp, ticket);
+                       ds_all, cp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     return launch_wsum_layers_rt<T, VEC>(G, N, d, runs, nruns, run_groups, wsum_grid, ds_all, out, s);
 }
@@ -585,6 +609,10 @@ static hipError_t dispatch_layers_stats(int N, const void *G, A... a) {
         case 2: return run_layers_stats<2, T, VEC>(G, N, a...);
         case 3: return run_layers_stats<3, T, VEC>(G, N, a...);
         case 4: return run_layers_stats<4, T, VEC>(G, N, a...);
+        case 5: return run_layers_stats<5, T, VEC>(G, N, a...);
+        case 6: return run_layers_stats<6, T, VEC>(G, N, a...);
+        case 7: return run_layers_stats<7, T, VEC>(G, N, a...);
+        case 8: return run_layers_stats<8, T, VEC>(G, N, a...);
         default: return hipErrorInvalidValue;
     }
 }
@@ -592,15 +620,15 @@ static hipError_t dispatch_layers_stats(int N, const void *G, A... a) {
 template <int N, typename T, int VEC>
 static hipError_t run_layers(const void *G, int64_t d, const LayerRun *runs, int nruns, int run_groups, const int *order, int gram_grid, int wsum_grid,
                              const int64_t *offsets, const int *layer_entry0, int L, double *partials, double *K_all,
-                             DevState *ds_all, unsigned *ticket, CoeffParams cp, float *out, hipStream_t s) {
+                             DevState *ds_all, CoeffParams cp, float *out, hipStream_t s) {
     // the first 320 MiB of G with cache-allocating loads (same policy as the model-wise stage A1)
     const int64_t cached_groups = ((int64_t)320 << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
     hipLaunchKernelGGL((gram_layers_kernel<N, T, VEC>), dim3(gram_grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), d, runs, nruns, order, ticket, partials, cached_groups);
+                       static_cast<const T *>(G), d, runs, nruns, order, partials, cached_groups);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(finish_layers_kernel, dim3(L), dim3(kLayerFinishBlock), 0, s, partials, layer_entry0, K_all,
-                       ds_all, cp, ticket);
+                       ds_all, cp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL((wsum_layers_kernel<N, T, VEC>), dim3(wsum_grid), dim3(kBlock), 0, s,
                        static_cast<const T *>(G), d, runs, nruns, offsets, ds_all, out, run_groups);
@@ -639,8 +667,7 @@ struct adacons_layers {
     double *partials;     // device, nruns x N(N+1)/2
     double *K;            // device, L x N x N
     DevState *ds;         // device, L
-    unsigned *ticket;     // device: run counter of stage A1, zero between calls
-    int *order;           // device, nruns: ticket -> run (full-length runs in column order, then the
+    int *order;           // device, nruns: the order stage A1 takes the runs in (full-length runs in column order, then the
                           // shorter ones, longest first, so that the sweep ends on small pieces)
 };
 
@@ -652,7 +679,7 @@ extern "C" {
 
 adacons_status adacons_destroy_layers(adacons_layers *ls) {
     if (!ls) return ADACONS_OK;
-    void *bufs[] = {ls->runs, ls->offsets, ls->layer_entry0, ls->partials, ls->K, ls->ds, ls->ticket, ls->order};
+    void *bufs[] = {ls->runs, ls->offsets, ls->layer_entry0, ls->partials, ls->K, ls->ds, ls->order};
     for (void *p : bufs)
         if (p) (void)hipFree(p);
     delete ls;
@@ -665,7 +692,7 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     *out_ls = nullptr;
     if (!offsets_host) return lfail(ADACONS_EINVAL, "offsets_host is NULL");
     if (N < 1 || L < 1) return lfail(ADACONS_EINVAL, "N < 1 or L < 1");
-    if (N > ADACONS_GRAM_N_MAX) return lfail(ADACONS_EUNSUPPORTED, "layer-wise aggregation takes N <= 64");
+    if (N > ADACONS_N_MAX) return lfail(ADACONS_EUNSUPPORTED, "N > ADACONS_N_MAX");
     if (dtype != ADACONS_F32 && dtype != ADACONS_BF16) return lfail(ADACONS_EUNSUPPORTED, "unknown dtype");
     if (!(beta >= 0.0 && beta < 1.0)) return lfail(ADACONS_EINVAL, "beta outside [0, 1)");
     if (flags & ~ADACONS_FLAG_ALL_) return lfail(ADACONS_EINVAL, "unknown flag bits");
@@ -733,17 +760,17 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->offsets), sizeof(int64_t) * (size_t)(L + 1));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->layer_entry0), sizeof(int) * (size_t)(L + 1));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->partials), sizeof(double) * (size_t)nruns * np);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->K), sizeof(double) * (size_t)L * N * N);
+    // K per layer exists only where stage A1 forms it (N <= kLayersMaxN); the statistics pass never touches it
+    const size_t k_doubles = N > kLayersMaxN ? 1 : (size_t)L * N * N;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->K), sizeof(double) * k_doubles);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->ds), sizeof(DevState) * (size_t)L);
     if (e == hipSuccess) e = hipMemcpyAsync(ls->runs, runs.data(), sizeof(LayerRun) * (size_t)nruns, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMemcpyAsync(ls->offsets, offsets_host, sizeof(int64_t) * (size_t)(L + 1), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMemcpyAsync(ls->layer_entry0, layer_entry0.data(), sizeof(int) * (size_t)(L + 1), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->order), sizeof(int) * (size_t)nruns);
     if (e == hipSuccess) e = hipMemcpyAsync(ls->order, order.data(), sizeof(int) * (size_t)nruns, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&ls->ticket), sizeof(unsigned));
-    if (e == hipSuccess) e = hipMemsetAsync(ls->ticket, 0, sizeof(unsigned), s);
     if (e == hipSuccess) e = hipMemsetAsync(ls->ds, 0, sizeof(DevState) * (size_t)L, s);
-    if (e == hipSuccess) e = hipMemsetAsync(ls->K, 0, sizeof(double) * (size_t)L * N * N, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ls->K, 0, sizeof(double) * k_doubles, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);   // the host vectors above go out of scope
     if (e != hipSuccess) {
         adacons_destroy_layers(ls);
@@ -772,19 +799,19 @@ adacons_status adacons_aggregate_layers(const void *G, int N, int64_t d, adacons
         if (dtype == ADACONS_F32)
             e = dispatch_layers_stats<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order,
                                                 ls->gram_grid, ls->wsum_grid, (const int *)ls->layer_entry0, ls->L,
-                                                ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
+                                                ls->partials, ls->K, ls->ds, cp, out, s);
         else
             e = dispatch_layers_stats<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order,
                                                     ls->gram_grid, ls->wsum_grid, (const int *)ls->layer_entry0, ls->L,
-                                                    ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
+                                                    ls->partials, ls->K, ls->ds, cp, out, s);
     } else if (dtype == ADACONS_F32)
         e = dispatch_layers<float, 4>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
                                       (const int64_t *)ls->offsets, (const int *)ls->layer_entry0, ls->L, ls->partials,
-                                      ls->K, ls->ds, ls->ticket, cp, out, s);
+                                      ls->K, ls->ds, cp, out, s);
     else
         e = dispatch_layers<bf16_bits, 8>(N, G, d, (const LayerRun *)ls->runs, ls->nruns, ls->run_groups, (const int *)ls->order, ls->gram_grid, ls->wsum_grid,
                                           (const int64_t *)ls->offsets, (const int *)ls->layer_entry0, ls->L,
-                                          ls->partials, ls->K, ls->ds, ls->ticket, cp, out, s);
+                                          ls->partials, ls->K, ls->ds, cp, out, s);
     if (e != hipSuccess) return lfail(ADACONS_EHIP, hipGetErrorString(e));
     return ADACONS_OK;
 }

@@ -3,10 +3,8 @@
 // A streaming kernel: one thread owns VEC consecutive columns, loads them from all N rows
 // (128-bit loads, eight rows in flight at a time), applies the weights in worker order
 // i = 0..N-1 with fused multiply-adds, and writes VEC floats.  G is read for the last time
-// here and `out` is not read back by this library, so both use non-temporal accesses.
-// With `reverse` the tiles of kBlock * UNR column groups are walked from the end (columns still
-// ascend inside a tile): the second pass then starts on the part of G the first pass touched last,
-// which is still in the memory-side cache.
+// here and `out` is not read back by this library, so both use non-temporal accesses.  The tiles are
+// walked forwards: the pass starts on the head of G, which stage A1 left in the memory-side cache.
 #include "adacons_internal.h"
 #include "device_util.h"
 
@@ -117,7 +115,7 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
 template <int NCT, typename T, int VEC, int UNR, bool APPLY>
 __global__ void __launch_bounds__(kBlock)
 wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
-            float *__restrict__ out, int reverse, float lr) {
+            float *__restrict__ out, float lr) {
     const int N = (NCT > 0) ? NCT : n_rt;
     __shared__ float gam_lds[kNMax];
     float gam_reg[NCT > 0 ? NCT : 1];
@@ -138,8 +136,7 @@ wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const
     const int grid = (int)gridDim.x, b = (int)blockIdx.x;
     const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;
     for (int64_t t = slot; t < ntiles; t += gridDim.x) {
-        // reverse: tiles in descending order, columns ascending inside a tile
-        const int64_t tt = reverse ? (ntiles - 1 - t) : t;
+        const int64_t tt = t;
         const int64_t base = tt * kTile + threadIdx.x;
         if ((tt + 1) * kTile <= ngroups)
             wsum_tile<NCT, T, VEC, UNR, true, APPLY>(G, N, d, ngroups, base, gam, out, lr);
@@ -156,7 +153,7 @@ wsum_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const
 template <int NCT, typename T, int VEC, int UNR, bool APPLY, int BLK>
 __global__ void __launch_bounds__(BLK)
 wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
-                   float *__restrict__ out, int reverse, float lr, int cap) {
+                   float *__restrict__ out, float lr, int cap) {
     extern __shared__ __attribute__((aligned(16))) float park[];   // cap tiles of kTileCols floats
     const int N = (NCT > 0) ? NCT : n_rt;
     __shared__ float gam_lds[kNMax];
@@ -183,8 +180,7 @@ wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups
     auto flush = [&](int64_t q_first, int n) __attribute__((always_inline)) {
         __syncthreads();   // the images are complete
         for (int k = 0; k < n; ++k) {
-            const int64_t t = tile_of(q_first + k);
-            const int64_t tt = reverse ? (ntiles - 1 - t) : t;
+            const int64_t tt = tile_of(q_first + k);
             float *dst = out + tt * kTileCols;
             const float *src = park + (size_t)k * kTileCols;
 #pragma unroll
@@ -208,7 +204,7 @@ wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups
     for (int64_t q = 0;; ++q) {   // uniform over the workgroup
         const int64_t t = tile_of(q);
         if (t >= ntiles) break;   // tile_of ascends
-        const int64_t tt = reverse ? (ntiles - 1 - t) : t;
+        const int64_t tt = t;
         const int64_t base = tt * kTile + threadIdx.x;
         if ((tt + 1) * kTile <= ngroups) {
             if (parked == 0) q_first = q;
@@ -239,7 +235,7 @@ static int occupancy(Kern k) {
 // dcols: the columns this launch covers, a multiple of VEC (rows are d elements apart).
 template <int NCT, typename T, int VEC, int UNR, bool APPLY>
 static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, const float *gamma,
-                         float *out, bool reverse, float lr, hipStream_t s) {
+                         float *out, float lr, hipStream_t s) {
     static const int occ = occupancy(wsum_kernel<NCT, T, VEC, UNR, APPLY>);
     const int64_t ngroups = dcols / VEC;
     const int64_t work = (ngroups + (int64_t)kBlock * UNR - 1) / ((int64_t)kBlock * UNR);
@@ -284,7 +280,7 @@ static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const L
         if (grid_p < 1) grid_p = 1;
         hipLaunchKernelGGL((wsum_parked_kernel<NCT, T, VEC, UNR, APPLY, kParkBlock>), dim3((unsigned)grid_p),
                            dim3(kParkBlock), (size_t)cap * kTileBytes, s, static_cast<const T *>(G), N, d, ngroups, gamma,
-                           out, reverse ? 1 : 0, lr, cap);
+                           out, lr, cap);
         return hipGetLastError();
     }
     int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : (long_stream ? 1 : 8);
@@ -293,21 +289,21 @@ static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const L
     if (grid > work) grid = work;
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL((wsum_kernel<NCT, T, VEC, UNR, APPLY>), dim3((unsigned)grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), N, d, ngroups, gamma, out, reverse ? 1 : 0, lr);
+                       static_cast<const T *>(G), N, d, ngroups, gamma, out, lr);
     return hipGetLastError();
 }
 
 // apply = false: out = sum_i gamma_i g_i.  apply = true: out -= lr * sum_i gamma_i g_i (Eq. 4 fused).
 struct WsumMode {
-    bool reverse, apply;
+    bool apply;
     float lr;
 };
 
 template <int NCT, typename T, int VEC, int UNR>
 static hipError_t run(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, const float *gamma,
                       float *out, const WsumMode &m, hipStream_t s) {
-    return m.apply ? run_as<NCT, T, VEC, UNR, true>(G, N, d, dcols, shape, gamma, out, m.reverse, m.lr, s)
-                   : run_as<NCT, T, VEC, UNR, false>(G, N, d, dcols, shape, gamma, out, m.reverse, 0.f, s);
+    return m.apply ? run_as<NCT, T, VEC, UNR, true>(G, N, d, dcols, shape, gamma, out, m.lr, s)
+                   : run_as<NCT, T, VEC, UNR, false>(G, N, d, dcols, shape, gamma, out, 0.f, s);
 }
 
 template <typename T, int VEC, int UNR>
@@ -340,9 +336,9 @@ wsum_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, const 
 // Without 16-byte aligned rows and output (vec_ok false) the same kernels run from element-aligned
 // addresses over the whole 128-bit groups of every row; wsum_edge_kernel takes the columns left over.
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
-                       const LaunchShape &shape, const float *gamma, float *out, bool reverse,
-                       hipStream_t stream, bool apply, float lr) {
-    const WsumMode m = {reverse, apply, lr};
+                       const LaunchShape &shape, const float *gamma, float *out, hipStream_t stream,
+                       bool apply, float lr) {
+    const WsumMode m = {apply, lr};
     const int64_t vec = (dtype == ADACONS_F32) ? 4 : 8;
     const int64_t dcols = vec_ok ? d : d / vec * vec;
     hipError_t e = (dtype == ADACONS_F32) ? dispatch<float, 4, 2>(G, N, d, dcols, shape, gamma, out, m, stream)

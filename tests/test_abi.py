@@ -80,7 +80,7 @@ def test_argument_validation_needs_no_gpu(lib):
                  (ctypes.byref(ls), 4, 2, (ctypes.c_int64 * 3)(1, 40, 100), 0, 0.9, 3, None),
                  (ctypes.byref(ls), 4, 2, (ctypes.c_int64 * 3)(0, 40, 40), 0, 0.9, 3, None)]:
         assert cdll.adacons_init_layers(*args) == EINVAL, args
-    assert cdll.adacons_init_layers(ctypes.byref(ls), 65, 2, good, 0, 0.9, 3, None) == EUNSUPPORTED
+    assert cdll.adacons_init_layers(ctypes.byref(ls), 129, 2, good, 0, 0.9, 3, None) == EUNSUPPORTED
     assert cdll.adacons_init_layers(ctypes.byref(ls), 4, 2, good, 7, 0.9, 3, None) == EUNSUPPORTED
     assert ls.value is None
     assert cdll.adacons_destroy_layers(None) == 0

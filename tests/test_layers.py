@@ -112,7 +112,8 @@ def _check_layers(pkg, G, off, agg, states, out_tol, check_out=True):
 @pytest.mark.parametrize("N,d,L", [(1, 64, 1), (2, 1000, 3), (4, 40_000, 17), (8, 300_000, 50), (8, 2_000_000, 9),
                                    (5, 123_456, 200), (8, 1024, 1024),
                                    (9, 50_000, 11), (16, 400_000, 40), (17, 1024, 1024), (33, 100_000, 7),
-                                   (48, 60_000, 30), (64, 300_000, 25), (64, 64, 1)])
+                                   (48, 60_000, 30), (64, 300_000, 25), (64, 64, 1),
+                                   (65, 30_000, 9), (80, 200_000, 20), (100, 50_000, 50), (128, 150_000, 12), (128, 1024, 64)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_random_layouts_match_oracle(pkg, N, d, L, dtype):
     rng = np.random.default_rng(N * 7 + L)
@@ -132,7 +133,8 @@ def test_random_layouts_match_oracle(pkg, N, d, L, dtype):
 @pytest.mark.gpu
 @pytest.mark.parametrize("N,d,L,shift", [(2, 1001, 3, 0), (4, 40_003, 17, 1), (8, 300_005, 50, 0), (8, 9, 2, 0), (5, 123_457, 200, 3),
                                          (8, 1027, 1027, 0), (9, 50_001, 11, 1), (16, 400_006, 40, 0), (33, 100_007, 7, 5),
-                                         (64, 300_002, 25, 0), (64, 71, 1, 1), (8, 300_000, 50, 2)])
+                                         (64, 300_002, 25, 0), (64, 71, 1, 1), (8, 300_000, 50, 2),
+                                         (97, 60_003, 13, 1), (128, 40_001, 5, 0)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_layouts_off_the_16_byte_grid(pkg, N, d, L, shift, dtype):
     """d that is not a multiple of the 128-bit group (the last group of every row is ragged), G and out
@@ -229,7 +231,7 @@ def test_one_layer_equals_model_wise_kernel_many_workers(pkg, dtype):
 @pytest.mark.gpu
 def test_layer_argument_errors(pkg):
     with pytest.raises(pkg.AdaConsError) as e:
-        pkg.AdaConsLayers(65, [0, 100])
+        pkg.AdaConsLayers(129, [0, 100])
     assert e.value.status == 2
     with pytest.raises(pkg.AdaConsError):
         pkg.AdaConsLayers(4, [0, 50, 50, 100])          # empty layer

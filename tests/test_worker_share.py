@@ -92,11 +92,13 @@ def test_worker_stats_and_scale_off_16_byte_boundaries(pkg, d, dtype, shift):
     the 128-bit kernels run from element-aligned addresses, the leftover elements go to single threads."""
     buf = torch.randn(2 * d + 2 * shift + 8, device=DEV).to(dtype)
     x, y = buf[shift:d + shift], buf[d + shift:2 * d + shift]
-    agg = pkg.AdaCons(2, d)
+    agg = pkg.AdaCons(2, d, flags=0)
     got = agg.worker_stats(x, y).cpu().numpy()
     ref = np.array(o.worker_stats(_bits(x), _bits(y)))
     assert np.allclose(got, ref, rtol=1e-12)
-    agg.weighted_sum(torch.stack([x, y]).contiguous(), [0.75, -1.25])      # sets the weights the scale uses
+    # the weights the scale uses: with momentum and normalisation off gamma_i = r_i / (N q_i) = 0.75, -1.25 exactly
+    agg.update_from_stats([1.0, 1.0], [1.5, -2.5])
+    assert np.array_equal(agg.coeffs()["gamma"], [0.75, -1.25])
     before = buf.clone()
     agg.worker_scale(x, 1)
     want = (before[shift:d + shift].float() * (-1.25)).to(dtype)
