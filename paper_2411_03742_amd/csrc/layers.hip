@@ -44,19 +44,40 @@ struct LayerRun {
 };
 
 constexpr int kLayersMaxN = 8;           // largest N with the Gram matrix per thread; above: statistics
-// Column groups per run: chosen per layout so that the full-length runs come to a whole number per
-// workgroup of stage A1 (a fixed length of 16 sweeps left 24 of 512 workgroups with a fourth
-// full-length run on the ResNet-50 layout while the others had three).  A multiple of 512, so that an
-// eighth of it (the piece of stage A3) is a whole number of wavefront segments.
-static int choose_run_groups(int64_t total_groups, int gram_grid) {
-    const int64_t nominal = 16 * kBlock;
-    int64_t per_block = (total_groups + (int64_t)gram_grid * nominal / 2) / ((int64_t)gram_grid * nominal);   // runs per workgroup
-    if (per_block < 1) per_block = 1;
-    int64_t len = (total_groups + gram_grid * per_block - 1) / (gram_grid * per_block);
-    len = (len + 511) / 512 * 512;
-    if (len < 4 * kBlock) len = 4 * kBlock;
-    if (len > 64 * kBlock) len = 64 * kBlock;
-    return (int)len;
+// Column groups per run.  Workgroup b of stage A1 takes the runs order[b], order[b + grid], ... (the
+// full-length runs in column order, then the shorter ones, longest first), so the pass lasts as long as
+// the workgroup with the most column groups.  The length is chosen per layout: every multiple of 512
+// groups (an eighth of a run must be a whole piece of stage A3) from 1024 to 16384 is laid out, the
+// assignment above is played through, and the length with the smallest largest share wins; a run's
+// fixed cost (descriptor, final reduction, barriers) is counted as kRunOverhead groups.  A fixed
+// length of 4608 left 363 of 512 workgroups with three runs and the others with two on one 25.6 M
+// column layer: 11 % more time than the bytes need.
+constexpr int kRunOverhead = 512;
+static int choose_run_groups(const int64_t *offsets, int L, int vec, int grid) {
+    int best_len = 4 * kBlock;
+    if (L > (1 << 16)) return best_len;   // a great many small layers: every run is short whatever the length
+    int64_t best_cost = -1;
+    std::vector<int64_t> load((size_t)grid);
+    std::vector<int> rest;
+    for (int len = 4 * kBlock; len <= 64 * kBlock; len += 512) {
+        std::fill(load.begin(), load.end(), (int64_t)0);
+        rest.clear();
+        int64_t slot = 0;   // position in the order: full-length runs first, as they come
+        for (int l = 0; l < L; ++l) {
+            const int64_t groups = (offsets[l + 1] + vec - 1) / vec - offsets[l] / vec;
+            const int64_t full = groups / len;
+            for (int64_t r = 0; r < full; ++r) load[(size_t)(slot++ % grid)] += len + kRunOverhead;
+            if (groups % len) rest.push_back((int)(groups % len));
+        }
+        std::sort(rest.begin(), rest.end(), [](int a, int b) { return a > b; });
+        for (int n : rest) load[(size_t)(slot++ % grid)] += n + kRunOverhead;
+        const int64_t cost = *std::max_element(load.begin(), load.end());
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best_len = len;
+        }
+    }
+    return best_len;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -710,10 +731,8 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return lfail(ADACONS_EUNSUPPORTED, "built for gfx950 only");
 
     const int vec = dtype == ADACONS_BF16 ? 8 : 4;
-    int64_t total_groups = 0;
-    for (int l = 0; l < L; ++l) total_groups += (offsets_host[l + 1] + vec - 1) / vec - offsets_host[l] / vec;
     const int grid_target = prop.multiProcessorCount * 2;   // measured (ResNet-50 layout): 144 us at two workgroups per CU, 152 at one, 155 at three
-    const int run_groups = choose_run_groups(total_groups, grid_target);
+    const int run_groups = choose_run_groups(offsets_host, L, vec, grid_target);
     // runs: per layer, the groups that contain any of its columns, cut into pieces of run_groups
     std::vector<LayerRun> runs;
     std::vector<int> layer_entry0(L + 1);
