@@ -87,7 +87,7 @@ def main() -> int:
                          "parameter tensor of a ResNet-50; not the headline metric")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="gram_blocks_per_cu / wsum_blocks_per_cu / cached_head_mb / gram_products / stats_only / "
-                         "wsum_park_kb")
+                         "wsum_park_kb / short_path")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 "
@@ -118,7 +118,8 @@ def main() -> int:
             "cached_head_mb": ada.ADACONS_TUNE_CACHED_HEAD_MB,
             "gram_products": ada.ADACONS_TUNE_GRAM_PRODUCTS,
             "stats_only": ada.ADACONS_TUNE_STATS_ONLY,
-            "wsum_park_kb": ada.ADACONS_TUNE_WSUM_PARK_KB}
+            "wsum_park_kb": ada.ADACONS_TUNE_WSUM_PARK_KB,
+            "short_path": ada.ADACONS_TUNE_SHORT_PATH}
     tuned = {}
     for kv in args.tune:
         k, v = kv.split("=")

@@ -230,6 +230,11 @@ typedef enum {
                                             tile by tile among the loads.  0: never; 1 (default): where it measured
                                             faster (long fp32 streams of many rows); 8 .. 144: always, with that
                                             many KB of LDS */
+    ADACONS_TUNE_SHORT_PATH = 6,         /* two launches instead of three for N <= 8 and 16-byte aligned rows: stage A3
+                                            adds stage A1's partial sums and runs stage A2 itself (same results, bit
+                                            for bit).  0: never; 1 (default): for gradients of at most 32 MiB, which
+                                            stay in the caches between the passes and are bound by launches, not
+                                            bytes; 2: whenever it applies */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);
@@ -240,8 +245,8 @@ adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);
  * allocates; call it outside any timed region); later adacons_aggregate() calls record an
  * event before stage A1, after the Gram kernel, after A2 and after A3.  adacons_profile_end()
  * waits for the stream, returns the mean duration in milliseconds of the Gram kernel (gram_ms), of
- * the partial-sum reduction + coefficient update (coeff_ms; 0 when the Gram kernel's last
- * workgroup does that work) and of A3 (wsum_ms) over the recorded calls and their count, and
+ * the partial-sum reduction + coefficient update (coeff_ms; 0 for calls on the short path, where
+ * stage A3 does that work) and of A3 (wsum_ms) over the recorded calls and their count, and
  * stops recording.  Any output pointer may be NULL.
  */
 adacons_status adacons_profile_begin(adacons_state *st, int max_calls);

@@ -15,15 +15,21 @@ constexpr int kWave = 64;
 
 // Device-resident part of a coefficient stream (one per adacons_state).
 struct DevState {
-    double m[kNMax];         // EMA of the order statistics, sorted order (Eq. 11)
+    // EMA of the order statistics, sorted order (Eq. 11): two copies, m[parity] is the current one.
+    // Launches in which one workgroup updates the state while others still read it (the short path:
+    // stage A2 inside stage A3) read m[parity ^ 1] and write m[parity] after stage A1 flipped `parity`;
+    // every other update rewrites m[parity] in place.
+    double m[2][kNMax];
     double gamma[kNMax];     // weights applied by the last aggregation (Eq. 12-13)
     double a_raw[kNMax];     // first-order coefficients a_i (Eq. 7)
     double a_smooth[kNMax];  // after the sorted EMA, redistributed to the workers (Eq. 11)
     float gamma32[kNMax];    // gamma rounded for the weighted-sum kernel
     unsigned long long step; // number of coefficient updates so far
     unsigned numeric_flags;  // ADACONS_NUM_* of the last update
-    unsigned pad_;
+    unsigned parity;         // which copy of m is current (0 or 1)
 };
+__device__ inline double *current_m(DevState *ds) { return ds->m[ds->parity & 1u]; }
+__device__ inline const double *current_m(const DevState *ds) { return ds->m[ds->parity & 1u]; }
 static_assert(sizeof(DevState) % sizeof(unsigned) == 0, "DevState is cleared word by word");
 
 struct CoeffParams {
@@ -51,12 +57,14 @@ struct LaunchShape {
     int cached_head_mb; // stage A1: MiB at the head of G read with cache-allocating loads; < 0: all
     int gram_products;  // stage A1, 8 < N <= 64, fp32: value of ADACONS_TUNE_GRAM_PRODUCTS
     int wsum_park_kb;   // stage A3: value of ADACONS_TUNE_WSUM_PARK_KB (LDS for parked output tiles; 0: store tile by tile)
+    bool short_path;    // two launches: stage A1 flips the state's parity and leaves the partial rows to stage A3
 };
 
 // gram.hip
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const GramWork &want, bool with_coeffs, hipStream_t stream,
-                       hipEvent_t between = nullptr);  // `between`: recorded after the main Gram kernel
+                       hipEvent_t between = nullptr,  // `between`: recorded after the main Gram kernel
+                       int *rows_out = nullptr);      // short path (shape.short_path): the number of partial rows written
 hipError_t launch_coeffs(const CoeffParams &cp, double *K, DevState *ds, hipStream_t stream);
 int gram_rows_needed(int N, int num_cu);
 hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t stream);  // K may be NULL
@@ -83,5 +91,10 @@ hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, int num_cu, con
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const float *gamma, float *out, hipStream_t stream,
                        bool apply = false, float lr = 0.f);  // apply: out -= lr * sum
+// Short path (N <= 8, 16-byte aligned rows): stage A3 whose every workgroup first adds the nrows partial rows
+// of stage A1 and runs stage A2 for itself; workgroup 0 writes K and the state.
+hipError_t launch_wsum_short(const void *G, int N, int64_t d, adacons_dtype dtype, const LaunchShape &shape,
+                             const GramWork &work, int nrows, float *out, hipStream_t stream, bool apply = false,
+                             float lr = 0.f);
 
 }  // namespace adacons

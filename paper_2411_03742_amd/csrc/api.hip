@@ -41,6 +41,7 @@ struct adacons_state {
     int tune[ADACONS_TUNE_COUNT_];
     // per-kernel timing (adacons_profile_begin/end)
     std::vector<hipEvent_t> events;  // 4 per call: before A1, after the Gram kernel, after A2, after A3
+    std::vector<unsigned char> prof_short;  // per recorded call: it took the short path (no launch of its own for A2)
     int prof_capacity;
     int prof_calls;
 };
@@ -67,7 +68,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 320, 2, 0, 1};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 320, 2, 0, 1, 1};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 
@@ -114,6 +115,7 @@ LaunchShape shape_of(const adacons_state *st, adacons_tune_key key) {
     s.cached_head_mb = head >= (1 << 20) ? -1 : head;  // a huge value means all of G
     s.gram_products = st->tune[ADACONS_TUNE_GRAM_PRODUCTS];
     s.wsum_park_kb = st->tune[ADACONS_TUNE_WSUM_PARK_KB];
+    s.short_path = false;
     return s;
 }
 
@@ -140,6 +142,38 @@ hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d,
     return launch_gram(G, N, d, dtype, vec_ok, shape, work_of(st), true, s, between);
 }
 
+// Gradients small enough to sit in the caches between the two passes take the short path: two launches,
+// stage A2 inside stage A3 (see wsum_short_kernel).
+constexpr int64_t kShortPathBytes = (int64_t)32 << 20;
+bool takes_short_path(const adacons_state *st, int N, int64_t d, adacons_dtype dtype, bool vec_ok) {
+    const int mode = st->tune[ADACONS_TUNE_SHORT_PATH];
+    if (mode == 0 || N > 8 || !vec_ok) return false;
+    return mode == 2 || (int64_t)N * d * (int64_t)elem_size(dtype) <= kShortPathBytes;
+}
+
+// All three stages of one aggregation on stream s: out = sum, or (apply) out -= lr * sum.
+// ev (or NULL): four events, recorded before A1, after the Gram kernel, after A2, after A3.
+hipError_t enqueue_aggregate(adacons_state *st, const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
+                             float *out, bool apply, float lr, hipStream_t s, hipEvent_t *ev, bool *took_short = nullptr) {
+    hipError_t e = hipSuccess;
+    if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
+    const bool short_path = takes_short_path(st, N, d, dtype, vec_ok);
+    if (took_short) *took_short = short_path;
+    if (short_path) {
+        LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
+        shape.short_path = true;
+        int rows = 0;
+        st->k_valid = true;
+        if ((e = launch_gram(G, N, d, dtype, vec_ok, shape, work_of(st), true, s, ev ? ev[1] : nullptr, &rows)) != hipSuccess) return e;
+        e = launch_wsum_short(G, N, d, dtype, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), work_of(st), rows, out, s, apply, lr);
+    } else {
+        if ((e = launch_first_pass(st, G, N, d, dtype, vec_ok, s, ev ? ev[1] : nullptr)) != hipSuccess) return e;
+        if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
+        e = launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out, s, apply, lr);
+    }
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[3], s);
+    return e;
+}
 
 // Per device: the address of that device's copy of `scratch`, resolved once with the device current.
 struct DeviceScratch {
@@ -276,12 +310,10 @@ adacons_status adacons_aggregate(const void *G, int N, int64_t d, adacons_dtype 
     const bool prof = st->prof_capacity > 0 && st->prof_calls < st->prof_capacity;
     hipEvent_t *ev = prof ? &st->events[(size_t)st->prof_calls * 4] : nullptr;
 
-    if (prof) HIP_TRY(hipEventRecord(ev[0], s));
-    HIP_TRY(launch_first_pass(st, G, N, d, dtype, vec_ok, s, prof ? ev[1] : nullptr));
-    if (prof) HIP_TRY(hipEventRecord(ev[2], s));
-    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, out, s));
+    bool took_short = false;
+    HIP_TRY(enqueue_aggregate(st, G, N, d, dtype, vec_ok, out, false, 0.f, s, ev, &took_short));
     if (prof) {
-        HIP_TRY(hipEventRecord(ev[3], s));
+        st->prof_short[(size_t)st->prof_calls] = took_short ? 1 : 0;
         st->prof_calls += 1;
     }
     return ADACONS_OK;
@@ -294,8 +326,7 @@ adacons_status adacons_aggregate_apply(const void *G, int N, int64_t d, adacons_
     if (rc != ADACONS_OK) return rc;
     if (!std::isfinite(lr)) return fail(ADACONS_EINVAL, "lr is not finite");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    HIP_TRY(launch_first_pass(st, G, N, d, dtype, vec_ok, s, nullptr));
-    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), st->ds->gamma32, w, s, true, lr));
+    HIP_TRY(enqueue_aggregate(st, G, N, d, dtype, vec_ok, w, true, lr, s, nullptr));
     return ADACONS_OK;
 }
 
@@ -399,8 +430,11 @@ adacons_status adacons_state_export(const adacons_state *st, double *m_host, int
     if (!st || !m_host || !step) return fail(ADACONS_EINVAL, "NULL argument");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     unsigned long long t = 0;
-    HIP_TRY(hipMemcpyAsync(m_host, st->ds->m, (size_t)st->N * sizeof(double), hipMemcpyDeviceToHost, s));
+    unsigned parity = 0;
+    HIP_TRY(hipMemcpyAsync(&parity, &st->ds->parity, sizeof parity, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipMemcpyAsync(&t, &st->ds->step, sizeof t, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));   // which of the two copies of m is the current one
+    HIP_TRY(hipMemcpyAsync(m_host, st->ds->m[parity & 1u], (size_t)st->N * sizeof(double), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     *step = (int64_t)t;
     return ADACONS_OK;
@@ -413,7 +447,9 @@ adacons_status adacons_state_import(adacons_state *st, const double *m_host, int
         if (!std::isfinite(m_host[i])) return fail(ADACONS_EINVAL, "m[%d] is not finite", i);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const unsigned long long t = (unsigned long long)step;
-    HIP_TRY(hipMemcpyAsync(st->ds->m, m_host, (size_t)st->N * sizeof(double), hipMemcpyHostToDevice, s));
+    // both copies: whichever is current holds the imported state
+    HIP_TRY(hipMemcpyAsync(st->ds->m[0], m_host, (size_t)st->N * sizeof(double), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(st->ds->m[1], m_host, (size_t)st->N * sizeof(double), hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(&st->ds->step, &t, sizeof t, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     return ADACONS_OK;
@@ -426,6 +462,7 @@ adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value) 
     if ((key == ADACONS_TUNE_GRAM_BLOCKS_PER_CU || key == ADACONS_TUNE_WSUM_BLOCKS_PER_CU) && value > 8)
         return fail(ADACONS_EINVAL, "at most 8 workgroups per CU");
     if (key == ADACONS_TUNE_GRAM_PRODUCTS && value > 2) return fail(ADACONS_EINVAL, "ADACONS_TUNE_GRAM_PRODUCTS takes 0, 1 or 2");
+    if (key == ADACONS_TUNE_SHORT_PATH && value > 2) return fail(ADACONS_EINVAL, "ADACONS_TUNE_SHORT_PATH takes 0, 1 or 2");
     if (key == ADACONS_TUNE_WSUM_PARK_KB && value != 0 && value != 1 && (value < 8 || value > 144))
         return fail(ADACONS_EINVAL, "ADACONS_TUNE_WSUM_PARK_KB takes 0, 1 or 8..144");
     st->tune[key] = value;
@@ -440,6 +477,7 @@ adacons_status adacons_profile_begin(adacons_state *st, int max_calls) {
         HIP_TRY(hipEventCreate(&ev));
         st->events.push_back(ev);
     }
+    st->prof_short.assign((size_t)max_calls, 0);
     st->prof_capacity = max_calls;
     st->prof_calls = 0;
     return ADACONS_OK;
@@ -454,6 +492,11 @@ adacons_status adacons_profile_end(adacons_state *st, double *gram_ms, double *c
         float ms = 0.f;
         HIP_TRY(hipEventElapsedTime(&ms, st->events[4 * c], st->events[4 * c + 1]));
         a += ms;
+        if (st->prof_short[(size_t)c]) {   // stage A2 ran inside stage A3: no time of its own
+            HIP_TRY(hipEventElapsedTime(&ms, st->events[4 * c + 1], st->events[4 * c + 3]));
+            w += ms;
+            continue;
+        }
         HIP_TRY(hipEventElapsedTime(&ms, st->events[4 * c + 1], st->events[4 * c + 2]));
         b += ms;
         HIP_TRY(hipEventElapsedTime(&ms, st->events[4 * c + 2], st->events[4 * c + 3]));
@@ -516,8 +559,7 @@ adacons_status adacons_aggregate_noalloc(const void *G, int N, int64_t d, adacon
     if (rc != ADACONS_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     HIP_TRY(launch_state_load(tmp.ds, N, m_dev, s));
-    HIP_TRY(launch_first_pass(&tmp, G, N, d, dtype, vec_ok, s, nullptr));
-    HIP_TRY(launch_wsum(G, N, d, dtype, vec_ok, shape_of(&tmp, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), tmp.ds->gamma32, out, s));
+    HIP_TRY(enqueue_aggregate(&tmp, G, N, d, dtype, vec_ok, out, false, 0.f, s, nullptr));
     HIP_TRY(launch_state_store(tmp.ds, N, m_dev, coeffs_dev, numeric_flags_dev, s));
     return ADACONS_OK;
 }

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include "adacons_internal.h"
+#include "device_util.h"
 
 namespace adacons {
 
@@ -21,8 +22,13 @@ namespace adacons {
 // m_old: the state entry m[tid] loaded by the caller ahead of time (thread tid < N), so that the
 // global-memory latency of the state overlaps the reduction; it is exchanged through LDS.
 // Core: thread tid < N passes its own q = ||g_tid||^2 and r = <g_tid, sum_j g_j>.
+// m_new: where the updated state goes (NULL: the current copy, in place).  gam_lds (or NULL): receives the
+// weights as fp32, N floats in LDS, for a caller that goes on to apply them.  write = false: compute only,
+// leave the state block alone (workgroups that run the update redundantly beside the one that owns it).
 __device__ inline void update_coefficients_from_stats(double q, double r, DevState *ds, const CoeffParams cp,
-                                                      double *lds, double m_old) {
+                                                      double *lds, double m_old, double *m_new = nullptr,
+                                                      float *gam_lds = nullptr, bool write = true) {
+    if (!m_new) m_new = current_m(ds);
     const int N = cp.N;
     const int tid = threadIdx.x;
     double *m_sh = lds + 2 * N;  // [N]
@@ -59,10 +65,13 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
         nf = ADACONS_NUM_NONFINITE | ADACONS_NUM_UNIFORM_FALLBACK;
         if (tid < N) {
             const double g = 1.0 / (double)N;
-            ds->gamma[tid] = g;
-            ds->gamma32[tid] = (float)g;
-            ds->a_raw[tid] = a;
-            ds->a_smooth[tid] = a;
+            if (gam_lds) gam_lds[tid] = (float)g;
+            if (write) {
+                ds->gamma[tid] = g;
+                ds->gamma32[tid] = (float)g;
+                ds->a_raw[tid] = a;
+                ds->a_smooth[tid] = a;
+            }
         }
     } else {
         if (s_zero) nf |= ADACONS_NUM_ZERO_NORM;
@@ -78,7 +87,7 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
             }
             // ranks are a permutation of 0..N-1: every state entry has exactly one writer
             const double mk = cp.beta * m_sh[rank] + (1.0 - cp.beta) * a;
-            ds->m[rank] = mk;
+            if (write) m_new[rank] = mk;
             as = mk;
         }
         double c = 0.0;
@@ -109,13 +118,16 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
             }
         }
         if (tid < N) {
-            ds->gamma[tid] = g;
-            ds->gamma32[tid] = (float)g;
-            ds->a_raw[tid] = a;
-            ds->a_smooth[tid] = as;
+            if (gam_lds) gam_lds[tid] = (float)g;
+            if (write) {
+                ds->gamma[tid] = g;
+                ds->gamma32[tid] = (float)g;
+                ds->a_raw[tid] = a;
+                ds->a_smooth[tid] = as;
+            }
         }
     }
-    if (tid == 0) {
+    if (tid == 0 && write) {
         ds->numeric_flags = nf;
         ds->step += 1ull;
     }
@@ -123,14 +135,71 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
 
 // From the Gram matrix: q_i is its diagonal, r_i its row sum (j ascending).
 __device__ inline void update_coefficients(const double *K, DevState *ds, const CoeffParams cp, double *lds,
-                                           double m_old) {
+                                           double m_old, double *m_new = nullptr, float *gam_lds = nullptr,
+                                           bool write = true) {
     const int N = cp.N, tid = threadIdx.x;
     double q = 0.0, r = 0.0;
     if (tid < N) {
         q = K[(size_t)tid * N + tid];
         for (int j = 0; j < N; ++j) r += K[(size_t)tid * N + j];
     }
-    update_coefficients_from_stats(q, r, ds, cp, lds, m_old);
+    update_coefficients_from_stats(q, r, ds, cp, lds, m_old, m_new, gam_lds, write);
+}
+
+// Unpack p (position in the packed upper triangle) into (i, j), i <= j.
+__device__ __forceinline__ void unpack_pair(int p, int N, int &i, int &j) {
+    int row = 0, left = p;
+    while (left >= N - row) {
+        left -= N - row;
+        ++row;
+    }
+    i = row;
+    j = row + left;
+}
+
+// K[i][j] = K[j][i] = sum over rows of partials[.][p]: min(kReduceThreads / np, 32) interleaved sub-sums per
+// pair, added in slice order.  One workgroup of any size, N(N+1)/2 <= kReduceThreads: the work is laid out
+// for kReduceThreads threads and a smaller workgroup takes several of those shares per thread, so that the
+// sums, and with them every bit of K, do not depend on the size of the workgroup that forms them.
+// lds >= kReduceThreads doubles.  K (global, or NULL) and K_lds (or NULL) receive the N x N matrix.
+// BD: the workgroup's size (a divisor of kReduceThreads).
+constexpr int kReduceThreads = 1024;
+template <int BD>
+__device__ inline void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds,
+                                           double *K_lds = nullptr) {
+    static_assert(kReduceThreads % BD == 0, "whole shares per thread");
+    const int np = num_pairs(N);
+    // at most 32 slices: the slice sums are added one after the other by a single thread per pair
+    const int slices = (kReduceThreads / np < 32) ? kReduceThreads / np : 32;
+    // the shares of one thread are independent of each other: unrolled, their loads go out together
+    double sub[kReduceThreads / BD];
+#pragma unroll
+    for (int k = 0; k < kReduceThreads / BD; ++k) {
+        const int vt = k * BD + (int)threadIdx.x;
+        const int s = vt / np, p = vt - s * np;
+        sub[k] = (vt < slices * np) ? sum_rows(partials, np, p, s, slices, nrows) : 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < kReduceThreads / BD; ++k) {
+        const int vt = k * BD + (int)threadIdx.x;
+        if (vt < slices * np) lds[vt] = sub[k];   // vt = s * np + p
+    }
+    __syncthreads();
+    for (int p = threadIdx.x; p < np; p += blockDim.x) {
+        double tot = 0.0;
+        for (int q = 0; q < slices; ++q) tot += lds[q * np + p];
+        int i, j;
+        unpack_pair(p, N, i, j);
+        if (K) {
+            K[(size_t)i * N + j] = tot;
+            K[(size_t)j * N + i] = tot;
+        }
+        if (K_lds) {
+            K_lds[i * N + j] = tot;
+            K_lds[j * N + i] = tot;
+        }
+    }
+    __syncthreads();
 }
 
 }  // namespace adacons

@@ -27,44 +27,6 @@ namespace adacons {
 // Reduction of the partial rows and the coefficient update
 // ------------------------------------------------------------------------------------------
 
-// Unpack p (position in the packed upper triangle) into (i, j), i <= j.
-__device__ __forceinline__ void unpack_pair(int p, int N, int &i, int &j) {
-    int row = 0, left = p;
-    while (left >= N - row) {
-        left -= N - row;
-        ++row;
-    }
-    i = row;
-    j = row + left;
-}
-
-// K[i][j] = K[j][i] = sum over rows of partials[.][p]: min(blockDim.x / np, 32) interleaved sub-sums per
-// pair, added in slice order.  One workgroup, N(N+1)/2 <= blockDim.x; lds >= blockDim.x doubles.
-// When K_lds is given, K is also left there (N x N) for the coefficient update that follows.
-__device__ void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds,
-                                    double *K_lds = nullptr) {
-    const int np = num_pairs(N);
-    const int tid = threadIdx.x;
-    // at most 32 slices: the slice sums are added one after the other by a single thread per pair
-    const int slices = ((int)blockDim.x / np < 32) ? (int)blockDim.x / np : 32;
-    const int s = tid / np, p = tid - s * np;
-    if (s < slices) lds[s * np + p] = sum_rows(partials, np, p, s, slices, nrows);
-    __syncthreads();
-    if (tid < np) {
-        double tot = 0.0;
-        for (int q = 0; q < slices; ++q) tot += lds[q * np + tid];
-        int i, j;
-        unpack_pair(tid, N, i, j);
-        K[(size_t)i * N + j] = tot;
-        K[(size_t)j * N + i] = tot;
-        if (K_lds) {
-            K_lds[i * N + j] = tot;
-            K_lds[j * N + i] = tot;
-        }
-    }
-    __syncthreads();
-}
-
 // Reduction of the partial rows as a launch of its own (large N: more pairs than one workgroup
 // has threads).  Workgroup c owns pairs [16 c, 16 c + 16); sixteen interleaved sub-sums per pair
 // (rows s, s + 16, ...), added in slice order.
@@ -94,8 +56,8 @@ __global__ void __launch_bounds__(kFinishBlock)
 finish_kernel(const double *partials, int nrows, double *K, DevState *ds, CoeffParams cp, int with_coeffs) {
     __shared__ double lds[kFinishBlock];
     __shared__ double K_lds[kFinishMaxN * kFinishMaxN];
-    const double m_old = ((int)threadIdx.x < cp.N) ? ds->m[threadIdx.x] : 0.0;
-    reduce_partial_rows(partials, nrows, cp.N, K, lds, K_lds);
+    const double m_old = ((int)threadIdx.x < cp.N) ? current_m(ds)[threadIdx.x] : 0.0;
+    reduce_partial_rows<kFinishBlock>(partials, nrows, cp.N, K, lds, K_lds);
     if (with_coeffs) update_coefficients(K_lds, ds, cp, lds, m_old);
 }
 
@@ -108,7 +70,7 @@ __global__ void __launch_bounds__(kBlock) coeff_kernel(const double *K, DevState
     __shared__ double part[4][ADACONS_GRAM_N_MAX];
     static_assert(4 * ADACONS_GRAM_N_MAX <= kBlock, "four threads per row");
     const int N = cp.N, tid = threadIdx.x;
-    const double m_old = (tid < N) ? ds->m[tid] : 0.0;
+    const double m_old = (tid < N) ? current_m(ds)[tid] : 0.0;
     const int row = tid >> 2, quarter = tid & 3;
     if (row < N) {
         double acc = 0.0;
@@ -151,15 +113,48 @@ __device__ __forceinline__ void gram_vec_step(const T *__restrict__ G, int64_t d
     }
 }
 
-template <int N, typename T, int VEC>
+// U column groups per thread at a time: the N U loads are issued together, then the products of the
+// groups in ascending order -- the same sums in the same order as U single steps.
+template <int N, typename T, int VEC, bool NT, int U>
+__device__ __forceinline__ void gram_vec_steps(const T *__restrict__ G, int64_t d, int64_t g, int64_t stride,
+                                               double (&acc)[N * (N + 1) / 2]) {
+    float v[U][N][VEC];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < N; ++i) load_vec<T, VEC, NT>(G + (int64_t)i * d + (g + u * stride) * VEC, v[u][i]);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            double x[N];
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = (double)v[u][i][c];
+            int p = 0;
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+#pragma unroll
+                for (int j = i; j < N; ++j) {
+                    acc[p] = fma(x[i], x[j], acc[p]);
+                    ++p;
+                }
+        }
+}
+
+// U > 1 (the short path: G of a few megabytes, a handful of sweeps per thread): the loads of U sweeps
+// are in flight together, so a thread waits for memory once or twice instead of once per sweep.
+// flip (or NULL): the state block whose parity word workgroup 0 flips -- the short path's stage A3
+// then reads the old copy of the momentum state and writes the other one.
+template <int N, typename T, int VEC, int U>
 __global__ void __launch_bounds__(kBlock, 2)
 gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cached_groups,
-                double *__restrict__ partials) {
+                double *__restrict__ partials, DevState *flip) {
     constexpr int NP = N * (N + 1) / 2;
     __shared__ double lds[(4 * NP > kBlock) ? 4 * NP : kBlock];
     double acc[NP];
 #pragma unroll
     for (int p = 0; p < NP; ++p) acc[p] = 0.0;
+    if (flip && blockIdx.x == 0 && threadIdx.x == 0) flip->parity ^= 1u;
 
     // The head of G is read with ordinary loads, so that it stays in the memory-side cache for
     // the second pass (which starts there); the rest streams through with non-temporal loads.
@@ -168,6 +163,8 @@ gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cac
     const int slot = xcd_contiguous_slot((int)blockIdx.x, (int)gridDim.x);
     int64_t g = (int64_t)slot * kBlock + threadIdx.x;
     const int64_t head_end = cached_groups < ngroups ? cached_groups : ngroups;
+    if constexpr (U > 1)
+        for (; g + (U - 1) * stride < head_end; g += U * stride) gram_vec_steps<N, T, VEC, false, U>(G, d, g, stride, acc);
     for (; g < head_end; g += stride) gram_vec_step<N, T, VEC, false>(G, d, g, acc);
     for (; g < ngroups; g += stride) gram_vec_step<N, T, VEC, true>(G, d, g, acc);
 
@@ -636,33 +633,41 @@ int gram_rows_needed(int N, int num_cu) {
 // dcols: the columns this launch covers, a multiple of VEC (rows are d elements apart).
 template <int N, typename T, int VEC>
 static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchShape &shape, double *partials,
-                          hipStream_t s, int *grid_out) {
-    static const int occ = occupancy(gram_vec_kernel<N, T, VEC>);
+                          DevState *ds, hipStream_t s, int *grid_out) {
+    static const int occ = occupancy(gram_vec_kernel<N, T, VEC, 1>);
     const int64_t ngroups = dcols / VEC;
     // measured best: one workgroup per CU for fp32, two for bf16 (twice the FMAs per byte)
     const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ, sizeof(T) == 2 ? 2 : 1);
     *grid_out = grid;
+    if (shape.short_path) {
+        // same grid, same columns per thread, same order of the sums as the kernel below: K comes out bit for
+        // bit the same; everything with ordinary loads (stage A3 finds G in the caches)
+        constexpr int U = (N * VEC <= 16) ? 4 : 2;   // sixteen 128-bit loads in flight per thread
+        hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, U>), dim3(grid), dim3(kBlock), 0, s,
+                           static_cast<const T *>(G), d, ngroups, ngroups, partials, ds);
+        return hipGetLastError();
+    }
     // shape.cached_head_mb < 0: everything with ordinary loads
     int64_t cached_groups = ngroups;
     if (shape.cached_head_mb >= 0)
         cached_groups = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
-    hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC>), dim3(grid), dim3(kBlock), 0, s,
-                       static_cast<const T *>(G), d, ngroups, cached_groups, partials);
+    hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, 1>), dim3(grid), dim3(kBlock), 0, s,
+                       static_cast<const T *>(G), d, ngroups, cached_groups, partials, static_cast<DevState *>(nullptr));
     return hipGetLastError();
 }
 
 template <typename T, int VEC>
 static hipError_t dispatch_vec(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                               double *partials, hipStream_t s, int *grid_out) {
+                               double *partials, DevState *ds, hipStream_t s, int *grid_out) {
     switch (N) {
-        case 1: return run_vec<1, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
-        case 2: return run_vec<2, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
-        case 3: return run_vec<3, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
-        case 4: return run_vec<4, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
-        case 5: return run_vec<5, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
-        case 6: return run_vec<6, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
-        case 7: return run_vec<7, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
-        case 8: return run_vec<8, T, VEC>(G, d, dcols, shape, partials, s, grid_out);
+        case 1: return run_vec<1, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
+        case 2: return run_vec<2, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
+        case 3: return run_vec<3, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
+        case 4: return run_vec<4, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
+        case 5: return run_vec<5, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
+        case 6: return run_vec<6, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
+        case 7: return run_vec<7, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
+        case 8: return run_vec<8, T, VEC>(G, d, dcols, shape, partials, ds, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
@@ -764,7 +769,8 @@ gram_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, double
 // launch for N <= 44, a multi-workgroup reduction followed by coeff_kernel above.
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape_in, const GramWork &want, bool with_coeffs, hipStream_t stream,
-                       hipEvent_t between) {
+                       hipEvent_t between, int *rows_out) {
+    if (shape_in.short_path && (N > 8 || !vec_ok || !rows_out)) return hipErrorInvalidValue;
     // Without 16-byte aligned rows (vec_ok false) the same 128-bit kernels run from element-aligned
     // addresses over the whole groups of every row, and the columns left over (fewer than one group) go
     // through gram_edge_kernel into one more partial row.
@@ -778,8 +784,8 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
     int grid = 0;
     hipError_t e;
     if (N <= 8) {
-        e = (dtype == ADACONS_F32) ? dispatch_vec<float, 4>(G, N, d, dcols, shape, want.partials, stream, &grid)
-                                   : dispatch_vec<bf16_bits, 8>(G, N, d, dcols, shape, want.partials, stream, &grid);
+        e = (dtype == ADACONS_F32) ? dispatch_vec<float, 4>(G, N, d, dcols, shape, want.partials, want.ds, stream, &grid)
+                                   : dispatch_vec<bf16_bits, 8>(G, N, d, dcols, shape, want.partials, want.ds, stream, &grid);
     } else {
         e = (dtype == ADACONS_F32) ? dispatch_mfma<float>(G, N, d, dcols, shape, want.partials, stream, &grid)
                                    : dispatch_mfma<bf16_bits>(G, N, d, dcols, shape, want.partials, stream, &grid);
@@ -797,6 +803,10 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
     }
     if (e == hipSuccess && between) e = hipEventRecord(between, stream);
     if (e != hipSuccess) return e;
+    if (shape.short_path) {   // stage A3 adds the rows and runs stage A2 itself
+        *rows_out = grid;
+        return hipSuccess;
+    }
     if (N <= kFinishMaxN) {
         hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kFinishBlock), 0, stream, want.partials, grid, want.K,
                            want.ds, want.cp, with_coeffs ? 1 : 0);
@@ -827,8 +837,12 @@ hipError_t launch_clear_state(DevState *ds, double *K, int nn, hipStream_t strea
 // works in the library's file-scope scratch array keeps no state of its own between calls).
 __global__ void __launch_bounds__(kNMax) state_load_kernel(DevState *ds, int N, const double *__restrict__ m_in) {
     const int i = threadIdx.x;
-    ds->m[i] = (i < N) ? m_in[i] : 0.0;
-    if (i == 0) ds->numeric_flags = 0u;
+    ds->m[0][i] = (i < N) ? m_in[i] : 0.0;
+    ds->m[1][i] = 0.0;
+    if (i == 0) {
+        ds->numeric_flags = 0u;
+        ds->parity = 0u;
+    }
 }
 
 __global__ void __launch_bounds__(kNMax)
@@ -836,7 +850,7 @@ state_store_kernel(const DevState *ds, int N, double *__restrict__ m_out, double
                    unsigned *__restrict__ numeric_flags) {
     const int i = threadIdx.x;
     if (i < N) {
-        m_out[i] = ds->m[i];
+        m_out[i] = current_m(ds)[i];
         if (coeffs) {
             coeffs[i] = ds->gamma[i];
             coeffs[N + i] = ds->a_raw[i];

@@ -310,7 +310,7 @@ finish_layers_kernel(const double *__restrict__ partials, const int *__restrict_
     const bool stats = cp.N > kLayersMaxN;                   // rows hold [q, r] instead of the packed K
     const int l = blockIdx.x, N = cp.N, np = stats ? 2 * N : num_pairs(N);
     DevState *ds = ds_all + l;
-    const double m_old = ((int)threadIdx.x < N) ? ds->m[threadIdx.x] : 0.0;
+    const double m_old = ((int)threadIdx.x < N) ? current_m(ds)[threadIdx.x] : 0.0;
     const int e0 = layer_entry0[l], e1 = layer_entry0[l + 1];
     // interleaved sub-sums over this layer's entries (entry order inside a slice), then the slices in order
     __shared__ double slice_sum[kLayerFinishBlock];

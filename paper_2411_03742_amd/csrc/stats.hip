@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(kStatsFinishBlock)
 stats_finish_kernel(const double *partials, int nrows, DevState *ds, CoeffParams cp) {
     __shared__ double lds[kStatsFinishBlock];
     const int N = cp.N, np = 2 * N, tid = threadIdx.x;
-    const double m_old = (tid < N) ? ds->m[tid] : 0.0;
+    const double m_old = (tid < N) ? current_m(ds)[tid] : 0.0;
     const int slices = kStatsFinishBlock / np;
     const int s = tid / np, p = tid - s * np;
     if (s < slices) lds[s * np + p] = sum_rows(partials, np, p, s, slices, nrows);

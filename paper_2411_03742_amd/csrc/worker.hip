@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(kBlock) coeff_stats_kernel(const double *__res
                                                              DevState *ds, CoeffParams cp) {
     __shared__ double lds[3 * kNMax];
     const int tid = threadIdx.x;
-    const double m_old = (tid < cp.N) ? ds->m[tid] : 0.0;
+    const double m_old = (tid < cp.N) ? current_m(ds)[tid] : 0.0;
     update_coefficients_from_stats(tid < cp.N ? q[tid] : 0.0, tid < cp.N ? r[tid] : 0.0, ds, cp, lds, m_old);
 }
 

@@ -6,6 +6,7 @@
 // here and `out` is not read back by this library, so both use non-temporal accesses.  The tiles are
 // walked forwards: the pass starts on the head of G, which stage A1 left in the memory-side cache.
 #include "adacons_internal.h"
+#include "coeff_device.h"
 #include "device_util.h"
 
 namespace adacons {
@@ -315,6 +316,131 @@ static hipError_t dispatch(const void *G, int N, int64_t d, int64_t dcols, const
         case 16: return run<16, T, VEC, 1>(G, N, d, dcols, shape, gamma, out, m, s);  // 16 loads in flight already
         default: return run<0, T, VEC, UNR>(G, N, d, dcols, shape, gamma, out, m, s);
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Short path: stage A2 inside stage A3
+// ------------------------------------------------------------------------------------------
+// For gradients of a few megabytes the three launches of an aggregation cost more than the bytes
+// (measured at N = 4, d = 2^20: 13 us a step, of which the launch of stage A2 alone is 2-3 us, against
+// 6 us for the traffic).  Here stage A3 does stage A2's work itself: every workgroup requests its first
+// tile of G, then -- while those loads are in flight -- adds the partial rows stage A1 left (the same
+// sums in the same order as finish_kernel, so K is the same bit for bit) and runs the coefficient
+// update; all workgroups arrive at the same weights, workgroup 0 alone writes K and the state.  The
+// momentum state is read from the copy stage A1 retired (parity flipped there) and written to the
+// other one, so no workgroup reads what workgroup 0 writes in this launch.
+template <int N, typename T, int VEC, int UNR, bool APPLY>
+__global__ void __launch_bounds__(kBlock)
+wsum_short_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, const double *__restrict__ partials, int nrows,
+                  double *__restrict__ K, DevState *ds, CoeffParams cp, float *__restrict__ out, float lr) {
+    __shared__ double lds[kReduceThreads];
+    __shared__ double K_lds[8 * 8];
+    __shared__ float gam_lds[8];
+    static_assert(N <= 8, "the short path serves N <= 8");
+    constexpr int64_t kTile = (int64_t)kBlock * UNR;
+    const int64_t ntiles = (ngroups + kTile - 1) / kTile;
+    const int grid = (int)gridDim.x, b = (int)blockIdx.x;
+    const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;   // XCD-contiguous tiles, as in wsum_kernel
+
+    float v[UNR][N][VEC];
+    bool live[UNR];
+    auto load_tile = [&](int64_t t) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t grp = t * kTile + (int64_t)u * kBlock + threadIdx.x;
+            live[u] = grp < ngroups;
+            const int64_t gc = live[u] ? grp : ngroups - 1;   // clamped: in bounds, the sums are not stored
+#pragma unroll
+            for (int i = 0; i < N; ++i) load_vec<T, VEC, true>(G + (int64_t)i * d + gc * VEC, v[u][i]);
+        }
+    };
+    int64_t t = slot;
+    if (t < ntiles) load_tile(t);
+
+    // stage A2 (the loads above are in flight meanwhile)
+    const int tid = threadIdx.x;
+    const bool writer = blockIdx.x == 0;
+    // both copies of the state are requested before the parity word is known, and the partial rows with
+    // them: one memory latency for the whole of stage A2's input, not three in a row
+    const unsigned parity = ds->parity;            // flipped by stage A1 of this call
+    const double m0 = (tid < N) ? ds->m[0][tid] : 0.0, m1 = (tid < N) ? ds->m[1][tid] : 0.0;
+    reduce_partial_rows<kBlock>(partials, nrows, N, writer ? K : nullptr, lds, K_lds);
+    const unsigned cur = parity & 1u;
+    double *m_cur = ds->m[cur];
+    const double m_old = cur ? m0 : m1;            // the copy stage A1 retired
+    // entries the update leaves alone (momentum off, a non-finite statistic) carry over to the new copy
+    if (writer && tid < N) m_cur[tid] = m_old;
+    CoeffParams cpn = cp;
+    cpn.N = N;
+    update_coefficients(K_lds, ds, cpn, lds, m_old, m_cur, gam_lds, writer);
+    __syncthreads();
+    float w[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) w[i] = gam_lds[i];
+
+    while (t < ntiles) {
+        float acc[UNR][VEC];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w[i], v[u][i][c], acc[u][c]);
+        }
+        const int64_t base = t * kTile + threadIdx.x;
+        bool was_live[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) was_live[u] = live[u];
+        t += grid;
+        if (t < ntiles) load_tile(t);   // the next tile's loads before this tile's stores
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+            if (was_live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * kBlock) * VEC, acc[u], lr);
+    }
+}
+
+template <int N, typename T, int VEC>
+static hipError_t run_short(const void *G, int64_t d, const LaunchShape &shape, const GramWork &work, int nrows,
+                            float *out, bool apply, float lr, hipStream_t s) {
+    constexpr int UNR = (N * VEC <= 32) ? 2 : 1;   // at most sixteen 128-bit loads in flight per thread
+    const int64_t ngroups = d / VEC;
+    const int64_t ntiles = (ngroups + (int64_t)kBlock * UNR - 1) / ((int64_t)kBlock * UNR);
+    const int per_cu = shape.blocks_per_cu > 0 ? shape.blocks_per_cu : 8;
+    int64_t grid = (int64_t)shape.num_cu * per_cu;
+    if (grid > ntiles) grid = ntiles;
+    if (grid < 1) grid = 1;
+    if (apply)
+        hipLaunchKernelGGL((wsum_short_kernel<N, T, VEC, UNR, true>), dim3((unsigned)grid), dim3(kBlock), 0, s,
+                           static_cast<const T *>(G), d, ngroups, work.partials, nrows, work.K, work.ds, work.cp, out, lr);
+    else
+        hipLaunchKernelGGL((wsum_short_kernel<N, T, VEC, UNR, false>), dim3((unsigned)grid), dim3(kBlock), 0, s,
+                           static_cast<const T *>(G), d, ngroups, work.partials, nrows, work.K, work.ds, work.cp, out, 0.f);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+static hipError_t dispatch_short(const void *G, int N, int64_t d, const LaunchShape &shape, const GramWork &work,
+                                 int nrows, float *out, bool apply, float lr, hipStream_t s) {
+    switch (N) {
+        case 1: return run_short<1, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        case 2: return run_short<2, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        case 3: return run_short<3, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        case 4: return run_short<4, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        case 5: return run_short<5, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        case 6: return run_short<6, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        case 7: return run_short<7, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        case 8: return run_short<8, T, VEC>(G, d, shape, work, nrows, out, apply, lr, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// Rows and output 16-byte aligned, d a multiple of the vector width (the caller checks).
+hipError_t launch_wsum_short(const void *G, int N, int64_t d, adacons_dtype dtype, const LaunchShape &shape,
+                             const GramWork &work, int nrows, float *out, hipStream_t stream, bool apply, float lr) {
+    return (dtype == ADACONS_F32) ? dispatch_short<float, 4>(G, N, d, shape, work, nrows, out, apply, lr, stream)
+                                  : dispatch_short<bf16_bits, 8>(G, N, d, shape, work, nrows, out, apply, lr, stream);
 }
 
 // The last d - col0 < 8 columns, which no whole 128-bit group covers: one thread per column.

@@ -224,6 +224,73 @@ def test_runs_are_bit_identical(pkg):
     assert np.array_equal(gams[0], gams[1]) and np.array_equal(gams[0], gams[2])
 
 
+@pytest.mark.parametrize("N,d,dtype,flags", [(4, 1 << 20, torch.float32, 3), (8, 500_000, torch.float32, 3),
+                                             (8, 400_008, torch.bfloat16, 3), (1, 4096, torch.float32, 3),
+                                             (5, 100_004, torch.float32, 0), (7, 33_336, torch.bfloat16, 7),
+                                             (2, 8, torch.float32, 11), (3, 2_000_004, torch.float32, 1)])
+def test_short_path_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags):
+    """ADACONS_TUNE_SHORT_PATH: stage A2 inside stage A3 (two launches, the momentum state double-buffered)
+    against the three-launch path on the same stream of inputs: output, coefficients, K and the carried
+    state must be equal bit for bit -- over regular steps, a zero row, a non-finite step (state left
+    untouched) and a regular step after it -- and the fused descent step likewise."""
+    short, plain = pkg.AdaCons(N, d, beta=0.9, flags=flags), pkg.AdaCons(N, d, beta=0.9, flags=flags)
+    short.tune(pkg.ADACONS_TUNE_SHORT_PATH, 2)
+    plain.tune(pkg.ADACONS_TUNE_SHORT_PATH, 0)
+    ost = o.OracleState(N, beta=0.9, flags=flags)
+    for t in range(6):
+        G = randG(N, d, dtype, sigma=2.0, seed=900 + t)
+        if t == 2:
+            G[N - 1].zero_()
+        if t == 3:
+            G[0, min(d - 1, 77)] = float("inf")
+        a, b = short.aggregate(G).clone(), plain.aggregate(G).clone()
+        ia, ib = short.coeffs(), plain.coeffs()
+        assert torch.equal(a, b) or t == 3      # a non-finite input: NaN/Inf positions agree, compared below
+        if t == 3:
+            assert torch.equal(torch.isfinite(a), torch.isfinite(b)) and torch.equal(a[torch.isfinite(a)], b[torch.isfinite(b)])
+        for key in ("gamma", "raw", "smoothed"):
+            assert np.array_equal(ia[key], ib[key], equal_nan=True), (t, key)
+        assert ia["numeric_flags"] == ib["numeric_flags"]
+        Ka, Kb = pkg.adacons_read_gram(short._st, N, None), pkg.adacons_read_gram(plain._st, N, None)
+        assert np.array_equal(Ka, Kb, equal_nan=True)
+        (ma, sa), (mb, sb) = short.export_state(), plain.export_state()
+        assert np.array_equal(ma, mb) and sa == sb == t + 1
+        # and against the oracle, like every other path
+        state_was_zero = not ost.m.any()
+        Gh = workloads.to_oracle_input(G)
+        oout, oinfo = o.aggregate(Gh, ost, want_out=(t != 3))
+        check_coefficients(ia, oinfo, ost.m, ost.flags, state_was_zero, ties_possible=(N == 1))
+        if t != 3:
+            check_out(a.cpu().numpy(), Gh, ia, oout, True)
+    w1, w2 = torch.randn(d, device=DEV), None
+    w2 = w1.clone()
+    G = randG(N, d, dtype, sigma=2.0, seed=990)
+    short.aggregate_apply(G, w1, lr=0.3)
+    plain.aggregate_apply(G, w2, lr=0.3)
+    assert torch.equal(w1, w2)
+    # checkpoint taken on one path resumes on the other
+    m, step = short.export_state()
+    plain.import_state(m, step)
+    G = randG(N, d, dtype, sigma=2.0, seed=991)
+    assert torch.equal(short.aggregate(G), plain.aggregate(G))
+    short.close(); plain.close()
+
+
+def test_short_path_is_the_default_for_small_gradients_only(pkg):
+    """Up to 32 MiB of gradients (N <= 8, aligned rows) take two launches, larger ones three: seen through
+    the per-stage timing, which reports no time of its own for stage A2 on the short path."""
+    for N, d, short in [(4, 1 << 20, True), (8, 1 << 20, True), (8, (1 << 20) + 4, False), (16, 1000, False), (4, 1001, False)]:
+        agg = pkg.AdaCons(N, d)
+        G = randG(N, d, seed=1)
+        agg.aggregate(G)
+        agg.profile_begin(20)
+        for _ in range(20):
+            agg.aggregate(G)
+        prof = agg.profile_end()
+        assert (prof["coeff_ms"] == 0.0) == short, (N, d, prof)
+        agg.close()
+
+
 @pytest.mark.parametrize("per_cu", [1, 2, 3])
 def test_launch_shape_does_not_change_results_beyond_rounding(pkg, per_cu):
     N, d = 8, 2_000_000
