@@ -127,6 +127,9 @@ def main() -> int:
         tuned[k] = int(v)
 
     stream = torch.cuda.current_stream()
+    # what this machine delivers for a read-only stream and a copy of the same buffers (context for the roofline
+    # fraction): measured first, ahead of the warm-up steps
+    ceilings = measured_ceilings(w, bufs, out, stream) if not args.no_ceilings else None
     for i in range(args.warmup):
         agg.aggregate(bufs[i % 2], out=out, stream=stream)
     torch.cuda.synchronize()
@@ -219,8 +222,6 @@ def main() -> int:
     per_call = sorted(a.elapsed_time(b) for a, b in pairs)
     pct = lambda q: round(per_call[min(ncall - 1, int(q * ncall))], 5)
     per_call_ms = {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "calls": ncall}
-
-    ceilings = measured_ceilings(w, bufs, out, stream) if not args.no_ceilings else None
 
     if args.copy_calibration > 0:
         scratch = torch.empty_like(bufs[0])
