@@ -402,7 +402,8 @@ gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, 
 // wavefronts are disjoint, so each scatters its own sums into the workgroup's partial row without a
 // reduction between them.  Measured on N = 64, d = 25,557,032: 1.06 ms against 1.12 ms for one
 // wavefront per chunk; four wavefronts per chunk (110 registers, sixteen wavefronts per CU) 1.18 ms, six
-// workgroups of two per CU 1.15 ms.
+// workgroups of two per CU 1.15 ms; workgroups that walk runs of 2 / 4 / 8 consecutive chunks (so that a
+// line two chunks share is asked for twice by the same workgroup) 1.07 / 1.08 / 1.08 ms.
 
 // Which of the two wavefronts owns tile pair p (pairs in row-major upper-triangle order): the first
 // half of the pairs, which share the first row tiles, and the second half.
@@ -642,7 +643,8 @@ static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchS
     if (shape.short_path) {
         // same grid, same columns per thread, same order of the sums as the kernel below: K comes out bit for
         // bit the same; everything with ordinary loads (stage A3 finds G in the caches)
-        constexpr int U = (N * VEC <= 16) ? 4 : 2;   // sixteen 128-bit loads in flight per thread
+        // sixteen 128-bit loads in flight per thread where the widened values fit the registers
+        constexpr int U = (N * VEC <= 16) ? 4 : (N * VEC <= 32 ? 2 : 1);
         hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, U>), dim3(grid), dim3(kBlock), 0, s,
                            static_cast<const T *>(G), d, ngroups, ngroups, partials, ds);
         return hipGetLastError();
