@@ -645,6 +645,15 @@ static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchS
         // bit the same; everything with ordinary loads (stage A3 finds G in the caches)
         // sixteen 128-bit loads in flight per thread where the widened values fit the registers
         constexpr int U = (N * VEC <= 16) ? 4 : (N * VEC <= 32 ? 2 : 1);
+        // forced on a stream too long for the caches: the cached-head policy of the long path
+        int64_t head = ngroups;
+        if ((int64_t)N * dcols * (int64_t)sizeof(T) > ((int64_t)32 << 20) && shape.cached_head_mb >= 0)
+            head = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
+        if (head < ngroups) {
+            hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, 1>), dim3(grid), dim3(kBlock), 0, s,
+                               static_cast<const T *>(G), d, ngroups, head, partials, ds);
+            return hipGetLastError();
+        }
         hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, U>), dim3(grid), dim3(kBlock), 0, s,
                            static_cast<const T *>(G), d, ngroups, ngroups, partials, ds);
         return hipGetLastError();
