@@ -119,7 +119,8 @@ def main() -> int:
             "gram_products": ada.ADACONS_TUNE_GRAM_PRODUCTS,
             "stats_only": ada.ADACONS_TUNE_STATS_ONLY,
             "wsum_park_kb": ada.ADACONS_TUNE_WSUM_PARK_KB,
-            "short_path": ada.ADACONS_TUNE_SHORT_PATH}
+            "short_path": ada.ADACONS_TUNE_SHORT_PATH,
+            "wsum_row_slices": ada.ADACONS_TUNE_WSUM_ROW_SLICES}
     tuned = {}
     for kv in args.tune:
         k, v = kv.split("=")

@@ -235,6 +235,11 @@ typedef enum {
                                             for bit).  0: never; 1 (default): for gradients of at most 32 MiB, which
                                             stay in the caches between the passes and are bound by launches, not
                                             bytes; 2: whenever it applies */
+    ADACONS_TUNE_WSUM_ROW_SLICES = 7,    /* A3 for many workers with few parameters each (N >= 16): the rows are
+                                            shared out over the sixteen wavefronts of a workgroup, which adds their
+                                            partial sums in wavefront order, instead of one thread walking all N
+                                            rows of its columns.  0: never; 1 (default): where it measured faster;
+                                            2: whenever N >= 16 */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);

@@ -29,6 +29,7 @@ ADACONS_TUNE_GRAM_PRODUCTS = 3
 ADACONS_TUNE_STATS_ONLY = 4
 ADACONS_TUNE_WSUM_PARK_KB = 5
 ADACONS_TUNE_SHORT_PATH = 6
+ADACONS_TUNE_WSUM_ROW_SLICES = 7
 
 EXPORTS = [
     "adacons_init_state", "adacons_destroy_state", "adacons_reset_state", "adacons_aggregate",

@@ -57,6 +57,7 @@ struct LaunchShape {
     int cached_head_mb; // stage A1: MiB at the head of G read with cache-allocating loads; < 0: all
     int gram_products;  // stage A1, 8 < N <= 64, fp32: value of ADACONS_TUNE_GRAM_PRODUCTS
     int wsum_park_kb;   // stage A3: value of ADACONS_TUNE_WSUM_PARK_KB (LDS for parked output tiles; 0: store tile by tile)
+    int wsum_row_slices; // stage A3: value of ADACONS_TUNE_WSUM_ROW_SLICES
     bool short_path;    // two launches: stage A1 flips the state's parity and leaves the partial rows to stage A3
 };
 

@@ -68,7 +68,7 @@ adacons_status hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call); \
     } while (0)
 
-const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 320, 2, 0, 1, 1};
+const int kTuneDefault[ADACONS_TUNE_COUNT_] = {0 /* kernel's own default */, 0 /* same */, 320, 2, 0, 1, 1, 1};
 
 size_t elem_size(adacons_dtype t) { return t == ADACONS_BF16 ? 2 : 4; }
 
@@ -115,6 +115,7 @@ LaunchShape shape_of(const adacons_state *st, adacons_tune_key key) {
     s.cached_head_mb = head >= (1 << 20) ? -1 : head;  // a huge value means all of G
     s.gram_products = st->tune[ADACONS_TUNE_GRAM_PRODUCTS];
     s.wsum_park_kb = st->tune[ADACONS_TUNE_WSUM_PARK_KB];
+    s.wsum_row_slices = st->tune[ADACONS_TUNE_WSUM_ROW_SLICES];
     s.short_path = false;
     return s;
 }
@@ -463,6 +464,7 @@ adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value) 
         return fail(ADACONS_EINVAL, "at most 8 workgroups per CU");
     if (key == ADACONS_TUNE_GRAM_PRODUCTS && value > 2) return fail(ADACONS_EINVAL, "ADACONS_TUNE_GRAM_PRODUCTS takes 0, 1 or 2");
     if (key == ADACONS_TUNE_SHORT_PATH && value > 2) return fail(ADACONS_EINVAL, "ADACONS_TUNE_SHORT_PATH takes 0, 1 or 2");
+    if (key == ADACONS_TUNE_WSUM_ROW_SLICES && value > 2) return fail(ADACONS_EINVAL, "ADACONS_TUNE_WSUM_ROW_SLICES takes 0, 1 or 2");
     if (key == ADACONS_TUNE_WSUM_PARK_KB && value != 0 && value != 1 && (value < 8 || value > 144))
         return fail(ADACONS_EINVAL, "ADACONS_TUNE_WSUM_PARK_KB takes 0, 1 or 8..144");
     st->tune[key] = value;

@@ -61,7 +61,7 @@ finish_kernel(const double *partials, int nrows, double *K, DevState *ds, CoeffP
     if (with_coeffs) update_coefficients(K_lds, ds, cp, lds, m_old);
 }
 
-// The coefficient update as a launch of its own (N > 44, after reduce_kernel).  Four threads share a
+// The coefficient update as a launch of its own (after reduce_kernel).  Four threads share a
 // row of K: each adds a quarter of it (elements j = quarter, quarter + 4, ...: neighbouring threads
 // read neighbouring addresses, the loads of one thread are independent), the quarters are added in
 // order; a single thread walking its row of N dependent-latency loads took 12 us at N = 64.
@@ -777,7 +777,7 @@ gram_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, double
 }
 
 // Stage A1, then the reduction of the partial rows into K and (with_coeffs) stage A2: one finish_kernel
-// launch for N <= 44, a multi-workgroup reduction followed by coeff_kernel above.
+// launch for small N or few rows, a multi-workgroup reduction followed by coeff_kernel otherwise.
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape_in, const GramWork &want, bool with_coeffs, hipStream_t stream,
                        hipEvent_t between, int *rows_out) {
@@ -818,7 +818,14 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
         *rows_out = grid;
         return hipSuccess;
     }
-    if (N <= kFinishMaxN) {
+    // One workgroup adds the rows and runs the update where that is a short job: its threads share a sum
+    // min(1024 / pairs, 32) ways, and a thread should not walk more than 32 rows.  Measured (time of stage A2
+    // between events): N = 44, 512 rows 129 us in one workgroup, 16 us as the two launches below; N = 32, 512
+    // rows 42 against 12 us; N = 16, 512 rows 17 against 12 us, 32 rows 8.7 us in one workgroup.
+    const int np = num_pairs(N);
+    const int shares = kFinishBlock / np < 32 ? kFinishBlock / np : 32;
+    const bool one_workgroup = N <= kFinishMaxN && grid <= 32 * shares;
+    if (one_workgroup) {
         hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(kFinishBlock), 0, stream, want.partials, grid, want.K,
                            want.ds, want.cp, with_coeffs ? 1 : 0);
         return hipGetLastError();

@@ -232,6 +232,81 @@ wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups
     if (parked > 0) flush(q_first, parked);
 }
 
+// Many workers with few parameters each (N >= 16, a gradient of a few thousand columns): too few columns
+// to fill the chip with one thread per column group, and that thread would walk its N rows eight at a
+// time, N / 8 memory latencies in a row.  Here a workgroup of sixteen wavefronts takes 64 column groups
+// and shares out the rows: wavefront w adds rows [w R, (w + 1) R), R = ceil(N / 16) <= 8, all requested at
+// once; the sixteen partial sums are added in wavefront order through LDS.  Every element still passes
+// through fewer than N + 1 roundings (R + 16 <= N + 1 for N >= 16).
+constexpr int kRowsBlock = 1024, kRowSlices = kRowsBlock / kWave;
+template <typename T, int VEC, bool APPLY>
+__global__ void __launch_bounds__(kRowsBlock)
+wsum_rows_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
+                 float *__restrict__ out, float lr) {
+    __shared__ __attribute__((aligned(16))) float part[kRowSlices][kWave * VEC];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int R = (N + kRowSlices - 1) / kRowSlices;
+    const int i0 = wave * R;
+    const int64_t grp = (int64_t)blockIdx.x * kWave + lane;
+    const int64_t gc = grp < ngroups ? grp : ngroups - 1;   // clamped: in bounds, the sums are not stored
+    float v[kRowsInFlight][VEC];
+#pragma unroll
+    for (int ii = 0; ii < kRowsInFlight; ++ii)
+        if (ii < R && i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + gc * VEC, v[ii]);
+    float acc[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+#pragma unroll
+    for (int ii = 0; ii < kRowsInFlight; ++ii)
+        if (ii < R && i0 + ii < N) {
+            const float w = gamma[i0 + ii];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w, v[ii][c], acc[c]);
+        }
+#pragma unroll
+    for (int c = 0; c < VEC; c += 4) {
+        const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+        *reinterpret_cast<f32x4 *>(&part[wave][lane * VEC + c]) = x;
+    }
+    __syncthreads();
+    // one output column per thread: consecutive threads read consecutive words of every slice
+    if ((int)threadIdx.x < kWave * VEC) {
+        const int64_t col = (int64_t)blockIdx.x * (kWave * VEC) + threadIdx.x;
+        if (col < ngroups * VEC) {
+            float tot = part[0][threadIdx.x];
+#pragma unroll
+            for (int s = 1; s < kRowSlices; ++s) tot += part[s][threadIdx.x];
+            out[col] = APPLY ? fmaf(-lr, tot, out[col]) : tot;
+        }
+    }
+}
+
+// Measured, whole step, columns -> row slices: N = 128, d = 1000 fp32 37.8 -> 18.6 us, d = 65536 56.7 -> 35.8 us;
+// N = 32, d = 8192 22.0 -> 16.0 us; bf16 N = 128, d = 8192 72.6 -> 21.2 us, N = 64, d = 262144 82.1 -> 35.1 us.
+// Even at N = 16 (two batches of rows either way).  The gain ends where the column kernel fills the chip by
+// itself: beyond 256 column groups per CU (fp32 d = 262144: 73.1 -> 68.9 us at N = 128; d = 524288: 68.6 ->
+// 80.3 us at N = 64, 38.7 -> 45.0 us at N = 32).
+static bool row_slices_pay(int N, int64_t ngroups, const LaunchShape &shape) {
+    if (N < 16 || shape.wsum_row_slices == 0) return false;
+    if (shape.wsum_row_slices == 2) return true;
+    return N > 16 && ngroups <= (int64_t)256 * shape.num_cu;
+}
+
+template <typename T, int VEC>
+static hipError_t run_rows(const void *G, int N, int64_t d, int64_t dcols, const float *gamma, float *out, bool apply,
+                           float lr, hipStream_t s) {
+    const int64_t ngroups = dcols / VEC;
+    const int64_t grid = (ngroups + kWave - 1) / kWave;
+    if (grid < 1 || grid > 0x7fffffff) return hipErrorInvalidValue;
+    if (apply)
+        hipLaunchKernelGGL((wsum_rows_kernel<T, VEC, true>), dim3((unsigned)grid), dim3(kRowsBlock), 0, s,
+                           static_cast<const T *>(G), N, d, ngroups, gamma, out, lr);
+    else
+        hipLaunchKernelGGL((wsum_rows_kernel<T, VEC, false>), dim3((unsigned)grid), dim3(kRowsBlock), 0, s,
+                           static_cast<const T *>(G), N, d, ngroups, gamma, out, 0.f);
+    return hipGetLastError();
+}
+
 template <typename Kern>
 static int occupancy(Kern k) {
     int nb = 0;
@@ -473,8 +548,13 @@ hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, boo
     const WsumMode m = {apply, lr};
     const int64_t vec = (dtype == ADACONS_F32) ? 4 : 8;
     const int64_t dcols = vec_ok ? d : d / vec * vec;
-    hipError_t e = (dtype == ADACONS_F32) ? dispatch<float, 4, 2>(G, N, d, dcols, shape, gamma, out, m, stream)
-                                          : dispatch<bf16_bits, 8, 2>(G, N, d, dcols, shape, gamma, out, m, stream);
+    hipError_t e;
+    if (dcols >= vec && row_slices_pay(N, dcols / vec, shape))
+        e = (dtype == ADACONS_F32) ? run_rows<float, 4>(G, N, d, dcols, gamma, out, apply, lr, stream)
+                                   : run_rows<bf16_bits, 8>(G, N, d, dcols, gamma, out, apply, lr, stream);
+    else
+        e = (dtype == ADACONS_F32) ? dispatch<float, 4, 2>(G, N, d, dcols, shape, gamma, out, m, stream)
+                                   : dispatch<bf16_bits, 8, 2>(G, N, d, dcols, shape, gamma, out, m, stream);
     if (e != hipSuccess || dcols == d) return e;
     if (dtype == ADACONS_F32)
         hipLaunchKernelGGL(wsum_edge_kernel<float>, dim3(1), dim3(kWave), 0, stream, static_cast<const float *>(G), N, d,

@@ -145,6 +145,50 @@ def test_weighted_sum_leaves_the_reported_coefficients_alone(pkg):
     agg.close(); ref.close()
 
 
+@pytest.mark.parametrize("N,d", [(16, 1000), (17, 1001), (24, 4100), (33, 70_003), (64, 3), (100, 8), (128, 1000),
+                                 (128, 65_536 + 24), (48, 300_000)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_weighted_sum_by_row_slices(pkg, N, d, dtype):
+    """Stage A3 for many workers with few parameters each: the rows shared out over the wavefronts of a
+    workgroup (ADACONS_TUNE_WSUM_ROW_SLICES = 2 forces it for N >= 16), partial sums added in wavefront
+    order.  Every element within the rounding bound of an fp32 sum of N terms; the descent step likewise."""
+    G = randG(N, d, dtype, sigma=1.5, seed=d % 1009 + N)
+    Gh = workloads.to_oracle_input(G)
+    gamma = np.random.default_rng(N).standard_normal(N) / N
+    agg = pkg.AdaCons(N, d)
+    agg.tune(pkg.ADACONS_TUNE_WSUM_ROW_SLICES, 2)
+    out = torch.full((d,), float("nan"), device=DEV)
+    out = agg.weighted_sum(G, gamma, out=out).cpu().numpy()
+    assert_out_elementwise(out, Gh, gamma)
+    assert rel_l2(out, o.weighted_sum(Gh, gamma)) <= OUT_TOL[dtype]
+    # whole aggregation and the fused step through the same kernel (the coefficients of a handful of columns
+    # are too ill-conditioned for the stated tolerance, whatever the kernel: only the sums are checked there)
+    agg.aggregate(G) if d < 512 else both(pkg, G, agg, o.OracleState(N))
+    w = torch.randn(d, device=DEV)
+    w0 = w.cpu().numpy()
+    agg.aggregate_apply(G, w, lr=0.25)
+    assert_out_elementwise(w.cpu().numpy(), Gh, agg.coeffs()["gamma"], base=w0, lr=0.25)
+    agg.close()
+
+
+def test_row_slices_are_the_default_for_many_workers_and_short_gradients_only(pkg):
+    """Default choice of the stage A3 kernel: the two kernels add in different orders, so their outputs
+    differ in the last bits; the default must equal the forced row slices for N > 16 at up to 256 column
+    groups per CU, and the column kernel elsewhere."""
+    for N, d, rows in [(32, 1000, True), (128, 8192, True), (17, 65_536, True), (16, 1000, False), (8, 1000, False),
+                       (32, 1 << 20, False)]:
+        G = randG(N, d, seed=3)
+        outs = []
+        for mode in (1, 2, 0):
+            agg = pkg.AdaCons(N, d)
+            agg.tune(pkg.ADACONS_TUNE_WSUM_ROW_SLICES, mode)
+            outs.append(agg.aggregate(G).clone())
+            agg.close()
+        if N >= 16:
+            assert not torch.equal(outs[1], outs[2])       # the inputs do tell the two kernels apart
+        assert torch.equal(outs[0], outs[1] if rows else outs[2]), (N, d)
+
+
 # --------------------------------------------------------------------- whole aggregation ----
 @pytest.mark.parametrize("name,d,steps", [("C1", None, 1), ("C2", 1_048_576 + 40, 20), ("C3", 2_097_152 + 3072, 1),
                                           ("C4", 262_144 + 8, 10), ("C5", 524_288 + 64, 100)])
