@@ -768,12 +768,14 @@ def test_more_than_64_workers_degenerate_inputs(pkg, dtype):
 
 
 # ------------------------------------------------------------------------- graph capture ----
-@pytest.mark.parametrize("N,d,park_kb", [(8, 1_000_004, 1), (16, 600_000, 96)])
+@pytest.mark.parametrize("N,d,park_kb", [(8, 1_000_004, 1), (16, 600_000, 96), (4, 65_536, 1), (32, 8192, 1), (128, 1000, 1)])
 def test_aggregate_can_be_captured_in_a_hip_graph(pkg, N, d, park_kb):
     """adacons_aggregate enqueues kernels only (no allocation, no synchronisation, no memset
     node), so a caller may capture it; every replay advances the momentum state like an eager
     call.  Replays are interleaved with eager work and checked one by one against the oracle.
-    Second case: the matrix-core Gram pass and the second pass with its output parked in LDS."""
+    Second case: the matrix-core Gram pass and the second pass with its output parked in LDS; third: the
+    two-launch short path (its parity flip happens on the device); fourth and fifth: many workers with
+    short gradients (second pass by row slices; statistics-only first pass for N > 64)."""
     agg = pkg.AdaCons(N, d, beta=0.9)
     agg.tune(pkg.ADACONS_TUNE_WSUM_PARK_KB, park_kb)
     ost = o.OracleState(N, beta=0.9)
