@@ -230,11 +230,13 @@ typedef enum {
                                             tile by tile among the loads.  0: never; 1 (default): where it measured
                                             faster (long fp32 streams of many rows); 8 .. 144: always, with that
                                             many KB of LDS */
-    ADACONS_TUNE_SHORT_PATH = 6,         /* two launches instead of three for N <= 8 and 16-byte aligned rows: stage A3
-                                            adds stage A1's partial sums and runs stage A2 itself (same results, bit
-                                            for bit).  0: never; 1 (default): for gradients of at most 32 MiB, which
+    ADACONS_TUNE_SHORT_PATH = 6,         /* two launches instead of three (16-byte aligned rows): stage A3 adds stage
+                                            A1's partial sums and runs stage A2 itself (same results, bit for bit).
+                                            0: never; 1 (default): N <= 8 with at most 32 MiB of gradients, which
                                             stay in the caches between the passes and are bound by launches, not
-                                            bytes; 2: whenever it applies */
+                                            bytes, and N > 16 with at most 1 MiB where stage A3 runs by row slices
+                                            (not for 44 < N <= 64 with the full matrix K); 2: also N <= 8 at any
+                                            size */
     ADACONS_TUNE_WSUM_ROW_SLICES = 7,    /* A3 for many workers with few parameters each (N >= 16): the rows are
                                             shared out over the sixteen wavefronts of a workgroup, which adds their
                                             partial sums in wavefront order, instead of one thread walking all N

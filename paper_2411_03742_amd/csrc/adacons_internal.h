@@ -47,6 +47,7 @@ struct GramWork {
 };
 
 __host__ __device__ inline int num_pairs(int N) { return N * (N + 1) / 2; }
+constexpr int kFinishMaxN = 44;   // largest N whose packed Gram row, N (N + 1) / 2 sums, one workgroup of 1024 threads reduces
 // Position of (i, j), i <= j, in the row-major packed upper triangle.
 __host__ __device__ inline int pair_index(int i, int j, int N) { return i * N - (i * (i - 1)) / 2 + (j - i); }
 
@@ -76,7 +77,8 @@ hipError_t launch_state_store(const DevState *ds, int N, double *m_out, double *
 // stats.hip: A1 reduced to diag K and its row sums, then A2 (N > 8)
 hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok, const LaunchShape &shape,
                         double *partials, DevState *ds, const CoeffParams &cp, hipStream_t stream,
-                        hipEvent_t between = nullptr);
+                        hipEvent_t between = nullptr,
+                        int *rows_out = nullptr);   // short path (shape.short_path): the number of partial rows written
 
 // api.hip: record the thread-local text adacons_last_error() returns; gives back `s`
 adacons_status set_error(adacons_status s, const char *fmt, ...);
@@ -92,10 +94,14 @@ hipError_t launch_scale(void *g, int64_t d, adacons_dtype dtype, int num_cu, con
 hipError_t launch_wsum(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape, const float *gamma, float *out, hipStream_t stream,
                        bool apply = false, float lr = 0.f);  // apply: out -= lr * sum
-// Short path (N <= 8, 16-byte aligned rows): stage A3 whose every workgroup first adds the nrows partial rows
-// of stage A1 and runs stage A2 for itself; workgroup 0 writes K and the state.
+// Whether launch_wsum takes the row-slice kernel for N rows of ngroups 128-bit column groups.
+bool row_slices_pay(int N, int64_t ngroups, const LaunchShape &shape);
+// Short path (16-byte aligned rows): stage A3 whose every workgroup first adds the nrows partial rows of
+// stage A1 and runs stage A2 for itself; workgroup 0 writes K and the state.  N <= 8: wsum_short_kernel.
+// N > 8: the row-slice kernel; stats_rows: the rows are those of the statistics-only pass (2 N doubles, any
+// N); otherwise packed Gram rows (N <= 44).
 hipError_t launch_wsum_short(const void *G, int N, int64_t d, adacons_dtype dtype, const LaunchShape &shape,
-                             const GramWork &work, int nrows, float *out, hipStream_t stream, bool apply = false,
-                             float lr = 0.f);
+                             const GramWork &work, int nrows, bool stats_rows, float *out, hipStream_t stream,
+                             bool apply = false, float lr = 0.f);
 
 }  // namespace adacons

@@ -131,11 +131,39 @@ GramWork work_of(adacons_state *st) {
     return t;
 }
 
+bool uses_stats_pass(const adacons_state *st, int N) {
+    return (st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8) || N > ADACONS_GRAM_N_MAX;
+}
+
+// Many workers with few parameters each (N > 16, at most 1 MiB of gradients, second pass by row slices): a
+// step is launch latencies and little else, and takes the short path below, where every workgroup of stage
+// A3 adds the partial rows itself.  Stage A1 then writes at most 8192 sums (16 rows at N = 32, 32 rows of
+// statistics at N = 128; such gradients give it that many workgroups at most anyway) -- on the long path too,
+// so that both form the coefficients from the same rows.
+constexpr int64_t kShortPathBytes = (int64_t)32 << 20;      // N <= 8
+constexpr int64_t kShortPathBytesWide = (int64_t)1 << 20;   // N > 16
+constexpr int kShortPathSums = 8192;
+bool many_workers_short_gradients(const adacons_state *st, int N, int64_t d, adacons_dtype dtype) {
+    if (N <= 16 || (int64_t)N * d * (int64_t)elem_size(dtype) > kShortPathBytesWide) return false;
+    if (!uses_stats_pass(st, N) && N > kFinishMaxN) return false;   // K takes more than one workgroup to reduce
+    const int64_t vec = 16 / (int64_t)elem_size(dtype);
+    return row_slices_pay(N, d / vec, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU));
+}
+LaunchShape first_pass_shape(const adacons_state *st, int N, int64_t d, adacons_dtype dtype) {
+    LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
+    if (many_workers_short_gradients(st, N, d, dtype)) {
+        const int row = uses_stats_pass(st, N) ? 2 * N : num_pairs(N);
+        const int cap = kShortPathSums / row;   // >= 8 (N <= 44 Gram: 990 sums; N <= 128 statistics: 256)
+        if (shape.max_rows > cap) shape.max_rows = cap;
+    }
+    return shape;
+}
+
 // Stages A1 + A2 of an aggregation: the Gram kernels, or the statistics-only pass when selected.
 hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                              hipStream_t s, hipEvent_t between) {
-    const LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
-    if ((st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8) || N > ADACONS_GRAM_N_MAX) {
+    const LaunchShape shape = first_pass_shape(st, N, d, dtype);
+    if (uses_stats_pass(st, N)) {
         st->k_valid = false;
         return launch_stats(G, N, d, dtype, vec_ok, shape, st->partials, st->ds, work_of(st).cp, s, between);
     }
@@ -144,12 +172,12 @@ hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d,
 }
 
 // Gradients small enough to sit in the caches between the two passes take the short path: two launches,
-// stage A2 inside stage A3 (see wsum_short_kernel).
-constexpr int64_t kShortPathBytes = (int64_t)32 << 20;
+// stage A2 inside stage A3 (see wsum_short_kernel and, for N > 16, wsum_rows_short_kernel).
 bool takes_short_path(const adacons_state *st, int N, int64_t d, adacons_dtype dtype, bool vec_ok) {
     const int mode = st->tune[ADACONS_TUNE_SHORT_PATH];
-    if (mode == 0 || N > 8 || !vec_ok) return false;
-    return mode == 2 || (int64_t)N * d * (int64_t)elem_size(dtype) <= kShortPathBytes;
+    if (mode == 0 || !vec_ok) return false;
+    if (N <= 8) return mode == 2 || (int64_t)N * d * (int64_t)elem_size(dtype) <= kShortPathBytes;
+    return many_workers_short_gradients(st, N, d, dtype);
 }
 
 // All three stages of one aggregation on stream s: out = sum, or (apply) out -= lr * sum.
@@ -161,12 +189,17 @@ hipError_t enqueue_aggregate(adacons_state *st, const void *G, int N, int64_t d,
     const bool short_path = takes_short_path(st, N, d, dtype, vec_ok);
     if (took_short) *took_short = short_path;
     if (short_path) {
-        LaunchShape shape = shape_of(st, ADACONS_TUNE_GRAM_BLOCKS_PER_CU);
+        LaunchShape shape = first_pass_shape(st, N, d, dtype);
         shape.short_path = true;
         int rows = 0;
-        st->k_valid = true;
-        if ((e = launch_gram(G, N, d, dtype, vec_ok, shape, work_of(st), true, s, ev ? ev[1] : nullptr, &rows)) != hipSuccess) return e;
-        e = launch_wsum_short(G, N, d, dtype, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), work_of(st), rows, out, s, apply, lr);
+        const bool stats_rows = uses_stats_pass(st, N);
+        st->k_valid = !stats_rows;
+        e = stats_rows ? launch_stats(G, N, d, dtype, vec_ok, shape, st->partials, st->ds, work_of(st).cp, s,
+                                      ev ? ev[1] : nullptr, &rows)
+                       : launch_gram(G, N, d, dtype, vec_ok, shape, work_of(st), true, s, ev ? ev[1] : nullptr, &rows);
+        if (e != hipSuccess) return e;
+        e = launch_wsum_short(G, N, d, dtype, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU), work_of(st), rows, stats_rows,
+                              out, s, apply, lr);
     } else {
         if ((e = launch_first_pass(st, G, N, d, dtype, vec_ok, s, ev ? ev[1] : nullptr)) != hipSuccess) return e;
         if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;

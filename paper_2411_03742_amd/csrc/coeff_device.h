@@ -164,6 +164,7 @@ __device__ __forceinline__ void unpack_pair(int p, int N, int &i, int &j) {
 // lds >= kReduceThreads doubles.  K (global, or NULL) and K_lds (or NULL) receive the N x N matrix.
 // BD: the workgroup's size (a divisor of kReduceThreads).
 constexpr int kReduceThreads = 1024;
+static_assert(kFinishMaxN * (kFinishMaxN + 1) / 2 <= kReduceThreads, "one workgroup reduces a whole Gram row");
 template <int BD>
 __device__ inline void reduce_partial_rows(const double *partials, int nrows, int N, double *K, double *lds,
                                            double *K_lds = nullptr) {
@@ -200,6 +201,39 @@ __device__ inline void reduce_partial_rows(const double *partials, int nrows, in
         }
     }
     __syncthreads();
+}
+
+// The statistics-only pass: rows of [q_0 .. q_{N-1}, r_0 .. r_{N-1}].  Thread tid < N receives the totals
+// of worker tid: kReduceThreads / (2 N) interleaved sub-sums per entry, added in slice order.  The same
+// virtual layout as above, so the totals do not depend on the size of the workgroup.  lds >= kReduceThreads
+// doubles, free again on return.
+template <int BD>
+__device__ inline void reduce_stat_rows(const double *partials, int nrows, int N, double *lds, double &q, double &r) {
+    static_assert(kReduceThreads % BD == 0, "whole shares per thread");
+    const int np = 2 * N;
+    const int slices = kReduceThreads / np;
+    double sub[kReduceThreads / BD];
+#pragma unroll
+    for (int k = 0; k < kReduceThreads / BD; ++k) {
+        const int vt = k * BD + (int)threadIdx.x;
+        const int s = vt / np, p = vt - s * np;
+        sub[k] = (s < slices) ? sum_rows(partials, np, p, s, slices, nrows) : 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < kReduceThreads / BD; ++k) {
+        const int vt = k * BD + (int)threadIdx.x;
+        if (vt < slices * np) lds[vt] = sub[k];   // vt = s * np + p
+    }
+    __syncthreads();
+    q = 0.0;
+    r = 0.0;
+    if ((int)threadIdx.x < N) {
+        for (int k = 0; k < slices; ++k) {
+            q += lds[k * np + threadIdx.x];
+            r += lds[k * np + N + threadIdx.x];
+        }
+    }
+    __syncthreads();   // the totals are in registers before the caller reuses the buffer
 }
 
 }  // namespace adacons

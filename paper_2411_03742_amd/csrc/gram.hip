@@ -51,7 +51,7 @@ __global__ void __launch_bounds__(kBlock) reduce_kernel(const double *partials, 
 // Reduction of the partial rows and (optionally) the coefficient update in one workgroup of
 // kFinishBlock threads, for N(N+1)/2 <= kFinishBlock: the launch between the two streaming passes.
 constexpr int kFinishBlock = 1024;
-constexpr int kFinishMaxN = 44;  // largest N with N(N+1)/2 <= kFinishBlock
+static_assert(kFinishMaxN * (kFinishMaxN + 1) / 2 <= kFinishBlock, "one thread per pair");
 __global__ void __launch_bounds__(kFinishBlock)
 finish_kernel(const double *partials, int nrows, double *K, DevState *ds, CoeffParams cp, int with_coeffs) {
     __shared__ double lds[kFinishBlock];
@@ -253,7 +253,8 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 template <int NT, typename T>
 __global__ void __launch_bounds__(kBlock, (NT >= 4) ? 1 : 2)
 gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks,
-                      int64_t cached_chunks, double *__restrict__ partials) {
+                      int64_t cached_chunks, double *__restrict__ partials, DevState *flip) {
+    if (flip && blockIdx.x == 0 && threadIdx.x == 0) flip->parity ^= 1u;   // as in gram_vec_kernel
     constexpr int NPT = NT * (NT + 1) / 2;
     constexpr int kRows = 16 * NT, kLoads = 4 * NT;          // 4 rows per load instruction
     constexpr int VECW = VecWidth<T>::value;                  // columns per 16-byte piece
@@ -422,7 +423,8 @@ __host__ __device__ constexpr int coop_max_pairs(int NT, int W) {
 template <int NT, int W>
 __global__ void __launch_bounds__(W * kWave, 2)
 gram_mfma_split_coop_kernel(const float *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks,
-                            int64_t cached_chunks, double *__restrict__ partials) {
+                            int64_t cached_chunks, double *__restrict__ partials, DevState *flip) {
+    if (flip && blockIdx.x == 0 && threadIdx.x == 0) flip->parity ^= 1u;   // as in gram_vec_kernel
     constexpr int NPW = coop_max_pairs(NT, W);                // tile pairs per wavefront at most
     constexpr int kRows = 16 * NT;
     constexpr int kLoads = 4 * NT;                            // load instructions per chunk (4 rows each) ...
@@ -686,7 +688,7 @@ static hipError_t dispatch_vec(const void *G, int N, int64_t d, int64_t dcols, c
 // dcols: the columns this launch covers, a multiple of the 128-bit vector width (rows are d elements apart).
 template <int NT, typename T>
 static hipError_t run_mfma_wave(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                                double *partials, hipStream_t s, int *grid_out) {
+                                double *partials, DevState *ds, hipStream_t s, int *grid_out) {
     auto kern = gram_mfma_wave_kernel<NT, T>;
     static const int occ = occupancy(kern);
     const int64_t cols = 16 * VecWidth<T>::value;   // columns per chunk
@@ -704,14 +706,14 @@ static hipError_t run_mfma_wave(const void *G, int N, int64_t d, int64_t dcols, 
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, static_cast<const T *>(G), N, d, dcols, nchunks,
-                       cached_chunks, partials);
+                       cached_chunks, partials, shape.short_path ? ds : nullptr);
     return hipGetLastError();
 }
 
 // The split-bf16 products with W wavefronts per chunk: one chunk and one partial row per workgroup.
 template <int NT, int W>
 static hipError_t run_mfma_coop(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                                double *partials, hipStream_t s, int *grid_out) {
+                                double *partials, DevState *ds, hipStream_t s, int *grid_out) {
     static const int occ = [] {
         int nb = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gram_mfma_split_coop_kernel<NT, W>, W * kWave, 0) != hipSuccess || nb < 1) nb = 1;
@@ -725,7 +727,7 @@ static hipError_t run_mfma_coop(const void *G, int N, int64_t d, int64_t dcols, 
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * 256);
     hipLaunchKernelGGL((gram_mfma_split_coop_kernel<NT, W>), dim3(grid), dim3(W * kWave), 0, s, static_cast<const float *>(G), N,
-                       d, dcols, nchunks, cached_chunks, partials);
+                       d, dcols, nchunks, cached_chunks, partials, shape.short_path ? ds : nullptr);
     return hipGetLastError();
 }
 
@@ -735,22 +737,22 @@ static hipError_t run_mfma_coop(const void *G, int N, int64_t d, int64_t dcols, 
 // bf16 inputs need no split: their products are exact on the bf16 instruction as they are.
 template <int NT, typename T>
 static hipError_t run_mfma(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                           double *partials, hipStream_t s, int *grid_out) {
+                           double *partials, DevState *ds, hipStream_t s, int *grid_out) {
     if constexpr (sizeof(T) == 4) {
         if (shape.gram_products == 1 || (shape.gram_products == 2 && NT >= 3))
-            return run_mfma_coop<NT, 2>(G, N, d, dcols, shape, partials, s, grid_out);
+            return run_mfma_coop<NT, 2>(G, N, d, dcols, shape, partials, ds, s, grid_out);
     }
-    return run_mfma_wave<NT, T>(G, N, d, dcols, shape, partials, s, grid_out);
+    return run_mfma_wave<NT, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
 }
 
 template <typename T>
 static hipError_t dispatch_mfma(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape,
-                                double *partials, hipStream_t s, int *grid_out) {
+                                double *partials, DevState *ds, hipStream_t s, int *grid_out) {
     switch ((N + 15) / 16) {
-        case 1: return run_mfma<1, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 2: return run_mfma<2, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 3: return run_mfma<3, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 4: return run_mfma<4, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 1: return run_mfma<1, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 2: return run_mfma<2, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 3: return run_mfma<3, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 4: return run_mfma<4, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
@@ -781,7 +783,7 @@ gram_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, double
 hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok,
                        const LaunchShape &shape_in, const GramWork &want, bool with_coeffs, hipStream_t stream,
                        hipEvent_t between, int *rows_out) {
-    if (shape_in.short_path && (N > 8 || !vec_ok || !rows_out)) return hipErrorInvalidValue;
+    if (shape_in.short_path && (N > kFinishMaxN || !vec_ok || !rows_out)) return hipErrorInvalidValue;
     // Without 16-byte aligned rows (vec_ok false) the same 128-bit kernels run from element-aligned
     // addresses over the whole groups of every row, and the columns left over (fewer than one group) go
     // through gram_edge_kernel into one more partial row.
@@ -798,8 +800,8 @@ hipError_t launch_gram(const void *G, int N, int64_t d, adacons_dtype dtype, boo
         e = (dtype == ADACONS_F32) ? dispatch_vec<float, 4>(G, N, d, dcols, shape, want.partials, want.ds, stream, &grid)
                                    : dispatch_vec<bf16_bits, 8>(G, N, d, dcols, shape, want.partials, want.ds, stream, &grid);
     } else {
-        e = (dtype == ADACONS_F32) ? dispatch_mfma<float>(G, N, d, dcols, shape, want.partials, stream, &grid)
-                                   : dispatch_mfma<bf16_bits>(G, N, d, dcols, shape, want.partials, stream, &grid);
+        e = (dtype == ADACONS_F32) ? dispatch_mfma<float>(G, N, d, dcols, shape, want.partials, want.ds, stream, &grid)
+                                   : dispatch_mfma<bf16_bits>(G, N, d, dcols, shape, want.partials, want.ds, stream, &grid);
     }
     if (e == hipSuccess && dcols < d) {
         double *row = want.partials + (size_t)grid * num_pairs(N);

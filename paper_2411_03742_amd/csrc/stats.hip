@@ -40,7 +40,9 @@ template <int NT, typename T> struct StatsShape {
 template <int NT, typename T>
 __global__ void __launch_bounds__(kBlock, (StatsShape<NT, T>::kLoads * VecWidth<T>::value > 48) ? 1 : 2)
 stats_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, int64_t nchunks, int64_t cached_chunks,
-                  double *__restrict__ partials) {
+                  double *__restrict__ partials, DevState *flip) {
+    // flip (or NULL): the short path's stage A3 reads the state copy this launch retires (see gram_vec_kernel)
+    if (flip && blockIdx.x == 0 && threadIdx.x == 0) flip->parity ^= 1u;
     constexpr int VECW = VecWidth<T>::value;
     constexpr int kLoads = StatsShape<NT, T>::kLoads;
     constexpr int kSuper = StatsShape<NT, T>::kSuper;
@@ -164,20 +166,10 @@ constexpr int kStatsFinishBlock = 1024;
 __global__ void __launch_bounds__(kStatsFinishBlock)
 stats_finish_kernel(const double *partials, int nrows, DevState *ds, CoeffParams cp) {
     __shared__ double lds[kStatsFinishBlock];
-    const int N = cp.N, np = 2 * N, tid = threadIdx.x;
+    const int N = cp.N, tid = threadIdx.x;
     const double m_old = (tid < N) ? current_m(ds)[tid] : 0.0;
-    const int slices = kStatsFinishBlock / np;
-    const int s = tid / np, p = tid - s * np;
-    if (s < slices) lds[s * np + p] = sum_rows(partials, np, p, s, slices, nrows);
-    __syncthreads();
-    double q = 0.0, r = 0.0;
-    if (tid < N) {
-        for (int k = 0; k < slices; ++k) {
-            q += lds[k * np + tid];
-            r += lds[k * np + N + tid];
-        }
-    }
-    __syncthreads();   // the totals are in registers before the update reuses the LDS buffer
+    double q, r;
+    reduce_stat_rows<kStatsFinishBlock>(partials, nrows, N, lds, q, r);
     update_coefficients_from_stats(q, r, ds, cp, lds, m_old);
 }
 
@@ -207,7 +199,7 @@ stats_edge_kernel(const T *__restrict__ G, int N, int64_t d, int64_t col0, doubl
 
 template <int NT, typename T>
 hipError_t run_stats(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, double *partials,
-                     hipStream_t s, int *grid_out) {
+                     DevState *ds, hipStream_t s, int *grid_out) {
     static const int occ = [] {
         int nb = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, stats_wave_kernel<NT, T>, kBlock, 0) != hipSuccess || nb < 1)
@@ -234,22 +226,22 @@ hipError_t run_stats(const void *G, int N, int64_t d, int64_t dcols, const Launc
     if (shape.cached_head_mb >= 0 && rows_on_lines)
         cached_chunks = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * chunk * (int64_t)sizeof(T));
     hipLaunchKernelGGL((stats_wave_kernel<NT, T>), dim3((unsigned)grid), dim3(kBlock), 0, s, static_cast<const T *>(G),
-                       N, d, dcols, nchunks, cached_chunks, partials);
+                       N, d, dcols, nchunks, cached_chunks, partials, shape.short_path ? ds : nullptr);
     return hipGetLastError();
 }
 
 template <typename T>
 hipError_t dispatch_stats(const void *G, int N, int64_t d, int64_t dcols, const LaunchShape &shape, double *partials,
-                          hipStream_t s, int *grid_out) {
+                          DevState *ds, hipStream_t s, int *grid_out) {
     switch ((N + 15) / 16) {
-        case 1: return run_stats<1, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 2: return run_stats<2, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 3: return run_stats<3, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 4: return run_stats<4, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 5: return run_stats<5, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 6: return run_stats<6, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 7: return run_stats<7, T>(G, N, d, dcols, shape, partials, s, grid_out);
-        case 8: return run_stats<8, T>(G, N, d, dcols, shape, partials, s, grid_out);
+        case 1: return run_stats<1, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 2: return run_stats<2, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 3: return run_stats<3, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 4: return run_stats<4, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 5: return run_stats<5, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 6: return run_stats<6, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 7: return run_stats<7, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
+        case 8: return run_stats<8, T>(G, N, d, dcols, shape, partials, ds, s, grid_out);
         default: return hipErrorInvalidValue;
     }
 }
@@ -259,8 +251,12 @@ hipError_t dispatch_stats(const void *G, int N, int64_t d, int64_t dcols, const 
 // The partial rows need 2 N doubles per workgroup (never more than the N (N + 1) / 2 of a Gram row for
 // N >= 3).  Without 16-byte aligned rows (vec_ok false) the kernel covers the whole 128-bit groups of
 // every row from element-aligned addresses and stats_edge_kernel adds a row for the columns left over.
+// shape.short_path: stage A1 only (it flips the state's parity); *rows_out receives the number of partial
+// rows, which stage A3 adds itself.
 hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bool vec_ok, const LaunchShape &shape_in,
-                        double *partials, DevState *ds, const CoeffParams &cp, hipStream_t stream, hipEvent_t between) {
+                        double *partials, DevState *ds, const CoeffParams &cp, hipStream_t stream, hipEvent_t between,
+                        int *rows_out) {
+    if (shape_in.short_path && (!vec_ok || !rows_out)) return hipErrorInvalidValue;
     const int64_t vec = (dtype == ADACONS_F32) ? 4 : 8;
     const int64_t dcols = vec_ok ? d : d / vec * vec;
     LaunchShape shape = shape_in;
@@ -269,8 +265,8 @@ hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bo
         shape.max_rows -= 1;   // room for the edge row
     }
     int grid = 0;
-    hipError_t e = (dtype == ADACONS_F32) ? dispatch_stats<float>(G, N, d, dcols, shape, partials, stream, &grid)
-                                          : dispatch_stats<bf16_bits>(G, N, d, dcols, shape, partials, stream, &grid);
+    hipError_t e = (dtype == ADACONS_F32) ? dispatch_stats<float>(G, N, d, dcols, shape, partials, ds, stream, &grid)
+                                          : dispatch_stats<bf16_bits>(G, N, d, dcols, shape, partials, ds, stream, &grid);
     if (e == hipSuccess && dcols < d) {
         double *row = partials + (size_t)grid * (2 * N);
         if (dtype == ADACONS_F32)
@@ -284,6 +280,10 @@ hipError_t launch_stats(const void *G, int N, int64_t d, adacons_dtype dtype, bo
     }
     if (e == hipSuccess && between) e = hipEventRecord(between, stream);
     if (e != hipSuccess) return e;
+    if (shape.short_path) {
+        *rows_out = grid;
+        return hipSuccess;
+    }
     hipLaunchKernelGGL(stats_finish_kernel, dim3(1), dim3(kStatsFinishBlock), 0, stream, partials, grid, ds, cp);
     return hipGetLastError();
 }

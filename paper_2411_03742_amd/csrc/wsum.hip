@@ -239,11 +239,15 @@ wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups
 // once; the sixteen partial sums are added in wavefront order through LDS.  Every element still passes
 // through fewer than N + 1 roundings (R + 16 <= N + 1 for N >= 16).
 constexpr int kRowsBlock = 1024, kRowSlices = kRowsBlock / kWave;
-template <typename T, int VEC, bool APPLY>
-__global__ void __launch_bounds__(kRowsBlock)
-wsum_rows_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
-                 float *__restrict__ out, float lr) {
-    __shared__ __attribute__((aligned(16))) float part[kRowSlices][kWave * VEC];
+static_assert(kRowsBlock == kReduceThreads, "the short variant reduces the partial rows with one share per thread");
+
+// gamma: N weights, in global memory or LDS.  part: kRowSlices x (kWave * VEC) floats of LDS.
+// between(): run by the whole workgroup once the loads are requested (the short variant produces the
+// weights there, while the loads are in flight).
+template <typename T, int VEC, bool APPLY, typename Between>
+__device__ __forceinline__ void wsum_rows_tile(const T *__restrict__ G, int N, int64_t d, int64_t ngroups,
+                                               const float *gamma, float *__restrict__ out, float lr,
+                                               float (*part)[kWave * VEC], Between between) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int R = (N + kRowSlices - 1) / kRowSlices;
     const int i0 = wave * R;
@@ -253,6 +257,7 @@ wsum_rows_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ngroups, con
 #pragma unroll
     for (int ii = 0; ii < kRowsInFlight; ++ii)
         if (ii < R && i0 + ii < N) load_vec<T, VEC, true>(G + (int64_t)(i0 + ii) * d + gc * VEC, v[ii]);
+    between();
     float acc[VEC];
 #pragma unroll
     for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
@@ -281,12 +286,58 @@ wsum_rows_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ngroups, con
     }
 }
 
+template <typename T, int VEC, bool APPLY>
+__global__ void __launch_bounds__(kRowsBlock)
+wsum_rows_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ngroups, const float *__restrict__ gamma,
+                 float *__restrict__ out, float lr) {
+    __shared__ __attribute__((aligned(16))) float part[kRowSlices][kWave * VEC];
+    wsum_rows_tile<T, VEC, APPLY>(G, N, d, ngroups, gamma, out, lr, part, [] {});
+}
+
+// The short path of this regime (see wsum_short_kernel): the aggregation is launch latencies and little
+// else, so stage A2 runs here, in every workgroup, on the few partial rows stage A1 left (the launcher caps
+// them at 8192 sums), summed as finish_kernel / stats_finish_kernel sum them; workgroup 0 writes K and the
+// state.  stats_rows: the rows hold q and r (statistics-only pass); otherwise packed Gram rows (N <= 44).
+template <typename T, int VEC, bool APPLY>
+__global__ void __launch_bounds__(kRowsBlock)
+wsum_rows_short_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ngroups, const double *__restrict__ partials,
+                       int nrows, int stats_rows, double *__restrict__ K, DevState *ds, CoeffParams cp,
+                       float *__restrict__ out, float lr) {
+    __shared__ __attribute__((aligned(16))) float part[kRowSlices][kWave * VEC];
+    __shared__ double lds[kReduceThreads];
+    __shared__ double K_lds[kFinishMaxN * kFinishMaxN];
+    __shared__ float gam_lds[kNMax];
+    auto stage_a2 = [&]() __attribute__((always_inline)) {
+        const int tid = threadIdx.x;
+        const bool writer = blockIdx.x == 0;
+        const unsigned parity = ds->parity;            // flipped by stage A1 of this call
+        const double m0 = (tid < N) ? ds->m[0][tid] : 0.0, m1 = (tid < N) ? ds->m[1][tid] : 0.0;
+        double q = 0.0, r = 0.0;
+        if (stats_rows) {
+            reduce_stat_rows<kRowsBlock>(partials, nrows, N, lds, q, r);
+        } else {
+            reduce_partial_rows<kRowsBlock>(partials, nrows, N, writer ? K : nullptr, lds, K_lds);
+            if (tid < N) {
+                q = K_lds[tid * N + tid];
+                for (int j = 0; j < N; ++j) r += K_lds[tid * N + j];   // as update_coefficients adds them
+            }
+        }
+        const unsigned cur = parity & 1u;
+        double *m_cur = ds->m[cur];
+        const double m_old = cur ? m0 : m1;            // the copy stage A1 retired
+        if (writer && tid < N) m_cur[tid] = m_old;     // entries the update leaves alone carry over
+        update_coefficients_from_stats(q, r, ds, cp, lds, m_old, m_cur, gam_lds, writer);
+        __syncthreads();
+    };
+    wsum_rows_tile<T, VEC, APPLY>(G, N, d, ngroups, gam_lds, out, lr, part, stage_a2);
+}
+
 // Measured, whole step, columns -> row slices: N = 128, d = 1000 fp32 37.8 -> 18.6 us, d = 65536 56.7 -> 35.8 us;
 // N = 32, d = 8192 22.0 -> 16.0 us; bf16 N = 128, d = 8192 72.6 -> 21.2 us, N = 64, d = 262144 82.1 -> 35.1 us.
 // Even at N = 16 (two batches of rows either way).  The gain ends where the column kernel fills the chip by
 // itself: beyond 256 column groups per CU (fp32 d = 262144: 73.1 -> 68.9 us at N = 128; d = 524288: 68.6 ->
 // 80.3 us at N = 64, 38.7 -> 45.0 us at N = 32).
-static bool row_slices_pay(int N, int64_t ngroups, const LaunchShape &shape) {
+bool row_slices_pay(int N, int64_t ngroups, const LaunchShape &shape) {
     if (N < 16 || shape.wsum_row_slices == 0) return false;
     if (shape.wsum_row_slices == 2) return true;
     return N > 16 && ngroups <= (int64_t)256 * shape.num_cu;
@@ -304,6 +355,25 @@ static hipError_t run_rows(const void *G, int N, int64_t d, int64_t dcols, const
     else
         hipLaunchKernelGGL((wsum_rows_kernel<T, VEC, false>), dim3((unsigned)grid), dim3(kRowsBlock), 0, s,
                            static_cast<const T *>(G), N, d, ngroups, gamma, out, 0.f);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+static hipError_t run_rows_short(const void *G, int N, int64_t d, const GramWork &work, int nrows, bool stats_rows,
+                                 float *out, bool apply, float lr, hipStream_t s) {
+    const int64_t ngroups = d / VEC;
+    const int64_t grid = (ngroups + kWave - 1) / kWave;
+    if (grid < 1 || grid > 0x7fffffff) return hipErrorInvalidValue;
+    CoeffParams cp = work.cp;
+    cp.N = N;
+    if (apply)
+        hipLaunchKernelGGL((wsum_rows_short_kernel<T, VEC, true>), dim3((unsigned)grid), dim3(kRowsBlock), 0, s,
+                           static_cast<const T *>(G), N, d, ngroups, work.partials, nrows, stats_rows ? 1 : 0, work.K,
+                           work.ds, cp, out, lr);
+    else
+        hipLaunchKernelGGL((wsum_rows_short_kernel<T, VEC, false>), dim3((unsigned)grid), dim3(kRowsBlock), 0, s,
+                           static_cast<const T *>(G), N, d, ngroups, work.partials, nrows, stats_rows ? 1 : 0, work.K,
+                           work.ds, cp, out, 0.f);
     return hipGetLastError();
 }
 
@@ -519,7 +589,14 @@ static hipError_t dispatch_short(const void *G, int N, int64_t d, const LaunchSh
 
 // Rows and output 16-byte aligned, d a multiple of the vector width (the caller checks).
 hipError_t launch_wsum_short(const void *G, int N, int64_t d, adacons_dtype dtype, const LaunchShape &shape,
-                             const GramWork &work, int nrows, float *out, hipStream_t stream, bool apply, float lr) {
+                             const GramWork &work, int nrows, bool stats_rows, float *out, hipStream_t stream,
+                             bool apply, float lr) {
+    if (N > 8 || stats_rows) {
+        if (!stats_rows && N > kFinishMaxN) return hipErrorInvalidValue;
+        return (dtype == ADACONS_F32)
+                   ? run_rows_short<float, 4>(G, N, d, work, nrows, stats_rows, out, apply, lr, stream)
+                   : run_rows_short<bf16_bits, 8>(G, N, d, work, nrows, stats_rows, out, apply, lr, stream);
+    }
     return (dtype == ADACONS_F32) ? dispatch_short<float, 4>(G, N, d, shape, work, nrows, out, apply, lr, stream)
                                   : dispatch_short<bf16_bits, 8>(G, N, d, shape, work, nrows, out, apply, lr, stream);
 }

@@ -277,9 +277,40 @@ def test_short_path_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags):
     against the three-launch path on the same stream of inputs: output, coefficients, K and the carried
     state must be equal bit for bit -- over regular steps, a zero row, a non-finite step (state left
     untouched) and a regular step after it -- and the fused descent step likewise."""
+    short_against_plain(pkg, N, d, dtype, flags, 0)
+
+
+@pytest.mark.parametrize("N,d,dtype,flags,stats_only", [
+    (17, 1000, torch.float32, 3, 0), (32, 1000, torch.float32, 3, 0), (44, 2048, torch.float32, 7, 0),
+    (32, 8192, torch.float32, 3, 0),     # 1 MiB: the cap on stage A1's partial rows binds
+    (24, 1008, torch.bfloat16, 3, 0), (40, 512, torch.float32, 0, 0),
+    (64, 1000, torch.float32, 3, 1), (20, 5000, torch.float32, 11, 1), (48, 2000, torch.bfloat16, 3, 1),
+    (65, 1000, torch.float32, 3, 0), (100, 1000, torch.float32, 3, 0), (128, 1000, torch.float32, 7, 0),
+    (128, 2048, torch.float32, 3, 0), (128, 1000, torch.bfloat16, 3, 0)])
+def test_short_path_for_many_workers_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags, stats_only):
+    """The same for N > 16 at up to 1 MiB of gradients (many workers with few parameters each, the regime of
+    Eq. 14's example), where stage A3 runs by row slices: packed Gram rows for N <= 44, the rows of the
+    statistics-only pass (chosen, or N > 64) for any N."""
+    short_against_plain(pkg, N, d, dtype, flags, stats_only)
+
+
+def short_against_plain(pkg, N, d, dtype, flags, stats_only):
     short, plain = pkg.AdaCons(N, d, beta=0.9, flags=flags), pkg.AdaCons(N, d, beta=0.9, flags=flags)
     short.tune(pkg.ADACONS_TUNE_SHORT_PATH, 2)
     plain.tune(pkg.ADACONS_TUNE_SHORT_PATH, 0)
+    short.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)
+    plain.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)
+    has_K = N <= 64 and not (stats_only and N > 8)
+    # two launches on one side, three on the other: seen through the per-stage timing
+    G = randG(N, d, dtype, sigma=2.0, seed=899)
+    for two in (True, False):
+        probe = pkg.AdaCons(N, d)
+        probe.tune(pkg.ADACONS_TUNE_SHORT_PATH, 2 if two else 0)
+        probe.tune(pkg.ADACONS_TUNE_STATS_ONLY, stats_only)
+        probe.profile_begin(2)
+        probe.aggregate(G); probe.aggregate(G)
+        assert (probe.profile_end()["coeff_ms"] == 0.0) == two
+        probe.close()
     ost = o.OracleState(N, beta=0.9, flags=flags)
     for t in range(6):
         G = randG(N, d, dtype, sigma=2.0, seed=900 + t)
@@ -295,8 +326,9 @@ def test_short_path_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags):
         for key in ("gamma", "raw", "smoothed"):
             assert np.array_equal(ia[key], ib[key], equal_nan=True), (t, key)
         assert ia["numeric_flags"] == ib["numeric_flags"]
-        Ka, Kb = pkg.adacons_read_gram(short._st, N, None), pkg.adacons_read_gram(plain._st, N, None)
-        assert np.array_equal(Ka, Kb, equal_nan=True)
+        if has_K:
+            Ka, Kb = pkg.adacons_read_gram(short._st, N, None), pkg.adacons_read_gram(plain._st, N, None)
+            assert np.array_equal(Ka, Kb, equal_nan=True)
         (ma, sa), (mb, sb) = short.export_state(), plain.export_state()
         assert np.array_equal(ma, mb) and sa == sb == t + 1
         # and against the oracle, like every other path
@@ -321,9 +353,12 @@ def test_short_path_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags):
 
 
 def test_short_path_is_the_default_for_small_gradients_only(pkg):
-    """Up to 32 MiB of gradients (N <= 8, aligned rows) take two launches, larger ones three: seen through
-    the per-stage timing, which reports no time of its own for stage A2 on the short path."""
-    for N, d, short in [(4, 1 << 20, True), (8, 1 << 20, True), (8, (1 << 20) + 4, False), (16, 1000, False), (4, 1001, False)]:
+    """Up to 32 MiB of gradients (N <= 8, aligned rows) take two launches, larger ones three; N > 16 up to 1 MiB,
+    unless the Gram matrix takes more than one workgroup to reduce (44 < N <= 64): seen through the per-stage
+    timing, which reports no time of its own for stage A2 on the short path."""
+    for N, d, short in [(4, 1 << 20, True), (8, 1 << 20, True), (8, (1 << 20) + 4, False), (4, 1001, False),
+                        (16, 1000, False), (32, 1000, True), (32, 8192, True), (32, 8196, False), (48, 1000, False),
+                        (128, 1000, True)]:
         agg = pkg.AdaCons(N, d)
         G = randG(N, d, seed=1)
         agg.aggregate(G)
