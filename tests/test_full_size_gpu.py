@@ -107,3 +107,67 @@ def test_full_size_configuration(pkg, capsys, name, steps, stats_only):
     assert step == steps
     assert np.abs(m - ost.m).max() <= 1e-6 * np.abs(ost.m).max()
     agg.close()
+
+
+def _filled(N, d, dtype, seed):
+    """N x d normal values, drawn in pieces of 2^28 columns (every call of the generator stays below 2^31 elements)."""
+    G = torch.empty((N, d), dtype=dtype, device=DEV)
+    gen = torch.Generator(device=DEV).manual_seed(seed)
+    piece = 1 << 28
+    for a in range(0, d, piece):
+        b = min(d, a + piece)
+        G[:, a:b] = torch.randn((N, b - a), generator=gen, device=DEV).to(dtype)
+    return G
+
+
+@pytest.mark.timeout(600)
+def test_more_column_groups_than_a_32_bit_index_holds(pkg):
+    """One worker, d = 2^33 + 12 fp32 columns: 2^31 + 3 column groups of 128 bits, 34 GB each way.  With N = 1
+    the method fixes the result whatever the input (Eq. 12 with a single weight): gamma = 1, the first-order
+    coefficient is ||g||, and out equals g bit for bit -- an index that wraps at 2^31 or 2^32 anywhere in the
+    two passes leaves columns unwritten (NaN here) or written from the wrong place."""
+    N, d = 1, (1 << 33) + 12
+    G = _filled(N, d, torch.float32, 5)
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device=DEV)
+    agg = pkg.AdaCons(N, d, beta=0.99)
+    agg.aggregate(G, out=out)
+    info = agg.coeffs()
+    assert info["numeric_flags"] == 0 and info["gamma"][0] == 1.0
+    piece = 1 << 28
+    q = 0.0
+    for a in range(0, d, piece):
+        b = min(d, a + piece)
+        assert torch.equal(out[a:b], G[0, a:b]), (a, b)
+        q += float((G[0, a:b].double() ** 2).sum())
+    assert abs(info["raw"][0] - np.sqrt(q)) <= 1e-10 * np.sqrt(q)
+    agg.close()
+
+
+@pytest.mark.timeout(900)
+def test_rows_longer_than_2_32_elements(pkg):
+    """Two workers, d = 2^32 + 16 bf16 columns (17 GB of gradients, 17 GB of output; element offsets of the
+    second row exceed 2^33): coefficients against the oracle's whole Gram matrix of the same bits, the output
+    element by element on blocks at both ends and on either side of the 2^31 and 2^32 column marks, and every
+    other element written and finite."""
+    N, d = 2, (1 << 32) + 16
+    G = _filled(N, d, torch.bfloat16, 6)
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device=DEV)
+    agg = pkg.AdaCons(N, d, beta=0.99)
+    ost = o.OracleState(N, beta=0.99)
+    agg.aggregate(G, out=out)
+    info = agg.coeffs()
+    Gh = HostCopy(N, d, torch.bfloat16).fetch(G)
+    _, oinfo = o.aggregate(Gh, ost, want_out=False)
+    assert check_coefficients(info, oinfo, ost.m, ost.flags, True)
+    width = 1 << 20
+    for start in (0, (1 << 31) - width // 2, (1 << 32) - width // 2, d - width):
+        a, b = start, min(d, start + width)
+        Gb = np.ascontiguousarray(Gh[:, a:b])
+        got = out[a:b].cpu().numpy()
+        assert_out_elementwise(got, Gb, info["gamma"])
+        ref = o.weighted_sum(Gb, oinfo["gamma"])
+        assert np.linalg.norm(got - ref) <= OUT_TOL["bf16"] * np.linalg.norm(ref)
+    piece = 1 << 28
+    for a in range(0, d, piece):
+        assert torch.isfinite(out[a:min(d, a + piece)]).all(), a
+    agg.close()
