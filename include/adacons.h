@@ -234,14 +234,14 @@ typedef enum {
                                             A1's partial sums and runs stage A2 itself (same results, bit for bit).
                                             0: never; 1 (default): N <= 8 with at most 32 MiB of gradients, which
                                             stay in the caches between the passes and are bound by launches, not
-                                            bytes, and N > 16 with at most 1 MiB where stage A3 runs by row slices
+                                            bytes, and N > 8 with at most 1 MiB where stage A3 runs by row slices
                                             (not for 44 < N <= 64 with the full matrix K); 2: also N <= 8 at any
                                             size */
-    ADACONS_TUNE_WSUM_ROW_SLICES = 7,    /* A3 for many workers with few parameters each (N >= 16): the rows are
+    ADACONS_TUNE_WSUM_ROW_SLICES = 7,    /* A3 for many workers with few parameters each (N > 8): the rows are
                                             shared out over the sixteen wavefronts of a workgroup, which adds their
                                             partial sums in wavefront order, instead of one thread walking all N
                                             rows of its columns.  0: never; 1 (default): where it measured faster;
-                                            2: whenever N >= 16 */
+                                            2: whenever N > 8 */
     ADACONS_TUNE_COUNT_
 } adacons_tune_key;
 adacons_status adacons_tune(adacons_state *st, adacons_tune_key key, int value);

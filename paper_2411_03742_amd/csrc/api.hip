@@ -135,16 +135,16 @@ bool uses_stats_pass(const adacons_state *st, int N) {
     return (st->tune[ADACONS_TUNE_STATS_ONLY] != 0 && N > 8) || N > ADACONS_GRAM_N_MAX;
 }
 
-// Many workers with few parameters each (N > 16, at most 1 MiB of gradients, second pass by row slices): a
+// Many workers with few parameters each (N > 8, at most 1 MiB of gradients, second pass by row slices): a
 // step is launch latencies and little else, and takes the short path below, where every workgroup of stage
 // A3 adds the partial rows itself.  Stage A1 then writes at most 8192 sums (16 rows at N = 32, 32 rows of
 // statistics at N = 128; such gradients give it that many workgroups at most anyway) -- on the long path too,
 // so that both form the coefficients from the same rows.
 constexpr int64_t kShortPathBytes = (int64_t)32 << 20;      // N <= 8
-constexpr int64_t kShortPathBytesWide = (int64_t)1 << 20;   // N > 16
+constexpr int64_t kShortPathBytesWide = (int64_t)1 << 20;   // N > 8
 constexpr int kShortPathSums = 8192;
 bool many_workers_short_gradients(const adacons_state *st, int N, int64_t d, adacons_dtype dtype) {
-    if (N <= 16 || (int64_t)N * d * (int64_t)elem_size(dtype) > kShortPathBytesWide) return false;
+    if (N <= 8 || (int64_t)N * d * (int64_t)elem_size(dtype) > kShortPathBytesWide) return false;
     if (!uses_stats_pass(st, N) && N > kFinishMaxN) return false;   // K takes more than one workgroup to reduce
     const int64_t vec = 16 / (int64_t)elem_size(dtype);
     return row_slices_pay(N, d / vec, shape_of(st, ADACONS_TUNE_WSUM_BLOCKS_PER_CU));
@@ -172,7 +172,7 @@ hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d,
 }
 
 // Gradients small enough to sit in the caches between the two passes take the short path: two launches,
-// stage A2 inside stage A3 (see wsum_short_kernel and, for N > 16, wsum_rows_short_kernel).
+// stage A2 inside stage A3 (see wsum_short_kernel and, for N > 8, wsum_rows_short_kernel).
 bool takes_short_path(const adacons_state *st, int N, int64_t d, adacons_dtype dtype, bool vec_ok) {
     const int mode = st->tune[ADACONS_TUNE_SHORT_PATH];
     if (mode == 0 || !vec_ok) return false;

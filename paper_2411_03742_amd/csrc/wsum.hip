@@ -232,12 +232,13 @@ wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups
     if (parked > 0) flush(q_first, parked);
 }
 
-// Many workers with few parameters each (N >= 16, a gradient of a few thousand columns): too few columns
+// Many workers with few parameters each (N > 8, a gradient of a few thousand columns): too few columns
 // to fill the chip with one thread per column group, and that thread would walk its N rows eight at a
 // time, N / 8 memory latencies in a row.  Here a workgroup of sixteen wavefronts takes 64 column groups
 // and shares out the rows: wavefront w adds rows [w R, (w + 1) R), R = ceil(N / 16) <= 8, all requested at
 // once; the sixteen partial sums are added in wavefront order through LDS.  Every element still passes
-// through fewer than N + 1 roundings (R + 16 <= N + 1 for N >= 16).
+// through at most N + 1 roundings (R + 16 <= N + 1 for N >= 16; below, the slices without rows add +0.0,
+// which is exact).
 constexpr int kRowsBlock = 1024, kRowSlices = kRowsBlock / kWave;
 static_assert(kRowsBlock == kReduceThreads, "the short variant reduces the partial rows with one share per thread");
 
@@ -337,10 +338,13 @@ wsum_rows_short_kernel(const T *__restrict__ G, int N, int64_t d, int64_t ngroup
 // Even at N = 16 (two batches of rows either way).  The gain ends where the column kernel fills the chip by
 // itself: beyond 256 column groups per CU (fp32 d = 262144: 73.1 -> 68.9 us at N = 128; d = 524288: 68.6 ->
 // 80.3 us at N = 64, 38.7 -> 45.0 us at N = 32).
+// 8 < N <= 16 with at most 1 MiB of gradients (16 bytes a group and row): no faster by itself, but it is the
+// second pass the two-launch short path is built on.
 bool row_slices_pay(int N, int64_t ngroups, const LaunchShape &shape) {
-    if (N < 16 || shape.wsum_row_slices == 0) return false;
+    if (N <= 8 || shape.wsum_row_slices == 0) return false;
     if (shape.wsum_row_slices == 2) return true;
-    return N > 16 && ngroups <= (int64_t)256 * shape.num_cu;
+    if (N <= 16) return (int64_t)N * ngroups * 16 <= ((int64_t)1 << 20);
+    return ngroups <= (int64_t)256 * shape.num_cu;
 }
 
 template <typename T, int VEC>

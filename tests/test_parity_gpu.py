@@ -145,12 +145,12 @@ def test_weighted_sum_leaves_the_reported_coefficients_alone(pkg):
     agg.close(); ref.close()
 
 
-@pytest.mark.parametrize("N,d", [(16, 1000), (17, 1001), (24, 4100), (33, 70_003), (64, 3), (100, 8), (128, 1000),
+@pytest.mark.parametrize("N,d", [(9, 1000), (13, 5003), (16, 1000), (17, 1001), (24, 4100), (33, 70_003), (64, 3), (100, 8), (128, 1000),
                                  (128, 65_536 + 24), (48, 300_000)])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_weighted_sum_by_row_slices(pkg, N, d, dtype):
     """Stage A3 for many workers with few parameters each: the rows shared out over the wavefronts of a
-    workgroup (ADACONS_TUNE_WSUM_ROW_SLICES = 2 forces it for N >= 16), partial sums added in wavefront
+    workgroup (ADACONS_TUNE_WSUM_ROW_SLICES = 2 forces it for N > 8), partial sums added in wavefront
     order.  Every element within the rounding bound of an fp32 sum of N terms; the descent step likewise."""
     G = randG(N, d, dtype, sigma=1.5, seed=d % 1009 + N)
     Gh = workloads.to_oracle_input(G)
@@ -174,9 +174,9 @@ def test_weighted_sum_by_row_slices(pkg, N, d, dtype):
 def test_row_slices_are_the_default_for_many_workers_and_short_gradients_only(pkg):
     """Default choice of the stage A3 kernel: the two kernels add in different orders, so their outputs
     differ in the last bits; the default must equal the forced row slices for N > 16 at up to 256 column
-    groups per CU, and the column kernel elsewhere."""
-    for N, d, rows in [(32, 1000, True), (128, 8192, True), (17, 65_536, True), (16, 1000, False), (8, 1000, False),
-                       (32, 1 << 20, False)]:
+    groups per CU and for N > 8 at up to 1 MiB of gradients, and the column kernel elsewhere."""
+    for N, d, rows in [(32, 1000, True), (128, 8192, True), (17, 65_536, True), (16, 1000, True), (16, 65_536, False),
+                       (8, 1000, False), (32, 1 << 20, False)]:
         G = randG(N, d, seed=3)
         outs = []
         for mode in (1, 2, 0):
@@ -184,7 +184,7 @@ def test_row_slices_are_the_default_for_many_workers_and_short_gradients_only(pk
             agg.tune(pkg.ADACONS_TUNE_WSUM_ROW_SLICES, mode)
             outs.append(agg.aggregate(G).clone())
             agg.close()
-        if N >= 16:
+        if N > 8:
             assert not torch.equal(outs[1], outs[2])       # the inputs do tell the two kernels apart
         assert torch.equal(outs[0], outs[1] if rows else outs[2]), (N, d)
 
@@ -281,6 +281,7 @@ def test_short_path_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags):
 
 
 @pytest.mark.parametrize("N,d,dtype,flags,stats_only", [
+    (9, 1000, torch.float32, 3, 0), (12, 4096, torch.bfloat16, 3, 0), (16, 16384, torch.float32, 3, 0), (16, 1000, torch.float32, 3, 1),
     (17, 1000, torch.float32, 3, 0), (32, 1000, torch.float32, 3, 0), (44, 2048, torch.float32, 7, 0),
     (32, 8192, torch.float32, 3, 0),     # 1 MiB: the cap on stage A1's partial rows binds
     (24, 1008, torch.bfloat16, 3, 0), (40, 512, torch.float32, 0, 0),
@@ -288,7 +289,7 @@ def test_short_path_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags):
     (65, 1000, torch.float32, 3, 0), (100, 1000, torch.float32, 3, 0), (128, 1000, torch.float32, 7, 0),
     (128, 2048, torch.float32, 3, 0), (128, 1000, torch.bfloat16, 3, 0)])
 def test_short_path_for_many_workers_equals_three_launches_bit_for_bit(pkg, N, d, dtype, flags, stats_only):
-    """The same for N > 16 at up to 1 MiB of gradients (many workers with few parameters each, the regime of
+    """The same for N > 8 at up to 1 MiB of gradients (many workers with few parameters each, the regime of
     Eq. 14's example), where stage A3 runs by row slices: packed Gram rows for N <= 44, the rows of the
     statistics-only pass (chosen, or N > 64) for any N."""
     short_against_plain(pkg, N, d, dtype, flags, stats_only)
@@ -353,11 +354,11 @@ def short_against_plain(pkg, N, d, dtype, flags, stats_only):
 
 
 def test_short_path_is_the_default_for_small_gradients_only(pkg):
-    """Up to 32 MiB of gradients (N <= 8, aligned rows) take two launches, larger ones three; N > 16 up to 1 MiB,
+    """Up to 32 MiB of gradients (N <= 8, aligned rows) take two launches, larger ones three; N > 8 up to 1 MiB,
     unless the Gram matrix takes more than one workgroup to reduce (44 < N <= 64): seen through the per-stage
     timing, which reports no time of its own for stage A2 on the short path."""
     for N, d, short in [(4, 1 << 20, True), (8, 1 << 20, True), (8, (1 << 20) + 4, False), (4, 1001, False),
-                        (16, 1000, False), (32, 1000, True), (32, 8192, True), (32, 8196, False), (48, 1000, False),
+                        (16, 1000, True), (16, 16388, False), (9, 1000, True), (32, 1000, True), (32, 8192, True), (32, 8196, False), (48, 1000, False),
                         (128, 1000, True)]:
         agg = pkg.AdaCons(N, d)
         G = randG(N, d, seed=1)
