@@ -402,13 +402,17 @@ static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const L
     // Parked output (wsum_parked_kernel).  Measured, plain -> parked: N = 64, d = 25.6 M 1.16 -> 1.02 ms;
     // N = 32 0.60 -> 0.52 ms; N = 16 0.295 -> 0.263 ms, and 1.51 -> 1.40 ms at d = 124 M; N = 12 0.220 -> 0.207 ms;
     // even (+-4 %) at d = 4 M .. 16.7 M, 3-5 % slower for N <= 9 at d = 25.6 M, 10-25 % slower at d = 1 M; bf16
-    // inputs lose (N >= 32: twice the time).  Streams of 1.25 GiB and more through the run-time-N kernel
+    // inputs lose (N >= 32: twice the time; but see long_bf16 below).  Streams of 1.25 GiB and more through the run-time-N kernel
     // (N other than 4, 8, 16) gain too: N = 1, 2, 3, 5 4-8 %, N = 9, 10, 11 7-12 %, N = 6, 7 even; the
     // kernels compiled for N = 4 and N = 8 stay 4-6 % ahead of it at any length.  Value 1 leaves the
-    // choice to that table.
+    // choice to these tables.
     const bool long_generic = NCT == 0 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 28;
     const bool park_pays = sizeof(T) == 4 && d >= ((int64_t)1 << 24) && (N >= 12 || long_generic);
-    const int park_kb = shape.wsum_park_kb == 1 ? (park_pays ? 128 : 0) : shape.wsum_park_kb;
+    // bf16 rows known at compile time (N = 4, 8) in streams of 2.5 GiB and more, where a fifth to a third of the
+    // traffic is output: 64 KB parked measured 4 % faster (N = 8, d = 335 M: 1.181 -> 1.133 ms; N = 4: 0.692 ->
+    // 0.665 ms), 128 KB 2 %; even at 1.6 GB, slower below; N = 2 and N = 16 lose at any length.
+    const bool long_bf16 = sizeof(T) == 2 && NCT > 0 && NCT <= 8 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 29;
+    const int park_kb = shape.wsum_park_kb == 1 ? (park_pays ? 128 : (long_bf16 ? 64 : 0)) : shape.wsum_park_kb;
     if (park_kb >= 8) {
         // output tiles parked in LDS: one workgroup of kParkBlock threads per CU (or as many as asked for,
         // sharing the LDS)
