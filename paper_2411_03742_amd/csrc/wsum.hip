@@ -409,10 +409,11 @@ static hipError_t run_as(const void *G, int N, int64_t d, int64_t dcols, const L
     const bool long_generic = NCT == 0 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 28;
     const bool park_pays = sizeof(T) == 4 && d >= ((int64_t)1 << 24) && (N >= 12 || long_generic);
     // bf16 rows known at compile time (N = 4, 8) in streams of 2.5 GiB and more, where a fifth to a third of the
-    // traffic is output: 64 KB parked measured 4 % faster (N = 8, d = 335 M: 1.181 -> 1.133 ms; N = 4: 0.692 ->
-    // 0.665 ms), 128 KB 2 %; even at 1.6 GB, slower below; N = 2 and N = 16 lose at any length.
+    // traffic is output: two or three parked tiles (32-48 KB) measured 4-6 % faster (N = 8, d = 335 M: 1.179 ->
+    // 1.109-1.119 ms, d = 200 M 0.685 -> 0.651 ms; N = 4, d = 335 M: 0.688 -> 0.657 ms), 64 KB 4 %, 128 KB 2 %;
+    // even at 1.6 GB, slower below; N = 2 and N = 16 lose at any length.
     const bool long_bf16 = sizeof(T) == 2 && NCT > 0 && NCT <= 8 && (int64_t)N * d * (int64_t)sizeof(T) >= (int64_t)5 << 29;
-    const int park_kb = shape.wsum_park_kb == 1 ? (park_pays ? 128 : (long_bf16 ? 64 : 0)) : shape.wsum_park_kb;
+    const int park_kb = shape.wsum_park_kb == 1 ? (park_pays ? 128 : (long_bf16 ? 48 : 0)) : shape.wsum_park_kb;
     if (park_kb >= 8) {
         // output tiles parked in LDS: one workgroup of kParkBlock threads per CU (or as many as asked for,
         // sharing the LDS)
