@@ -571,6 +571,28 @@ def test_error_codes_on_the_gpu(pkg):
     agg.close()
 
 
+def test_tuning_values_are_validated_and_restored(pkg):
+    """adacons_tune rejects values outside a key's documented range with ADACONS_EINVAL and leaves the
+    setting alone; a negative value restores the default (same bits as a fresh state)."""
+    N, d = 32, 4096
+    G = randG(N, d, seed=21)
+    agg, fresh = pkg.AdaCons(N, d), pkg.AdaCons(N, d)
+    for key, bad in [(pkg.ADACONS_TUNE_GRAM_BLOCKS_PER_CU, 9), (pkg.ADACONS_TUNE_WSUM_BLOCKS_PER_CU, 9),
+                     (pkg.ADACONS_TUNE_GRAM_PRODUCTS, 3), (pkg.ADACONS_TUNE_SHORT_PATH, 3),
+                     (pkg.ADACONS_TUNE_WSUM_ROW_SLICES, 3), (pkg.ADACONS_TUNE_WSUM_PARK_KB, 4),
+                     (pkg.ADACONS_TUNE_WSUM_PARK_KB, 145), (8, 0), (-1, 0)]:
+        with pytest.raises(pkg.AdaConsError) as e:
+            agg.tune(key, bad)
+        assert e.value.status == 1, (key, bad)        # ADACONS_EINVAL
+    assert torch.equal(agg.aggregate(G), fresh.aggregate(G))      # nothing was changed by the rejected calls
+    agg.tune(pkg.ADACONS_TUNE_WSUM_ROW_SLICES, 0)
+    agg.tune(pkg.ADACONS_TUNE_SHORT_PATH, 0)
+    agg.tune(pkg.ADACONS_TUNE_WSUM_ROW_SLICES, -1)
+    agg.tune(pkg.ADACONS_TUNE_SHORT_PATH, -1)
+    assert torch.equal(agg.aggregate(G), fresh.aggregate(G))      # defaults restored
+    agg.close(); fresh.close()
+
+
 def test_non_default_stream(pkg):
     N, d = 8, 500_000
     G = randG(N, d, seed=21)
