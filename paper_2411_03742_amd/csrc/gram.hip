@@ -166,6 +166,8 @@ gram_vec_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, int64_t cac
     if constexpr (U > 1)
         for (; g + (U - 1) * stride < head_end; g += U * stride) gram_vec_steps<N, T, VEC, false, U>(G, d, g, stride, acc);
     for (; g < head_end; g += stride) gram_vec_step<N, T, VEC, false>(G, d, g, acc);
+    if constexpr (U > 1)
+        for (; g + (U - 1) * stride < ngroups; g += U * stride) gram_vec_steps<N, T, VEC, true, U>(G, d, g, stride, acc);
     for (; g < ngroups; g += stride) gram_vec_step<N, T, VEC, true>(G, d, g, acc);
 
     // workgroup sum: recursive halving inside each wavefront, then the four wavefronts in order
@@ -277,17 +279,33 @@ gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, 
 
     // load j of a chunk: row 4 j + lane / 16, columns chunk * kCols + VECW (lane % 16) .. + VECW - 1
     f32x4 stage[kLoads];
-    // interior: every row exists (N = 16 NT) and the chunk lies inside d, so no clamp and no zero-fill
-    // (the address selects and zero masks cost more vector instructions than the loads themselves)
+    // interior 1: every row exists (N = 16 NT) and the chunk lies inside d, so no clamp and no zero-fill
+    // (the address selects and zero masks cost more vector instructions than the loads themselves).
+    // interior 2: the chunk lies inside d but N < 16 NT: a load instruction whose four rows all exist goes
+    // out as it is, one whose rows all lie past N is not issued at all (N is uniform, so these are scalar
+    // branches), and in the instruction that straddles N the lanes of absent rows are switched off.  Measured
+    // at d = 25.6 M fp32 with every instruction clamped and masked: N = 12 0.340 ms (N = 16: 0.265), N = 24
+    // 0.599 ms (N = 32: 0.534).
     auto load_chunk_as = [&](int64_t ch, auto stream, auto interior) __attribute__((always_inline)) {
+        constexpr int kInterior = decltype(interior)::value;
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
             const int row = 4 * j + (lane >> 4);
             const int64_t col = ch * kCols + (lane & 15) * VECW;
-            if constexpr (decltype(interior)::value) {
+            if (kInterior == 1 || (kInterior == 2 && 4 * j + 4 <= N)) {
                 const gf32x4 *src = reinterpret_cast<const gf32x4 *>(G + (int64_t)row * d + col);
                 if constexpr (decltype(stream)::value) stage[j] = __builtin_nontemporal_load(src);
                 else stage[j] = *src;
+            } else if (kInterior == 2 && 4 * j >= N) {
+                stage[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            } else if (kInterior == 2) {
+                // the instruction that straddles N: lanes of absent rows sit it out
+                stage[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (row < N) {
+                    const gf32x4 *src = reinterpret_cast<const gf32x4 *>(G + (int64_t)row * d + col);
+                    if constexpr (decltype(stream)::value) stage[j] = __builtin_nontemporal_load(src);
+                    else stage[j] = *src;
+                }
             } else {
                 const bool live = row < N && col < dcols;   // dcols is a multiple of VECW
                 const int rowc = row < N ? row : N - 1;
@@ -300,10 +318,11 @@ gram_mfma_wave_kernel(const T *__restrict__ G, int N, int64_t d, int64_t dcols, 
             }
         }
     };
-    const int64_t full_chunks = (N == kRows) ? dcols / kCols : 0;   // chunks below this index are interior
+    const int64_t full_chunks = dcols / kCols;   // chunks below this index lie inside d
     auto load_chunk = [&](int64_t ch, auto stream) __attribute__((always_inline)) {
-        if (ch < full_chunks) load_chunk_as(ch, stream, std::true_type{});
-        else load_chunk_as(ch, stream, std::false_type{});
+        if (ch >= full_chunks) load_chunk_as(ch, stream, std::integral_constant<int, 0>{});
+        else if (N == kRows) load_chunk_as(ch, stream, std::integral_constant<int, 1>{});
+        else load_chunk_as(ch, stream, std::integral_constant<int, 2>{});
     };
 
     const int64_t wstride = (int64_t)gridDim.x * (kBlock / kWave);
@@ -642,6 +661,11 @@ static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchS
     // measured best: one workgroup per CU for fp32, two for bf16 (twice the FMAs per byte)
     const int grid = grid_for((ngroups + kBlock - 1) / kBlock, shape, occ, sizeof(T) == 2 ? 2 : 1);
     *grid_out = grid;
+    // Streams: few rows put few loads in flight (N per thread and sweep), so U sweeps are requested together until
+    // a thread has about eight outstanding.  Measured, A1 at d = 25.6 M fp32, U = 1 -> U below: N = 1 50 -> 22 us,
+    // N = 2 61 -> 36, N = 3 69 -> 51, N = 4 78 -> 67 us; bf16 (two workgroups per CU): N = 1 19 -> 13, N = 2
+    // 23 -> 21 us, N >= 3 no gain.  Same sums in the same order for any U.
+    constexpr int U_stream = (sizeof(T) == 4) ? (N <= 2 ? 4 : (N <= 4 ? 2 : 1)) : (N == 1 ? 4 : (N == 2 ? 2 : 1));
     if (shape.short_path) {
         // same grid, same columns per thread, same order of the sums as the kernel below: K comes out bit for
         // bit the same; everything with ordinary loads (stage A3 finds G in the caches)
@@ -652,7 +676,7 @@ static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchS
         if ((int64_t)N * dcols * (int64_t)sizeof(T) > ((int64_t)32 << 20) && shape.cached_head_mb >= 0)
             head = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
         if (head < ngroups) {
-            hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, 1>), dim3(grid), dim3(kBlock), 0, s,
+            hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, U_stream>), dim3(grid), dim3(kBlock), 0, s,
                                static_cast<const T *>(G), d, ngroups, head, partials, ds);
             return hipGetLastError();
         }
@@ -664,7 +688,7 @@ static hipError_t run_vec(const void *G, int64_t d, int64_t dcols, const LaunchS
     int64_t cached_groups = ngroups;
     if (shape.cached_head_mb >= 0)
         cached_groups = ((int64_t)shape.cached_head_mb << 20) / ((int64_t)N * VEC * (int64_t)sizeof(T));
-    hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, 1>), dim3(grid), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL((gram_vec_kernel<N, T, VEC, U_stream>), dim3(grid), dim3(kBlock), 0, s,
                        static_cast<const T *>(G), d, ngroups, cached_groups, partials, static_cast<DevState *>(nullptr));
     return hipGetLastError();
 }

@@ -474,7 +474,12 @@ static hipError_t dispatch(const void *G, int N, int64_t d, int64_t dcols, const
         case 4: return run<4, T, VEC, UNR>(G, N, d, dcols, shape, gamma, out, m, s);
         case 8: return run<8, T, VEC, UNR>(G, N, d, dcols, shape, gamma, out, m, s);
         case 16: return run<16, T, VEC, 1>(G, N, d, dcols, shape, gamma, out, m, s);  // 16 loads in flight already
-        default: return run<0, T, VEC, UNR>(G, N, d, dcols, shape, gamma, out, m, s);
+        default:
+            // rows walked eight at a time: a second tile per thread doubles the staged values, which for bf16 inputs
+            // (eight widened columns per load) are 128 registers and leave two wavefronts per SIMD.  Measured at
+            // d = 25.6 M, bf16, two tiles -> one: N = 64 0.92 -> 0.60 ms, N = 32 0.46 -> 0.30, N = 12 0.172 -> 0.116,
+            // N = 6 0.093 -> 0.068 ms; fp32 inputs keep two (N = 6 0.111 against 0.119 ms with one).
+            return run<0, T, VEC, (sizeof(T) == 2) ? 1 : UNR>(G, N, d, dcols, shape, gamma, out, m, s);
     }
 }
 
