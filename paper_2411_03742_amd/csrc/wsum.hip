@@ -15,22 +15,36 @@ constexpr int kRowsInFlight = 8;
 constexpr int kParkBlock = kBlock;   // workgroup size of wsum_parked_kernel (512 measured 3-8 % slower)
 
 // APPLY = false: out[col..] = acc (non-temporal).  APPLY = true: the descent step of Eq. 4 in
-// place, out[col..] = out[col..] - lr * acc (out is then the parameter vector w: read and written
-// with ordinary accesses, it is needed again next step).
+// place, out[col..] = out[col..] - lr * acc (out is then the parameter vector w).  w streams past the
+// caches like everything else here: read and written with ordinary accesses it pushed the head of G, which
+// stage A1 left for this pass, out of the memory-side cache, and the fused step cost 52-95 us on top of the
+// plain aggregation at d = 25.6 M (N = 16, 64) where the extra 102 MB read is worth 16; streamed, 14 us.
+// wv: the VEC values of w, requested by the caller together with the rows of G (APPLY only; read at the
+// time of the store they would add a memory latency to every tile).
 template <int VEC, bool APPLY>
-__device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, const float (&acc)[VEC], float lr) {
+__device__ __forceinline__ void store_out(float *__restrict__ out, int64_t col, const float (&acc)[VEC], float lr,
+                                          const float (&wv)[VEC]) {
 #pragma unroll
     for (int c = 0; c < VEC; c += 4) {
         gf32x4 *dst = reinterpret_cast<gf32x4 *>(out + col + c);
         if constexpr (APPLY) {
-            const f32x4 w = *dst;
-            const f32x4 x = {fmaf(-lr, acc[c], w.x), fmaf(-lr, acc[c + 1], w.y), fmaf(-lr, acc[c + 2], w.z),
-                             fmaf(-lr, acc[c + 3], w.w)};
-            *dst = x;
+            const f32x4 x = {fmaf(-lr, acc[c], wv[c]), fmaf(-lr, acc[c + 1], wv[c + 1]), fmaf(-lr, acc[c + 2], wv[c + 2]),
+                             fmaf(-lr, acc[c + 3], wv[c + 3])};
+            __builtin_nontemporal_store(x, dst);
         } else {
             const f32x4 x = {acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
             __builtin_nontemporal_store(x, dst);
         }
+    }
+}
+
+// The updated parameters on the short path (a few megabytes: they stay in the caches for the next step): ordinary stores.
+template <int VEC>
+__device__ __forceinline__ void store_params(float *__restrict__ w, int64_t col, const float (&x)[VEC]) {
+#pragma unroll
+    for (int c = 0; c < VEC; c += 4) {
+        const f32x4 y = {x[c], x[c + 1], x[c + 2], x[c + 3]};
+        *reinterpret_cast<gf32x4 *>(w + col + c) = y;
     }
 }
 
@@ -65,12 +79,22 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
                                           const int64_t base, const float *gam, float *__restrict__ out, float lr,
                                           float *park = nullptr) {
     float acc[UNR][VEC];
+    float wv[UNR][VEC];   // APPLY, stored directly: the parameters this tile updates, requested ahead of the rows
     bool live[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
         live[u] = FULL || (base + (int64_t)u * BLK < ngroups);
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc[u][c] = 0.f;
+        if constexpr (APPLY && !PARK) {
+            if (live[u]) {
+#pragma unroll
+                for (int c = 0; c < VEC; c += 4) {
+                    const f32x4 w4 = __builtin_nontemporal_load(reinterpret_cast<const gf32x4 *>(out + (base + (int64_t)u * BLK) * VEC + c));
+                    wv[u][c] = w4.x, wv[u][c + 1] = w4.y, wv[u][c + 2] = w4.z, wv[u][c + 3] = w4.w;
+                }
+            }
+        }
     }
 #pragma clang loop unroll_count(NCT > 0 ? (NCT + kRowsInFlight - 1) / kRowsInFlight : 1)
     for (int i0 = 0; i0 < N; i0 += kRowsInFlight) {
@@ -107,7 +131,7 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
     } else {
 #pragma unroll
         for (int u = 0; u < UNR; ++u)
-            if (live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * BLK) * VEC, acc[u], lr);
+            if (live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * BLK) * VEC, acc[u], lr, wv[u]);
     }
 }
 
@@ -117,7 +141,7 @@ __device__ __forceinline__ void wsum_tile(const T *__restrict__ G, const int N, 
 // compile time, sixteen 128-bit loads per thread.  The launcher asks for eight workgroups per CU; at 72
 // registers only seven are resident, and the pass measured 7 % slower (N = 8, d = 25.6 M: 148 against 138 us).
 template <int NCT, typename T, int UNR, bool APPLY>
-constexpr int wsum_min_waves() { return (sizeof(T) == 4 && NCT > 0 && NCT * UNR <= 16 && !APPLY) ? 8 : 1; }
+constexpr int wsum_min_waves() { return (sizeof(T) == 4 && NCT > 0 && NCT * UNR <= 16) ? (APPLY ? 5 : 8) : 1; }
 
 template <int NCT, typename T, int VEC, int UNR, bool APPLY>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(wsum_min_waves<NCT, T, UNR, APPLY>(), 8)))
@@ -186,21 +210,45 @@ wsum_parked_kernel(const T *__restrict__ G, int n_rt, int64_t d, int64_t ngroups
     // parked tiles are the q_first-th, ... of this workgroup: written out when `cap` of them are waiting
     auto flush = [&](int64_t q_first, int n) __attribute__((always_inline)) {
         __syncthreads();   // the images are complete
-        for (int k = 0; k < n; ++k) {
-            const int64_t tt = tile_of(q_first + k);
-            float *dst = out + tt * kTileCols;
-            const float *src = park + (size_t)k * kTileCols;
+        constexpr int kPieces = kTileCols / 4 / BLK;   // 128-bit pieces per thread and tile
+        if constexpr (APPLY) {
+            // the parameters of four tiles are requested together, then updated and written: one memory latency
+            // per four tiles, not one per tile
+            constexpr int kAhead = 4;
+            for (int k0 = 0; k0 < n; k0 += kAhead) {
+                f32x4 w[kAhead][kPieces];
 #pragma unroll
-            for (int q = 0; q < kTileCols / 4 / BLK; ++q) {
-                const int e = (q * BLK + (int)threadIdx.x) * 4;   // 1 KB per wavefront and instruction
-                const f32x4 x = *reinterpret_cast<const f32x4 *>(src + e);
-                gf32x4 *p = reinterpret_cast<gf32x4 *>(dst + e);
-                if constexpr (APPLY) {
-                    const f32x4 w = *p;
-                    const f32x4 y = {fmaf(-lr, x.x, w.x), fmaf(-lr, x.y, w.y), fmaf(-lr, x.z, w.z), fmaf(-lr, x.w, w.w)};
-                    *p = y;
-                } else {
-                    __builtin_nontemporal_store(x, p);
+                for (int a = 0; a < kAhead; ++a)
+                    if (k0 + a < n) {
+                        const float *dst = out + tile_of(q_first + k0 + a) * kTileCols;
+#pragma unroll
+                        for (int q = 0; q < kPieces; ++q)
+                            w[a][q] = __builtin_nontemporal_load(reinterpret_cast<const gf32x4 *>(dst + (q * BLK + (int)threadIdx.x) * 4));
+                    }
+#pragma unroll
+                for (int a = 0; a < kAhead; ++a)
+                    if (k0 + a < n) {
+                        float *dst = out + tile_of(q_first + k0 + a) * kTileCols;
+                        const float *src = park + (size_t)(k0 + a) * kTileCols;
+#pragma unroll
+                        for (int q = 0; q < kPieces; ++q) {
+                            const int e = (q * BLK + (int)threadIdx.x) * 4;
+                            const f32x4 x = *reinterpret_cast<const f32x4 *>(src + e);
+                            const f32x4 y = {fmaf(-lr, x.x, w[a][q].x), fmaf(-lr, x.y, w[a][q].y), fmaf(-lr, x.z, w[a][q].z),
+                                             fmaf(-lr, x.w, w[a][q].w)};
+                            __builtin_nontemporal_store(y, reinterpret_cast<gf32x4 *>(dst + e));
+                        }
+                    }
+            }
+        } else {
+            for (int k = 0; k < n; ++k) {
+                float *dst = out + tile_of(q_first + k) * kTileCols;
+                const float *src = park + (size_t)k * kTileCols;
+#pragma unroll
+                for (int q = 0; q < kPieces; ++q) {
+                    const int e = (q * BLK + (int)threadIdx.x) * 4;   // 1 KB per wavefront and instruction
+                    const f32x4 x = *reinterpret_cast<const f32x4 *>(src + e);
+                    __builtin_nontemporal_store(x, reinterpret_cast<gf32x4 *>(dst + e));
                 }
             }
         }
@@ -508,6 +556,7 @@ wsum_short_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, const dou
     const int slot = (grid % 8) ? b : (b % 8) * (grid / 8) + b / 8;   // XCD-contiguous tiles, as in wsum_kernel
 
     float v[UNR][N][VEC];
+    float wv[UNR][VEC];   // APPLY: the parameters the tile updates, requested with its rows
     bool live[UNR];
     auto load_tile = [&](int64_t t) __attribute__((always_inline)) {
 #pragma unroll
@@ -517,6 +566,13 @@ wsum_short_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, const dou
             const int64_t gc = live[u] ? grp : ngroups - 1;   // clamped: in bounds, the sums are not stored
 #pragma unroll
             for (int i = 0; i < N; ++i) load_vec<T, VEC, true>(G + (int64_t)i * d + gc * VEC, v[u][i]);
+            if constexpr (APPLY) {
+#pragma unroll
+                for (int c = 0; c < VEC; c += 4) {
+                    const f32x4 w4 = *reinterpret_cast<const gf32x4 *>(out + gc * VEC + c);
+                    wv[u][c] = w4.x, wv[u][c + 1] = w4.y, wv[u][c + 2] = w4.z, wv[u][c + 3] = w4.w;
+                }
+            }
         }
     };
     int64_t t = slot;
@@ -554,6 +610,12 @@ wsum_short_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, const dou
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(w[i], v[u][i][c], acc[u][c]);
         }
+        if constexpr (APPLY) {   // the step itself, before the next tile's loads reuse wv
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[u][c] = fmaf(-lr, acc[u][c], wv[u][c]);
+        }
         const int64_t base = t * kTile + threadIdx.x;
         bool was_live[UNR];
 #pragma unroll
@@ -562,7 +624,10 @@ wsum_short_kernel(const T *__restrict__ G, int64_t d, int64_t ngroups, const dou
         if (t < ntiles) load_tile(t);   // the next tile's loads before this tile's stores
 #pragma unroll
         for (int u = 0; u < UNR; ++u)
-            if (was_live[u]) store_out<VEC, APPLY>(out, (base + (int64_t)u * kBlock) * VEC, acc[u], lr);
+            if (was_live[u]) {
+                if constexpr (APPLY) store_params<VEC>(out, (base + (int64_t)u * kBlock) * VEC, acc[u]);
+                else store_out<VEC, false>(out, (base + (int64_t)u * kBlock) * VEC, acc[u], lr, acc[u]);
+            }
     }
 }
 
