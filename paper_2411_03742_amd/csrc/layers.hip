@@ -731,7 +731,10 @@ adacons_status adacons_init_layers(adacons_layers **out_ls, int N, int L, const 
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return lfail(ADACONS_EUNSUPPORTED, "built for gfx950 only");
 
     const int vec = dtype == ADACONS_BF16 ? 8 : 4;
-    const int grid_target = prop.multiProcessorCount * 2;   // measured (ResNet-50 layout): 144 us at two workgroups per CU, 152 at one, 155 at three
+    // measured (ResNet-50 layout, N = 8): 144 us at two workgroups per CU, 152 at one, 155 at three; with few
+    // rows a thread has few loads in flight (N per column group), and more workgroups make up for it
+    const int per_cu = N <= 2 ? 8 : (N <= 4 ? 4 : 2);
+    const int grid_target = prop.multiProcessorCount * per_cu;
     const int run_groups = choose_run_groups(offsets_host, L, vec, grid_target);
     // runs: per layer, the groups that contain any of its columns, cut into pieces of run_groups
     std::vector<LayerRun> runs;
