@@ -232,7 +232,8 @@ typedef enum {
                                             many KB of LDS */
     ADACONS_TUNE_SHORT_PATH = 6,         /* two launches instead of three (16-byte aligned rows): stage A3 adds stage
                                             A1's partial sums and runs stage A2 itself (same results, bit for bit).
-                                            0: never; 1 (default): N <= 8 with at most 32 MiB of gradients, which
+                                            0: never; 1 (default): N <= 8 with at most 32 MiB of gradients (bf16: 16 MiB
+                                            for 2 < N <= 6, 8 MiB for N = 7, 8), which
                                             stay in the caches between the passes and are bound by launches, not
                                             bytes, and N > 8 with at most 1 MiB where stage A3 runs by row slices
                                             (not for 44 < N <= 64 with the full matrix K); 2: also N <= 8 at any

@@ -176,7 +176,16 @@ hipError_t launch_first_pass(adacons_state *st, const void *G, int N, int64_t d,
 bool takes_short_path(const adacons_state *st, int N, int64_t d, adacons_dtype dtype, bool vec_ok) {
     const int mode = st->tune[ADACONS_TUNE_SHORT_PATH];
     if (mode == 0 || !vec_ok) return false;
-    if (N <= 8) return mode == 2 || (int64_t)N * d * (int64_t)elem_size(dtype) <= kShortPathBytes;
+    if (N <= 8) {
+        // Measured crossovers (two launches against three, whole step): fp32 wins up to 32 MiB for every N <= 8
+        // (N = 8: -7 % at 32 MiB, +7 % at 64; N = 2 still -8 % at 128 MiB); bf16 rows hold twice the columns per
+        // byte and stage A3 keeps them widened in registers, so its limit is lower: N <= 2 32 MiB (-5 %, +9 % at
+        // 64), N <= 6 16 MiB (N = 4: -14 % at 16, +6 % at 32), N = 7, 8 8 MiB (N = 8: -6 % at 8, +10 % at 16,
+        // +31 % at 32).
+        int64_t limit = kShortPathBytes;
+        if (dtype == ADACONS_BF16 && N > 2) limit = (N <= 6) ? kShortPathBytes / 2 : kShortPathBytes / 4;
+        return mode == 2 || (int64_t)N * d * (int64_t)elem_size(dtype) <= limit;
+    }
     return many_workers_short_gradients(st, N, d, dtype);
 }
 

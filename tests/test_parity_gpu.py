@@ -354,20 +354,26 @@ def short_against_plain(pkg, N, d, dtype, flags, stats_only):
 
 
 def test_short_path_is_the_default_for_small_gradients_only(pkg):
-    """Up to 32 MiB of gradients (N <= 8, aligned rows) take two launches, larger ones three; N > 8 up to 1 MiB,
-    unless the Gram matrix takes more than one workgroup to reduce (44 < N <= 64): seen through the per-stage
-    timing, which reports no time of its own for stage A2 on the short path."""
-    for N, d, short in [(4, 1 << 20, True), (8, 1 << 20, True), (8, (1 << 20) + 4, False), (4, 1001, False),
-                        (16, 1000, True), (16, 16388, False), (9, 1000, True), (32, 1000, True), (32, 8192, True), (32, 8196, False), (48, 1000, False),
-                        (128, 1000, True)]:
+    """Up to 32 MiB of gradients (N <= 8, aligned rows; bf16: 16 MiB for 2 < N <= 6, 8 MiB for N = 7, 8) take two
+    launches, larger ones three; N > 8 up to 1 MiB, unless the Gram matrix takes more than one workgroup to
+    reduce (44 < N <= 64): seen through the per-stage timing, which reports no time of its own for stage A2
+    on the short path."""
+    f32, bf16 = torch.float32, torch.bfloat16
+    for N, d, dtype, short in [(4, 1 << 20, f32, True), (8, 1 << 20, f32, True), (8, (1 << 20) + 4, f32, False),
+                               (4, 1001, f32, False), (2, 1 << 23, bf16, True), (2, (1 << 23) + 8, bf16, False),
+                               (4, 1 << 21, bf16, True), (4, (1 << 21) + 8, bf16, False), (6, 1 << 20, bf16, True),
+                               (8, 1 << 19, bf16, True), (8, (1 << 19) + 8, bf16, False), (7, 1 << 20, bf16, False),
+                               (16, 1000, f32, True), (16, 16388, f32, False), (9, 1000, f32, True),
+                               (32, 1000, f32, True), (32, 8192, f32, True), (32, 8196, f32, False),
+                               (48, 1000, f32, False), (128, 1000, f32, True)]:
         agg = pkg.AdaCons(N, d)
-        G = randG(N, d, seed=1)
+        G = randG(N, d, dtype, seed=1)
         agg.aggregate(G)
         agg.profile_begin(20)
         for _ in range(20):
             agg.aggregate(G)
         prof = agg.profile_end()
-        assert (prof["coeff_ms"] == 0.0) == short, (N, d, prof)
+        assert (prof["coeff_ms"] == 0.0) == short, (N, d, dtype, prof)
         agg.close()
 
 
