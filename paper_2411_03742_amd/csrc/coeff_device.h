@@ -8,7 +8,7 @@
 
 namespace adacons {
 
-// Stage A2.  One workgroup (at least N threads, lds of 3 N doubles); thread i < N is worker i.  fp64 throughout.
+// Stage A2.  One workgroup (at least max(N, 16) threads, lds of 3 N doubles); thread i < N is worker i.  fp64 throughout.
 //   q_i = K_ii, r_i = sum_j K_ij                      (||g_i||^2 and N <g_i, gbar>)
 //   a_i = r_i / (N sqrt(q_i))                          Eq. 7, positive for a descent direction
 //   rank_i = #{j : a_j < a_i or (a_j = a_i and j < i)} ascending, ties to the lower index
@@ -97,11 +97,26 @@ __device__ inline void update_coefficients_from_stats(double q, double r, DevSta
             c_sh[tid] = (cp.flags & ADACONS_FLAG_LAMBDA_EQ13) ? as : c;
         }
         __syncthreads();
-        if (tid == 0) {
+        // sum c and sum |c| in a fixed order: sixteen interleaved sub-sums (elements t, t + 16, ...), then the
+        // sub-sums in order -- for N <= 16 that is the plain index order; a single thread walking 128 entries
+        // took about a microsecond of every launch that ends in this update
+        __shared__ double s_part[2][16];
+        if (tid < 16) {
             double s = 0.0, sabs = 0.0;
-            for (int i = 0; i < N; ++i) {
+            for (int i = tid; i < N; i += 16) {
                 s += c_sh[i];
                 sabs += fabs(c_sh[i]);
+            }
+            s_part[0][tid] = s;
+            s_part[1][tid] = sabs;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double s = 0.0, sabs = 0.0;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                s += s_part[0][t];
+                sabs += s_part[1][t];
             }
             s_sum = s;
             s_abs = sabs;

@@ -55,6 +55,11 @@ C3 = Workload("C3-bertlarge-bf16", 8, 335_141_888, "bf16", 1, 2.0, "block_scaled
 C4 = Workload("C4-many-workers", 64, 25_557_032, "f32", 10, 3.0, "plain")
 C5 = Workload("C5-robustness", 16, 124_439_808, "f32", 100, 1.0, "outlier_shuffled")
 CONFIGS = {"C1": C1, "C2": C2, "C3": C3, "C4": C4, "C5": C5}
+# Beside them: the shape of the paper's stochastic linear-regression example (Eq. 14: d = 1000, up to 128
+# workers) -- many workers with few parameters each, bound by launches.  Not one of the five configurations;
+# bench.py takes it as --workload E14 so that the figures quoted for this regime have a command behind them.
+E14 = Workload("E14-many-workers-short-gradients", 128, 1000, "f32", 25, 1.0, "plain")
+EXTRA = {"E14": E14}
 
 
 def _gen(device, seed: int) -> torch.Generator:
