@@ -868,3 +868,43 @@ def test_aggregate_can_be_captured_in_a_hip_graph(pkg, N, d, park_kb):
     _, step = agg.export_state()
     assert step == 5
     agg.close()
+
+
+# ------------------------------------------------------------------- randomized sweep ----
+def test_randomized_shapes_flags_and_tunings(pkg):
+    """A seeded sweep over what the other tests fix one at a time: worker count (all kernel families and
+    their boundaries), length, dtype, ablation flags, base alignment, and every tuning key that selects a
+    kernel (statistics-only, row slices, short path, Gram products), three steps with the state carried,
+    the last one sometimes as the fused descent step.  Every step is checked like any other."""
+    rng = np.random.default_rng(20241103)
+    Ns = [1, 2, 3, 4, 5, 7, 8, 9, 12, 15, 16, 17, 24, 31, 32, 33, 44, 45, 48, 63, 64, 65, 96, 127, 128]
+    for case in range(120):
+        N = int(rng.choice(Ns))
+        d = int(np.exp(rng.uniform(np.log(600), np.log(300_000 if N <= 32 else 50_000))))
+        dtype = torch.float32 if rng.random() < 0.5 else torch.bfloat16
+        flags = int(rng.choice([0, 1, 2, 3, 3, 3, 7, 11, 15]))
+        shift = int(rng.integers(1, 8)) if rng.random() < 0.3 else 0
+        tunes = [(pkg.ADACONS_TUNE_STATS_ONLY, int(rng.random() < 0.3)), (pkg.ADACONS_TUNE_WSUM_ROW_SLICES, int(rng.choice([0, 1, 1, 2]))),
+                 (pkg.ADACONS_TUNE_SHORT_PATH, int(rng.choice([0, 1, 1, 2]))), (pkg.ADACONS_TUNE_GRAM_PRODUCTS, int(rng.choice([0, 1, 2])))]
+        apply_last = rng.random() < 0.5
+        what = (case, N, d, dtype, flags, shift, tunes, apply_last)
+        agg = pkg.AdaCons(N, d, beta=0.9, flags=flags)
+        for key, value in tunes:
+            agg.tune(key, value)
+        ost = o.OracleState(N, beta=0.9, flags=flags)
+        for t in range(3):
+            G = shifted_rows(N, d, dtype, shift, seed=1000 * case + t)
+            if apply_last and t == 2:
+                w = torch.randn(d, device=DEV)
+                w0 = w.cpu().numpy()
+                state_was_zero = not ost.m.any()
+                agg.aggregate_apply(G, w, lr=0.125)
+                info = agg.coeffs()
+                Gh = workloads.to_oracle_input(G)
+                _, oinfo = o.aggregate(Gh, ost, want_out=False)
+                assert check_coefficients(info, oinfo, ost.m, ost.flags, state_was_zero), what
+                assert_out_elementwise(w.cpu().numpy(), Gh, info["gamma"], base=w0, lr=0.125)
+            else:
+                _, _, oinfo = both(pkg, G, agg, ost)
+                assert oinfo["strict"], what
+        agg.close()
