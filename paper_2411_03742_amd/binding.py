@@ -18,7 +18,7 @@ from . import build as _build
 ADACONS_N_MAX = 128
 ADACONS_GRAM_N_MAX = 64
 ADACONS_F32, ADACONS_BF16 = 0, 1
-ADACONS_OK = 0
+ADACONS_OK, ADACONS_EINVAL, ADACONS_EUNSUPPORTED, ADACONS_EALIGN, ADACONS_EHIP, ADACONS_ENOMEM = 0, 1, 2, 3, 4, 5
 ADACONS_FLAG_MOMENTUM, ADACONS_FLAG_NORMALIZE, ADACONS_FLAG_DEFAULT = 1, 2, 3
 ADACONS_FLAG_INDEX_EMA, ADACONS_FLAG_LAMBDA_EQ13 = 4, 8
 ADACONS_NUM_ZERO_NORM, ADACONS_NUM_NONFINITE, ADACONS_NUM_UNIFORM_FALLBACK = 1, 2, 4

@@ -125,3 +125,21 @@ def test_noalloc_entry_point_rejects_sizes_beyond_its_maximum_before_touching_a_
     assert cdll.adacons_aggregate_noalloc(None, 4, 10, 0, 1.5, 3, 8, None, None, 16, None) == EINVAL
     assert cdll.adacons_aggregate_noalloc(None, 4, 10, 0, 0.9, 3, None, None, None, 16, None) == EINVAL
     assert cdll.adacons_aggregate_noalloc(None, 4, 10, 0, 0.9, 3, 12, None, None, 16, None) == EALIGN
+
+
+def test_binding_constants_equal_the_header(lib):
+    """Every enumerator and flag the header defines with a value (status codes, dtypes, flags, numeric
+    flags, tuning keys, limits) has the same value under the same name in the Python binding."""
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    found = {}
+    for name, value in re.findall(r"\b(ADACONS_[A-Z0-9_]+)\s*=\s*(0x[0-9a-fA-F]+|\d+)u?\b", text):
+        found[name] = int(value, 0)
+    for name, value in re.findall(r"#define\s+(ADACONS_[A-Z0-9_]+)\s+(0x[0-9a-fA-F]+|\d+)u?\b", text):
+        found[name] = int(value, 0)
+    assert len(found) >= 20, found
+    missing = [n for n in found if not n.endswith("_") and not hasattr(lib, n)]
+    assert not missing, missing
+    for name, value in found.items():
+        if hasattr(lib, name):
+            assert getattr(lib, name) == value, (name, getattr(lib, name), value)
